@@ -1,0 +1,153 @@
+/*
+ * ps.h -- C ABI of the MI355X (gfx950) engine-step library.
+ *
+ * What is computed: one attention layer over the mixed batch that the SlideBatching local
+ * scheduler forms each iteration (Alg. 1: prefill chunks of l_q tokens over a cached prefix
+ * plus single-token decode requests of several priority classes), read through per-request
+ * block lists from a paged KV cache, and the KV-block copies behind asynchronous offload and
+ * budgeted, pipelined reload (Sec. 4.3; stream/event structure of Appendix B).
+ *
+ * Conventions for every function
+ *   - returns PS_OK (0) or a negative ps_status; never throws, never aborts.
+ *   - never blocks the host on the GPU unless its name says "wait" (exception: a call may
+ *     wait for one of the library's own small staging buffers to become reusable).
+ *   - ps_last_error() gives a thread-local text for the last failure on this thread.
+ *   - pointers marked HOST are ordinary host memory, borrowed only for the duration of the
+ *     call; DEVICE pointers are HIP device memory owned by the caller; PINNED pointers are
+ *     page-locked host memory (hipHostMalloc) that the GPU can address directly.
+ *   - bf16 values are 16-bit patterns (upper half of an IEEE binary32).
+ *
+ * KV cache layout (device, bf16), chosen so that both attention contractions read their
+ * operands as contiguous 16-byte runs:
+ *     cache[b][0][g][t][x]   K of block b, kv-head g, token slot t (0..15), dim x   (token-major)
+ *     cache[b][1][g][x][t]   V of block b, kv-head g, dim x, token slot t           (dim-major)
+ *   i.e. element offsets, with blk = block_tokens and d = head_dim:
+ *     K: (((b*2 + 0)*Hkv + g)*blk + t)*d + x        V: (((b*2 + 1)*Hkv + g)*d + x)*blk + t
+ *   One block is one contiguous run of 2*Hkv*blk*d*2 bytes (64 KiB at Hkv = 8); a swap moves
+ *   whole runs, so the host copy of a block has the same internal layout.
+ *   Token j of a request lives in block  block_ids[bt_start[r] + j / blk], slot j % blk.
+ *   Slots past kv_len and blocks no table references may hold anything (NaN included); they
+ *   never influence an output.
+ */
+#ifndef PS_H_
+#define PS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PS_OK = 0,
+  PS_EINVAL = -1, /* bad argument / inconsistent batch description            */
+  PS_ENOMEM = -2, /* workspace too small, or a host allocation failed         */
+  PS_EHIP = -3,   /* a HIP call failed; ps_last_error() holds its text        */
+  PS_ESTATE = -4, /* unknown ticket                                            */
+  PS_EBUSY = -5   /* ticket still in flight (ps_ticket_query only)             */
+} ps_status;
+
+enum { PS_BF16 = 0, PS_F32 = 1 };
+
+typedef struct ps_ctx ps_ctx;
+
+/* Fixed per layer. */
+typedef struct {
+  int32_t n_q_heads;       /* Hq                                                          */
+  int32_t n_kv_heads;      /* Hkv; Hq % Hkv == 0, group G = Hq/Hkv in 1..16               */
+  int32_t head_dim;        /* must be 128                                                 */
+  int32_t block_tokens;    /* must be 16                                                  */
+  int32_t n_device_blocks; /* M: blocks in the device pool                                */
+  int32_t n_host_blocks;   /* slots in the pinned host pool (0 if swaps are not used)     */
+  float softmax_scale;     /* 0 => 1/sqrt(head_dim)                                       */
+  int32_t out_dtype;       /* PS_BF16 (default) or PS_F32                                 */
+  int32_t decode_chunk;    /* KV tokens per split-K partition; 0 => library picks; else a
+                              multiple of 32 in [32, 65536]                               */
+  int32_t swap_workgroups; /* workgroups used by a swap kernel; 0 => library picks        */
+} ps_layer_cfg;
+
+/* One mixed batch (the output of Alg. 1 as the attention layer sees it). HOST arrays. */
+typedef struct {
+  int32_t n_req;
+  int32_t n_tokens;         /* == q_start[n_req]                                           */
+  const int32_t* q_start;   /* [n_req+1] prefix sum of l_q; l_q == 1 is a decode token,
+                               l_q > 1 a prefill chunk                                     */
+  const int32_t* kv_len;    /* [n_req] cached length INCLUDING this step's l_q tokens      */
+  const int32_t* bt_start;  /* [n_req+1] CSR offsets into block_ids;
+                               bt_start[r+1]-bt_start[r] == ceil(kv_len[r]/block_tokens)   */
+  const int32_t* block_ids; /* physical device block ids, logical order                   */
+  const uint8_t* prio;      /* [n_req] priority class, may be NULL; carried, not used      */
+} ps_batch;
+
+/* GPU time of the phases of the last profiled ps_step, in milliseconds (0 if not run). */
+typedef struct {
+  float upload_ms, append_ms, decode_ms, merge_ms, prefill_ms, total_ms;
+} ps_step_times;
+
+const char* ps_last_error(void);
+
+/* Creates a context on the current HIP device. The context owns only small pinned staging
+ * buffers, events and a few KB of device memory. PS_EINVAL on a bad cfg. */
+int ps_create(const ps_layer_cfg* cfg, ps_ctx** out);
+void ps_destroy(ps_ctx* ctx);
+
+/* Device workspace needed by ps_step for any batch with n_req <= max_req,
+ * n_tokens <= max_tokens and at most max_table_entries block-table entries. */
+int ps_workspace_bytes(const ps_ctx* ctx, int32_t max_req, int32_t max_tokens,
+                       int64_t max_table_entries, size_t* out_bytes);
+
+/* One mixed-batch attention layer (Sec. 4.1 describes the batch; the attention is causal
+ * softmax attention: query token i of request r, at absolute position p+i with
+ * p = kv_len - l_q, attends cached tokens 0..p+i of kv-head h/G, scale softmax_scale).
+ *   q        DEVICE bf16 [n_tokens][Hq][d]
+ *   k_new,
+ *   v_new    DEVICE bf16 [n_tokens][Hkv][d], this step's new K/V rows, written into the cache
+ *            at positions p..kv_len-1 of each request before attention; both NULL if the
+ *            cache already holds them
+ *   kv_cache DEVICE, layout above, n_device_blocks blocks
+ *   out      DEVICE [n_tokens][Hq][d], bf16 or f32 per cfg.out_dtype
+ *   workspace DEVICE, 256-byte aligned, at least ps_workspace_bytes(...) bytes; its contents
+ *            are scratch and may be reused by the next call on the same stream
+ *   hip_stream  hipStream_t (NULL = default stream); all work is enqueued there
+ *   wait_ticket 0, or a ticket from ps_swap_in/ps_swap_out: the stream waits for that copy
+ *            to complete before any kernel of this step runs (Appendix B: compute
+ *            synchronises on the reload's event only just before it needs the blocks)
+ * Validation is host-side, O(batch description): PS_EINVAL for NULL pointers, non-monotone
+ * q_start / bt_start, l_q < 1, l_q > kv_len, wrong table length, block id outside [0, M),
+ * k_new given without v_new; PS_ENOMEM if the workspace is too small. n_req == 0 is a
+ * successful no-op. Nothing is enqueued if validation fails. */
+int ps_step(ps_ctx* ctx, const ps_batch* batch, const void* q, const void* k_new,
+            const void* v_new, void* kv_cache, void* out, void* workspace,
+            size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket);
+
+/* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds). */
+int ps_set_profiling(ps_ctx* ctx, int enabled);
+/* Blocks until the last profiled step has finished, then fills *out. */
+int ps_get_step_times(ps_ctx* ctx, ps_step_times* out);
+
+/* Asynchronous offload (Sec. 4.3): host_pool[host_slot_ids[k]] <- cache[dev_block_ids[k]] for
+ * the first min(n, copy_budget) entries, in list order (copy_budget < 0: unlimited), enqueued
+ * on side_stream. *n_done gets that count, *ticket a completion handle (0 if nothing moved).
+ * The device blocks may be reused only after the ticket completes.
+ *   dev_block_ids, host_slot_ids  HOST int32 [n]
+ *   kv_cache DEVICE; host_pool PINNED, n_host_blocks slots of one block each
+ * PS_EINVAL: id outside its pool, duplicate id within a list, NULL pointer with n > 0. */
+int ps_swap_out(ps_ctx* ctx, const int32_t* dev_block_ids, const int32_t* host_slot_ids,
+                int32_t n, int32_t copy_budget, const void* kv_cache, void* host_pool,
+                void* side_stream, int32_t* n_done, uint64_t* ticket);
+
+/* Pipelined reload (Sec. 4.3): cache[dev_block_ids[k]] <- host_pool[host_slot_ids[k]], same
+ * rules as ps_swap_out; copy_budget is B_copy of the adaptive copy-budget control. Pass the
+ * ticket to ps_step so that attention starts only after the blocks have landed. */
+int ps_swap_in(ps_ctx* ctx, const int32_t* host_slot_ids, const int32_t* dev_block_ids,
+               int32_t n, int32_t copy_budget, const void* host_pool, void* kv_cache,
+               void* side_stream, int32_t* n_done, uint64_t* ticket);
+
+int ps_ticket_query(ps_ctx* ctx, uint64_t ticket); /* PS_OK done | PS_EBUSY | PS_ESTATE */
+int ps_ticket_wait(ps_ctx* ctx, uint64_t ticket);  /* host blocks until done            */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PS_H_ */

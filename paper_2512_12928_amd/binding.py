@@ -1,0 +1,195 @@
+"""ctypes binding of the C ABI in include/ps.h -- argument marshalling only.
+
+Every function has the name and meaning of its C counterpart; all computation happens in
+the HIP library.  Loading fails loudly if the library has not been built
+(``python -m paper_2512_12928_amd.build``); there is no fallback path.
+
+Tensors may be passed as torch tensors (their ``data_ptr()`` is used; the caller keeps them
+alive and on the right device) or as integer addresses.  Batch arrays are numpy int32.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libproserve_mi355x.so")
+
+PS_OK, PS_EINVAL, PS_ENOMEM, PS_EHIP, PS_ESTATE, PS_EBUSY = 0, -1, -2, -3, -4, -5
+PS_BF16, PS_F32 = 0, 1
+
+EXPORTS = [
+    "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_set_profiling",
+    "ps_get_step_times", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
+]
+
+
+class ps_layer_cfg(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("block_tokens", C.c_int32), ("n_device_blocks", C.c_int32), ("n_host_blocks", C.c_int32),
+                ("softmax_scale", C.c_float), ("out_dtype", C.c_int32), ("decode_chunk", C.c_int32),
+                ("swap_workgroups", C.c_int32)]
+
+
+class ps_batch(C.Structure):
+    _fields_ = [("n_req", C.c_int32), ("n_tokens", C.c_int32), ("q_start", C.POINTER(C.c_int32)),
+                ("kv_len", C.POINTER(C.c_int32)), ("bt_start", C.POINTER(C.c_int32)),
+                ("block_ids", C.POINTER(C.c_int32)), ("prio", C.POINTER(C.c_uint8))]
+
+
+class ps_step_times(C.Structure):
+    _fields_ = [(n, C.c_float) for n in ("upload_ms", "append_ms", "decode_ms", "merge_ms", "prefill_ms", "total_ms")]
+
+
+class PsError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("ps error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s not built: run `python -m paper_2512_12928_amd.build`" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        L.ps_last_error.restype = C.c_char_p
+        L.ps_create.argtypes = [C.POINTER(ps_layer_cfg), C.POINTER(C.c_void_p)]
+        L.ps_destroy.argtypes = [C.c_void_p]
+        L.ps_destroy.restype = None
+        L.ps_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
+        L.ps_step.argtypes = [C.c_void_p, C.POINTER(ps_batch)] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
+        L.ps_set_profiling.argtypes = [C.c_void_p, C.c_int]
+        L.ps_get_step_times.argtypes = [C.c_void_p, C.POINTER(ps_step_times)]
+        swap_args = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p,
+                     C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
+        L.ps_swap_out.argtypes = swap_args
+        L.ps_swap_in.argtypes = swap_args
+        L.ps_ticket_query.argtypes = [C.c_void_p, C.c_uint64]
+        L.ps_ticket_wait.argtypes = [C.c_void_p, C.c_uint64]
+        _lib = L
+    return _lib
+
+
+def ps_last_error() -> str:
+    return lib().ps_last_error().decode()
+
+
+def _check(rc: int, ok=(PS_OK,)) -> int:
+    if rc not in ok:
+        raise PsError(rc, ps_last_error())
+    return rc
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return int(s.cuda_stream)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _i32p(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def ps_create(n_q_heads: int, n_kv_heads: int, n_device_blocks: int, n_host_blocks: int = 0,
+              softmax_scale: float = 0.0, out_dtype: int = PS_BF16, decode_chunk: int = 0,
+              swap_workgroups: int = 0, head_dim: int = 128, block_tokens: int = 16) -> int:
+    cfg = ps_layer_cfg(n_q_heads, n_kv_heads, head_dim, block_tokens, n_device_blocks, n_host_blocks,
+                       softmax_scale, out_dtype, decode_chunk, swap_workgroups)
+    h = C.c_void_p()
+    _check(lib().ps_create(C.byref(cfg), C.byref(h)))
+    return h.value
+
+
+def ps_destroy(ctx: int) -> None:
+    lib().ps_destroy(ctx)
+
+
+def ps_workspace_bytes(ctx: int, max_req: int, max_tokens: int, max_table_entries: int) -> int:
+    out = C.c_size_t()
+    _check(lib().ps_workspace_bytes(ctx, max_req, max_tokens, max_table_entries, C.byref(out)))
+    return out.value
+
+
+def make_batch(q_start, kv_len, bt_start, block_ids, prio=None):
+    """Builds the C struct; returns (struct, keepalive) -- keep both until the call returns."""
+    qs, kv, bs, ids = _i32(q_start), _i32(kv_len), _i32(bt_start), _i32(block_ids)
+    pr = None if prio is None else np.ascontiguousarray(prio, dtype=np.uint8)
+    b = ps_batch(len(kv), int(qs[-1]) if len(qs) else 0, _i32p(qs), _i32p(kv), _i32p(bs), _i32p(ids),
+                 None if pr is None else pr.ctypes.data_as(C.POINTER(C.c_uint8)))
+    return b, (qs, kv, bs, ids, pr)
+
+
+def ps_step(ctx: int, batch, q, k_new, v_new, kv_cache, out, workspace, workspace_bytes: int,
+            stream=None, wait_ticket: int = 0) -> None:
+    """batch: a ps_batch struct, a (struct, keepalive) pair from make_batch, or an object with
+    q_start / kv_len / bt_start / block_ids (/ prio) arrays."""
+    keep = None
+    if isinstance(batch, tuple):
+        batch, keep = batch
+    elif not isinstance(batch, ps_batch):
+        batch, keep = make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids,
+                                 getattr(batch, "prio", None))
+    _check(lib().ps_step(ctx, C.byref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_cache), _ptr(out),
+                         _ptr(workspace), workspace_bytes, _stream(stream), wait_ticket))
+    del keep
+
+
+def ps_set_profiling(ctx: int, enabled: bool) -> None:
+    _check(lib().ps_set_profiling(ctx, int(enabled)))
+
+
+def ps_get_step_times(ctx: int) -> dict:
+    t = ps_step_times()
+    _check(lib().ps_get_step_times(ctx, C.byref(t)))
+    return {n: getattr(t, n) for n, _ in ps_step_times._fields_}
+
+
+def _swap(fn, ctx, first_ids, second_ids, copy_budget, a, b, stream) -> Tuple[int, int]:
+    x, y = _i32(first_ids), _i32(second_ids)
+    if len(x) != len(y):
+        raise ValueError("id lists differ in length")
+    n_done, ticket = C.c_int32(), C.c_uint64()
+    _check(fn(ctx, _i32p(x), _i32p(y), len(x), copy_budget, _ptr(a), _ptr(b), _stream(stream),
+              C.byref(n_done), C.byref(ticket)))
+    return n_done.value, ticket.value
+
+
+def ps_swap_out(ctx: int, dev_block_ids, host_slot_ids, copy_budget: int, kv_cache, host_pool,
+                side_stream=None) -> Tuple[int, int]:
+    return _swap(lib().ps_swap_out, ctx, dev_block_ids, host_slot_ids, copy_budget, kv_cache, host_pool, side_stream)
+
+
+def ps_swap_in(ctx: int, host_slot_ids, dev_block_ids, copy_budget: int, host_pool, kv_cache,
+               side_stream=None) -> Tuple[int, int]:
+    return _swap(lib().ps_swap_in, ctx, host_slot_ids, dev_block_ids, copy_budget, host_pool, kv_cache, side_stream)
+
+
+def ps_ticket_query(ctx: int, ticket: int) -> int:
+    """PS_OK when done, PS_EBUSY while in flight."""
+    return _check(lib().ps_ticket_query(ctx, ticket), ok=(PS_OK, PS_EBUSY))
+
+
+def ps_ticket_wait(ctx: int, ticket: int) -> None:
+    _check(lib().ps_ticket_wait(ctx, ticket))

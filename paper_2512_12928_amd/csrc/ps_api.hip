@@ -1,0 +1,489 @@
+// Host side of the C ABI declared in include/ps.h: argument validation, work-list
+// construction, metadata staging, kernel launches, swap tickets.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ps_internal.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define PS_HIP(call)                                                                          \
+  do {                                                                                        \
+    hipError_t e_ = (call);                                                                   \
+    if (e_ != hipSuccess) return fail(PS_EHIP, "%s: %s", #call, hipGetErrorString(e_));       \
+  } while (0)
+
+constexpr int kStepSlots = 4;     // pinned staging buffers for ps_step metadata
+constexpr int kSwapSlots = 8;     // id staging for swaps
+constexpr int kMaxSwap = 16384;   // blocks per swap call
+constexpr int kTicketRing = 64;
+
+struct StageSlot {
+  void* pinned = nullptr;
+  size_t cap = 0;
+  hipEvent_t ev = nullptr;
+  bool in_flight = false;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+struct ps_ctx {
+  ps_layer_cfg cfg;
+  int device = 0;
+  int G = 1;
+  size_t block_bytes = 0;
+  float scale_log2 = 0.f;
+  StageSlot step_slot[kStepSlots];
+  int step_next = 0;
+  StageSlot swap_slot[kSwapSlots];
+  int32_t* swap_ids_dev = nullptr;  // [kSwapSlots][2][kMaxSwap]
+  int swap_next = 0;
+  hipEvent_t ticket_ev[kTicketRing];
+  uint64_t ticket_id[kTicketRing];
+  uint64_t next_ticket = 1;
+  bool profiling = false;
+  hipEvent_t prof_ev[6];
+  bool prof_valid = false;
+  bool prof_phase[5];
+  std::vector<ps::DecodeItem> ditems;
+  std::vector<ps::MergeItem> mitems;
+  std::vector<ps::PrefillTile> ptiles;
+  std::vector<int32_t> tok_req;
+  std::vector<int32_t> seen;  // duplicate detection in swap lists
+};
+
+namespace {
+
+int pick_decode_chunk(const ps_ctx* c, int64_t decode_kv_tokens) {
+  if (c->cfg.decode_chunk > 0) return c->cfg.decode_chunk;
+  // aim at ~8 workgroups per CU over 256 CUs; partitions are multiples of 128 tokens so the
+  // four waves of a workgroup get whole 32-token tiles
+  int64_t ch = decode_kv_tokens * c->cfg.n_kv_heads / 2048;
+  ch = (ch + 127) / 128 * 128;
+  if (ch < 256) ch = 256;
+  if (ch > 1024) ch = 1024;
+  return (int)ch;
+}
+
+// Bytes of the metadata block for given sizes (also the layout used by ps_step).
+struct MetaLayout {
+  size_t q_start, kv_len, bt_start, block_ids, tok_req, ditems, mitems, ptiles, total;
+};
+
+MetaLayout meta_layout(int n_req, int n_tokens, int64_t n_table, size_t n_ditems, size_t n_mitems,
+                       size_t n_ptiles) {
+  MetaLayout m;
+  size_t o = 0;
+  auto put = [&](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + bytes, 256);
+    return at;
+  };
+  m.q_start = put((size_t)(n_req + 1) * 4);
+  m.kv_len = put((size_t)n_req * 4);
+  m.bt_start = put((size_t)(n_req + 1) * 4);
+  m.block_ids = put((size_t)n_table * 4);
+  m.tok_req = put((size_t)n_tokens * 4);
+  m.ditems = put(n_ditems * sizeof(ps::DecodeItem));
+  m.mitems = put(n_mitems * sizeof(ps::MergeItem));
+  m.ptiles = put(n_ptiles * sizeof(ps::PrefillTile));
+  m.total = o;
+  return m;
+}
+
+constexpr int kMinChunk = 32;
+
+int acquire_slot(StageSlot& s, size_t bytes) {
+  if (s.in_flight) {
+    PS_HIP(hipEventSynchronize(s.ev));
+    s.in_flight = false;
+  }
+  if (s.cap < bytes) {
+    if (s.pinned) PS_HIP(hipHostFree(s.pinned));
+    s.pinned = nullptr;
+    s.cap = 0;
+    size_t cap = align_up(bytes + bytes / 2, 4096);
+    PS_HIP(hipHostMalloc(&s.pinned, cap, hipHostMallocDefault));
+    s.cap = cap;
+  }
+  return PS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ps_last_error(void) { return g_err.c_str(); }
+
+int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
+  if (!cfg || !out) return fail(PS_EINVAL, "ps_create: NULL argument");
+  *out = nullptr;
+  if (cfg->head_dim != ps::kHeadDim) return fail(PS_EINVAL, "head_dim must be 128 (got %d)", cfg->head_dim);
+  if (cfg->block_tokens != ps::kBlockTokens)
+    return fail(PS_EINVAL, "block_tokens must be 16 (got %d)", cfg->block_tokens);
+  if (cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads != 0)
+    return fail(PS_EINVAL, "n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", cfg->n_q_heads,
+                cfg->n_kv_heads);
+  const int G = cfg->n_q_heads / cfg->n_kv_heads;
+  if (G > 16) return fail(PS_EINVAL, "group size Hq/Hkv = %d exceeds 16", G);
+  if (cfg->n_device_blocks < 1 || cfg->n_host_blocks < 0)
+    return fail(PS_EINVAL, "n_device_blocks must be >= 1 and n_host_blocks >= 0");
+  if ((int64_t)cfg->n_device_blocks * 2 * cfg->n_kv_heads > INT32_MAX / 2)
+    return fail(PS_EINVAL, "n_device_blocks * n_kv_heads too large");
+  if (cfg->out_dtype != PS_BF16 && cfg->out_dtype != PS_F32) return fail(PS_EINVAL, "bad out_dtype");
+  if (cfg->decode_chunk != 0 &&
+      (cfg->decode_chunk < kMinChunk || cfg->decode_chunk > 65536 || cfg->decode_chunk % 32 != 0))
+    return fail(PS_EINVAL, "decode_chunk must be 0 or a multiple of 32 in [32, 65536]");
+  if (cfg->swap_workgroups < 0 || cfg->swap_workgroups > 65536) return fail(PS_EINVAL, "bad swap_workgroups");
+  if (!(cfg->softmax_scale >= 0.f) || std::isinf(cfg->softmax_scale))
+    return fail(PS_EINVAL, "softmax_scale must be finite and >= 0");
+
+  ps_ctx* c = new (std::nothrow) ps_ctx();
+  if (!c) return fail(PS_ENOMEM, "out of host memory");
+  c->cfg = *cfg;
+  c->G = G;
+  c->block_bytes = (size_t)2 * cfg->n_kv_heads * ps::kSliceElems * 2;
+  const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  c->scale_log2 = scale * 1.4426950408889634f;
+  for (auto& e : c->ticket_ev) e = nullptr;
+  for (auto& e : c->prof_ev) e = nullptr;
+  for (auto& t : c->ticket_id) t = 0;
+  hipError_t e = hipGetDevice(&c->device);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->swap_ids_dev, (size_t)kSwapSlots * 2 * kMaxSwap * sizeof(int32_t));
+  for (int i = 0; i < kStepSlots && e == hipSuccess; ++i)
+    e = hipEventCreateWithFlags(&c->step_slot[i].ev, hipEventDisableTiming);
+  for (int i = 0; i < kSwapSlots && e == hipSuccess; ++i)
+    e = hipEventCreateWithFlags(&c->swap_slot[i].ev, hipEventDisableTiming);
+  for (int i = 0; i < kTicketRing && e == hipSuccess; ++i)
+    e = hipEventCreateWithFlags(&c->ticket_ev[i], hipEventDisableTiming);
+  for (int i = 0; i < 6 && e == hipSuccess; ++i) e = hipEventCreate(&c->prof_ev[i]);
+  if (e != hipSuccess) {
+    int rc = fail(PS_EHIP, "ps_create: %s", hipGetErrorString(e));
+    ps_destroy(c);
+    return rc;
+  }
+  *out = c;
+  return PS_OK;
+}
+
+void ps_destroy(ps_ctx* c) {
+  if (!c) return;
+  (void)hipDeviceSynchronize();
+  for (auto& s : c->step_slot) {
+    if (s.pinned) (void)hipHostFree(s.pinned);
+    if (s.ev) (void)hipEventDestroy(s.ev);
+  }
+  for (auto& s : c->swap_slot) {
+    if (s.pinned) (void)hipHostFree(s.pinned);
+    if (s.ev) (void)hipEventDestroy(s.ev);
+  }
+  for (auto& e : c->ticket_ev)
+    if (e) (void)hipEventDestroy(e);
+  for (auto& e : c->prof_ev)
+    if (e) (void)hipEventDestroy(e);
+  if (c->swap_ids_dev) (void)hipFree(c->swap_ids_dev);
+  delete c;
+}
+
+int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int64_t max_table_entries,
+                       size_t* out_bytes) {
+  if (!c || !out_bytes) return fail(PS_EINVAL, "ps_workspace_bytes: NULL argument");
+  if (max_req < 0 || max_tokens < 0 || max_table_entries < 0) return fail(PS_EINVAL, "negative size");
+  // worst case over chunk choices: every request is a decode split at the smallest chunk
+  const int min_chunk = c->cfg.decode_chunk > 0 ? c->cfg.decode_chunk : 256;
+  const size_t max_parts = (size_t)max_req + (size_t)(max_table_entries * ps::kBlockTokens / min_chunk);
+  const size_t max_tiles = (size_t)max_req + (size_t)max_tokens / 32;
+  const MetaLayout m = meta_layout(max_req, max_tokens, max_table_entries, max_parts, (size_t)max_req, max_tiles);
+  *out_bytes = m.total + align_up(max_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256);
+  return PS_OK;
+}
+
+int ps_set_profiling(ps_ctx* c, int enabled) {
+  if (!c) return fail(PS_EINVAL, "NULL ctx");
+  c->profiling = enabled != 0;
+  c->prof_valid = false;
+  return PS_OK;
+}
+
+int ps_get_step_times(ps_ctx* c, ps_step_times* out) {
+  if (!c || !out) return fail(PS_EINVAL, "NULL argument");
+  std::memset(out, 0, sizeof *out);
+  if (!c->prof_valid) return fail(PS_ESTATE, "no profiled step");
+  PS_HIP(hipEventSynchronize(c->prof_ev[5]));
+  float* dst[5] = {&out->upload_ms, &out->append_ms, &out->decode_ms, &out->merge_ms, &out->prefill_ms};
+  for (int i = 0; i < 5; ++i) PS_HIP(hipEventElapsedTime(dst[i], c->prof_ev[i], c->prof_ev[i + 1]));
+  PS_HIP(hipEventElapsedTime(&out->total_ms, c->prof_ev[0], c->prof_ev[5]));
+  return PS_OK;
+}
+
+static int find_ticket(ps_ctx* c, uint64_t ticket, hipEvent_t* ev, bool* done) {
+  *done = false;
+  if (ticket == 0 || ticket >= c->next_ticket) return fail(PS_ESTATE, "unknown ticket %llu", (unsigned long long)ticket);
+  const int slot = (int)(ticket % kTicketRing);
+  if (c->ticket_id[slot] != ticket) {  // slot recycled: the older copy finished before reuse
+    *done = true;
+    return PS_OK;
+  }
+  *ev = c->ticket_ev[slot];
+  return PS_OK;
+}
+
+int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, const void* v_new, void* kv_cache,
+            void* out, void* workspace, size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket) {
+  if (!c || !b) return fail(PS_EINVAL, "ps_step: NULL ctx or batch");
+  if (b->n_req < 0 || b->n_tokens < 0) return fail(PS_EINVAL, "negative n_req / n_tokens");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipEvent_t wait_ev = nullptr;
+  if (wait_ticket != 0) {
+    bool done = false;
+    int rc = find_ticket(c, wait_ticket, &wait_ev, &done);
+    if (rc != PS_OK) return rc;
+    if (done) wait_ev = nullptr;
+  }
+  if (b->n_req == 0) {
+    if (b->n_tokens != 0) return fail(PS_EINVAL, "n_tokens != 0 with n_req == 0");
+    if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
+    return PS_OK;
+  }
+  if (!b->q_start || !b->kv_len || !b->bt_start || !b->block_ids)
+    return fail(PS_EINVAL, "ps_step: NULL batch array");
+  if (!q || !kv_cache || !out || !workspace) return fail(PS_EINVAL, "ps_step: NULL tensor pointer");
+  if ((k_new == nullptr) != (v_new == nullptr)) return fail(PS_EINVAL, "k_new and v_new must be given together");
+  if (((uintptr_t)workspace & 255) != 0) return fail(PS_EINVAL, "workspace must be 256-byte aligned");
+  if ((((uintptr_t)q | (uintptr_t)kv_cache | (uintptr_t)out | (uintptr_t)k_new | (uintptr_t)v_new) & 15) != 0)
+    return fail(PS_EINVAL, "tensor pointers must be 16-byte aligned");
+
+  // ---- validation, O(batch description)
+  const int n_req = b->n_req;
+  const int M = c->cfg.n_device_blocks;
+  if (b->q_start[0] != 0 || b->bt_start[0] != 0) return fail(PS_EINVAL, "q_start[0] and bt_start[0] must be 0");
+  int64_t decode_kv = 0;
+  for (int r = 0; r < n_req; ++r) {
+    const int64_t lq = (int64_t)b->q_start[r + 1] - b->q_start[r];
+    const int64_t L = b->kv_len[r];
+    if (lq < 1) return fail(PS_EINVAL, "request %d: l_q = %lld < 1", r, (long long)lq);
+    if (L < lq) return fail(PS_EINVAL, "request %d: l_q = %lld exceeds kv_len = %lld", r, (long long)lq, (long long)L);
+    const int64_t nb = (int64_t)b->bt_start[r + 1] - b->bt_start[r];
+    if (nb != (L + ps::kBlockTokens - 1) / ps::kBlockTokens)
+      return fail(PS_EINVAL, "request %d: block table has %lld entries, kv_len %lld needs %lld", r, (long long)nb,
+                  (long long)L, (long long)((L + ps::kBlockTokens - 1) / ps::kBlockTokens));
+    if (lq == 1) decode_kv += L;
+  }
+  if (b->q_start[n_req] != b->n_tokens) return fail(PS_EINVAL, "q_start[n_req] != n_tokens");
+  const int64_t n_table = b->bt_start[n_req];
+  for (int64_t i = 0; i < n_table; ++i)
+    if ((uint32_t)b->block_ids[i] >= (uint32_t)M)
+      return fail(PS_EINVAL, "block_ids[%lld] = %d outside [0, %d)", (long long)i, b->block_ids[i], M);
+
+  // ---- work lists
+  const int CH = pick_decode_chunk(c, decode_kv);
+  const int TT = ps::prefill_tile_tokens(c->G);
+  c->ditems.clear();
+  c->mitems.clear();
+  c->ptiles.clear();
+  c->tok_req.resize((size_t)b->n_tokens);
+  int n_parts = 0;
+  struct TileKey {
+    int64_t reach;
+    ps::PrefillTile t;
+  };
+  std::vector<TileKey> tiles;
+  for (int r = 0; r < n_req; ++r) {
+    const int qs = b->q_start[r], lq = b->q_start[r + 1] - qs, L = b->kv_len[r];
+    for (int t = 0; t < lq; ++t) c->tok_req[(size_t)qs + t] = r;
+    if (lq == 1) {
+      const int np = (L + CH - 1) / CH;
+      if (np == 1) {
+        c->ditems.push_back(ps::DecodeItem{r, qs, 0, L, -1, {0, 0, 0}});
+      } else {
+        c->mitems.push_back(ps::MergeItem{qs, n_parts, np, 0});
+        for (int k = 0; k < np; ++k)
+          c->ditems.push_back(ps::DecodeItem{r, qs, k * CH, std::min((k + 1) * CH, L), n_parts++, {0, 0, 0}});
+      }
+    } else {
+      const int p = L - lq;
+      for (int q0 = 0; q0 < lq; q0 += TT) tiles.push_back(TileKey{(int64_t)p + q0, ps::PrefillTile{r, q0}});
+    }
+  }
+  // heaviest tiles (longest causal reach) first, so the tail of the launch is made of short ones
+  std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
+  for (auto& t : tiles) c->ptiles.push_back(t.t);
+
+  const MetaLayout ml = meta_layout(n_req, b->n_tokens, n_table, c->ditems.size(), c->mitems.size(), c->ptiles.size());
+  const size_t part_bytes = align_up((size_t)n_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256);
+  if (ml.total + part_bytes > workspace_bytes)
+    return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", ml.total + part_bytes, workspace_bytes);
+
+  // ---- stage + upload metadata
+  StageSlot& slot = c->step_slot[c->step_next];
+  c->step_next = (c->step_next + 1) % kStepSlots;
+  int rc = acquire_slot(slot, ml.total);
+  if (rc != PS_OK) return rc;
+  char* h = (char*)slot.pinned;
+  std::memcpy(h + ml.q_start, b->q_start, (size_t)(n_req + 1) * 4);
+  std::memcpy(h + ml.kv_len, b->kv_len, (size_t)n_req * 4);
+  std::memcpy(h + ml.bt_start, b->bt_start, (size_t)(n_req + 1) * 4);
+  std::memcpy(h + ml.block_ids, b->block_ids, (size_t)n_table * 4);
+  std::memcpy(h + ml.tok_req, c->tok_req.data(), c->tok_req.size() * 4);
+  if (!c->ditems.empty()) std::memcpy(h + ml.ditems, c->ditems.data(), c->ditems.size() * sizeof(ps::DecodeItem));
+  if (!c->mitems.empty()) std::memcpy(h + ml.mitems, c->mitems.data(), c->mitems.size() * sizeof(ps::MergeItem));
+  if (!c->ptiles.empty()) std::memcpy(h + ml.ptiles, c->ptiles.data(), c->ptiles.size() * sizeof(ps::PrefillTile));
+
+  if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
+  const bool prof = c->profiling;
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
+  char* w = (char*)workspace;
+  PS_HIP(hipMemcpyAsync(w, h, ml.total, hipMemcpyHostToDevice, stream));
+  PS_HIP(hipEventRecord(slot.ev, stream));
+  slot.in_flight = true;
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev[1], stream));
+
+  ps::StepParams P;
+  P.q_start = (const int32_t*)(w + ml.q_start);
+  P.kv_len = (const int32_t*)(w + ml.kv_len);
+  P.bt_start = (const int32_t*)(w + ml.bt_start);
+  P.block_ids = (const int32_t*)(w + ml.block_ids);
+  P.tok_req = (const int32_t*)(w + ml.tok_req);
+  P.ditems = (const ps::DecodeItem*)(w + ml.ditems);
+  P.mitems = (const ps::MergeItem*)(w + ml.mitems);
+  P.ptiles = (const ps::PrefillTile*)(w + ml.ptiles);
+  P.partials = (float*)(w + ml.total);
+  P.q = (const uint16_t*)q;
+  P.k_new = (const uint16_t*)k_new;
+  P.v_new = (const uint16_t*)v_new;
+  P.cache = (uint16_t*)kv_cache;
+  P.out = out;
+  P.Hq = c->cfg.n_q_heads;
+  P.Hkv = c->cfg.n_kv_heads;
+  P.G = c->G;
+  P.out_f32 = c->cfg.out_dtype == PS_F32;
+  P.scale_log2 = c->scale_log2;
+
+  if (k_new) PS_HIP(ps::launch_append(P, b->n_tokens, stream));
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
+  PS_HIP(ps::launch_decode(P, (int)c->ditems.size(), stream));
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev[3], stream));
+  PS_HIP(ps::launch_merge(P, (int)c->mitems.size(), stream));
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev[4], stream));
+  PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), stream));
+  if (prof) {
+    PS_HIP(hipEventRecord(c->prof_ev[5], stream));
+    c->prof_valid = true;
+  }
+  return PS_OK;
+}
+
+static int swap_common(ps_ctx* c, bool out_dir, const int32_t* dev_ids, const int32_t* host_ids, int32_t n,
+                       int32_t copy_budget, const void* kv_cache, const void* host_pool, void* side_stream,
+                       int32_t* n_done, uint64_t* ticket) {
+  const char* fn = out_dir ? "ps_swap_out" : "ps_swap_in";
+  if (!c || !n_done || !ticket) return fail(PS_EINVAL, "%s: NULL ctx / n_done / ticket", fn);
+  *n_done = 0;
+  *ticket = 0;
+  if (n < 0) return fail(PS_EINVAL, "%s: n < 0", fn);
+  const int m = copy_budget < 0 ? n : std::min(n, copy_budget);
+  if (n > 0 && (!dev_ids || !host_ids)) return fail(PS_EINVAL, "%s: NULL id list", fn);
+  // the whole list is validated, also the part the budget leaves for a later step
+  const int M = c->cfg.n_device_blocks, Mh = c->cfg.n_host_blocks;
+  for (int pass = 0; pass < 2; ++pass) {
+    const int32_t* ids = pass == 0 ? dev_ids : host_ids;
+    const int lim = pass == 0 ? M : Mh;
+    c->seen.assign((size_t)lim, 0);
+    for (int k = 0; k < n; ++k) {
+      if ((uint32_t)ids[k] >= (uint32_t)lim)
+        return fail(PS_EINVAL, "%s: %s id %d at %d outside [0, %d)", fn, pass == 0 ? "device block" : "host slot",
+                    ids[k], k, lim);
+      if (c->seen[(size_t)ids[k]]++) return fail(PS_EINVAL, "%s: duplicate %s id %d", fn, pass == 0 ? "device block" : "host slot", ids[k]);
+    }
+  }
+  if (m == 0) return PS_OK;
+  if (!kv_cache || !host_pool) return fail(PS_EINVAL, "%s: NULL pool pointer", fn);
+  if ((((uintptr_t)kv_cache | (uintptr_t)host_pool) & 15) != 0) return fail(PS_EINVAL, "%s: pools must be 16-byte aligned", fn);
+  if (m > kMaxSwap) return fail(PS_EINVAL, "%s: at most %d blocks per call (got %d)", fn, kMaxSwap, m);
+  hipStream_t stream = (hipStream_t)side_stream;
+
+  const int si = c->swap_next;
+  c->swap_next = (c->swap_next + 1) % kSwapSlots;
+  StageSlot& slot = c->swap_slot[si];
+  int rc = acquire_slot(slot, (size_t)2 * kMaxSwap * sizeof(int32_t));
+  if (rc != PS_OK) return rc;
+  int32_t* h = (int32_t*)slot.pinned;
+  std::memcpy(h, dev_ids, (size_t)m * 4);
+  std::memcpy(h + m, host_ids, (size_t)m * 4);
+  int32_t* d = c->swap_ids_dev + (size_t)si * 2 * kMaxSwap;
+  PS_HIP(hipMemcpyAsync(d, h, (size_t)2 * m * 4, hipMemcpyHostToDevice, stream));
+  const int wgs = c->cfg.swap_workgroups > 0 ? c->cfg.swap_workgroups : 64;
+  if (out_dir)
+    PS_HIP(ps::launch_block_copy(d, d + m, m, kv_cache, const_cast<void*>(host_pool), c->block_bytes, wgs, stream));
+  else
+    PS_HIP(ps::launch_block_copy(d + m, d, m, host_pool, const_cast<void*>(kv_cache), c->block_bytes, wgs, stream));
+  PS_HIP(hipEventRecord(slot.ev, stream));
+  slot.in_flight = true;
+
+  const uint64_t id = c->next_ticket++;
+  const int ts = (int)(id % kTicketRing);
+  if (c->ticket_id[ts] != 0) PS_HIP(hipEventSynchronize(c->ticket_ev[ts]));  // recycled: older copy must be over
+  PS_HIP(hipEventRecord(c->ticket_ev[ts], stream));
+  c->ticket_id[ts] = id;
+  *n_done = m;
+  *ticket = id;
+  return PS_OK;
+}
+
+int ps_swap_out(ps_ctx* c, const int32_t* dev_block_ids, const int32_t* host_slot_ids, int32_t n, int32_t copy_budget,
+                const void* kv_cache, void* host_pool, void* side_stream, int32_t* n_done, uint64_t* ticket) {
+  return swap_common(c, true, dev_block_ids, host_slot_ids, n, copy_budget, kv_cache, host_pool, side_stream, n_done,
+                     ticket);
+}
+
+int ps_swap_in(ps_ctx* c, const int32_t* host_slot_ids, const int32_t* dev_block_ids, int32_t n, int32_t copy_budget,
+               const void* host_pool, void* kv_cache, void* side_stream, int32_t* n_done, uint64_t* ticket) {
+  return swap_common(c, false, dev_block_ids, host_slot_ids, n, copy_budget, kv_cache, host_pool, side_stream, n_done,
+                     ticket);
+}
+
+int ps_ticket_query(ps_ctx* c, uint64_t ticket) {
+  if (!c) return fail(PS_EINVAL, "NULL ctx");
+  hipEvent_t ev = nullptr;
+  bool done = false;
+  int rc = find_ticket(c, ticket, &ev, &done);
+  if (rc != PS_OK) return rc;
+  if (done) return PS_OK;
+  hipError_t e = hipEventQuery(ev);
+  if (e == hipSuccess) return PS_OK;
+  if (e == hipErrorNotReady) return PS_EBUSY;
+  return fail(PS_EHIP, "hipEventQuery: %s", hipGetErrorString(e));
+}
+
+int ps_ticket_wait(ps_ctx* c, uint64_t ticket) {
+  if (!c) return fail(PS_EINVAL, "NULL ctx");
+  hipEvent_t ev = nullptr;
+  bool done = false;
+  int rc = find_ticket(c, ticket, &ev, &done);
+  if (rc != PS_OK) return rc;
+  if (done) return PS_OK;
+  PS_HIP(hipEventSynchronize(ev));
+  return PS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Internal declarations shared by the host-side API code and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ps.h"
+
+namespace ps {
+
+constexpr int kHeadDim = 128;
+constexpr int kBlockTokens = 16;
+constexpr int kSliceElems = kBlockTokens * kHeadDim;  // one (block, K|V, kv-head) slice: 4 KiB
+constexpr int kTileTokens = 32;                       // KV tokens per MFMA tile (two blocks)
+constexpr int kPartStride = 132;                      // fp32 per split-K partial: o[128], m, l, pad
+
+// One split-K partition of one decode token (all G query heads of one kv-head are handled by
+// the workgroup that blockIdx.y selects).
+struct DecodeItem {
+  int32_t req;   // request index in the batch
+  int32_t tok;   // batch token index (row of q / out)
+  int32_t t0;    // first cached token of the partition (multiple of the chunk size)
+  int32_t t1;    // one past the last cached token (kv_len for the final partition)
+  int32_t part;  // slot in the partials buffer, or -1: single partition, write out directly
+  int32_t pad[3];
+};
+
+struct MergeItem {
+  int32_t tok;
+  int32_t part0;
+  int32_t n_parts;
+  int32_t pad;
+};
+
+// One tile of consecutive query tokens of a prefill chunk.
+struct PrefillTile {
+  int32_t req;
+  int32_t q0;  // chunk-relative index of the tile's first query token
+};
+
+struct StepParams {
+  // batch description (device copies)
+  const int32_t* q_start;
+  const int32_t* kv_len;
+  const int32_t* bt_start;
+  const int32_t* block_ids;
+  const int32_t* tok_req;  // [n_tokens] request index of each batch token
+  const DecodeItem* ditems;
+  const MergeItem* mitems;
+  const PrefillTile* ptiles;
+  float* partials;
+  // tensors
+  const uint16_t* q;
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  uint16_t* cache;
+  void* out;
+  int32_t Hq, Hkv, G;
+  int32_t out_f32;
+  float scale_log2;  // softmax_scale * log2(e)
+};
+
+// Launchers (ps_kernels.hip). Each checks its own launch and returns the hipError_t.
+hipError_t launch_append(const StepParams& p, int n_tokens, hipStream_t s);
+hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s);
+hipError_t launch_merge(const StepParams& p, int n_merge, hipStream_t s);
+// tile_tokens: query tokens per workgroup tile as returned by prefill_tile_tokens(G).
+hipError_t launch_prefill(const StepParams& p, int n_tiles, hipStream_t s);
+int prefill_tile_tokens(int G);
+int prefill_heads_per_wg(int G);
+hipError_t launch_block_copy(const int32_t* src_ids, const int32_t* dst_ids, int n, const void* src_pool,
+                             void* dst_pool, size_t block_bytes, int workgroups, hipStream_t s);
+
+}  // namespace ps

@@ -1,0 +1,486 @@
+// gfx950 (CDNA4) kernels for one mixed-batch attention layer over a paged bf16 KV cache and for
+// KV block copies.  Wave64; bf16 MFMA with fp32 accumulation.
+//
+// Operand plan shared by the decode and prefill kernels.  Scores are produced transposed,
+//   S^T[token][qrow] = K[token][:] . Q[qrow][:]        (A = K tile, B = Q^T)
+// so that in the MFMA result layout each lane owns ONE query row and several tokens.  The
+// probabilities that lane computes are then, without any cross-lane movement, exactly the
+// B operand of the second product
+//   O^T[dim][qrow] += V^T[dim][token] . P^T[token][qrow]   (A = V^T tile, B = P^T)
+// and the per-row rescale factors of the online softmax are per-lane scalars.  K is stored
+// token-major and V dim-major inside a block, so both A operands are plain 16-byte (K) or
+// 8-byte (V) loads from the cache.
+#include "ps_internal.h"
+
+namespace ps {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define PS_NEG_INF (-__builtin_inff())
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  f32x2 v = {a, b};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);  // round to nearest even
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ bf16x8 join_bf16x4(uint2 lo, uint2 hi) {
+  uint4 v = {lo.x, lo.y, hi.x, hi.y};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Zero the 16-bit elements e (0..3) of v whose token index first+e is >= limit.
+__device__ __forceinline__ uint2 zero_from(uint2 v, int first, int limit) {
+  uint32_t m0 = (first + 0 < limit ? 0x0000FFFFu : 0u) | (first + 1 < limit ? 0xFFFF0000u : 0u);
+  uint32_t m1 = (first + 2 < limit ? 0x0000FFFFu : 0u) | (first + 3 < limit ? 0xFFFF0000u : 0u);
+  v.x &= m0;
+  v.y &= m1;
+  return v;
+}
+
+__device__ __forceinline__ const uint16_t* k_slice(const uint16_t* cache, int block, int Hkv, int g) {
+  return cache + ((size_t)(block * 2 + 0) * Hkv + g) * kSliceElems;
+}
+__device__ __forceinline__ const uint16_t* v_slice(const uint16_t* cache, int block, int Hkv, int g) {
+  return cache + ((size_t)(block * 2 + 1) * Hkv + g) * kSliceElems;
+}
+
+// ------------------------------------------------------------------------------------ append
+// Writes this step's new K/V rows into the paged cache.  grid (n_tokens, Hkv), 128 threads:
+// thread x moves dim x.  K rows stay contiguous; V goes to the dim-major slot (stride 16).
+__global__ __launch_bounds__(128) void append_kernel(StepParams P) {
+  const int tok = blockIdx.x, g = blockIdx.y, x = threadIdx.x;
+  const int r = P.tok_req[tok];
+  const int qs = P.q_start[r];
+  const int lq = P.q_start[r + 1] - qs;
+  const int pos = P.kv_len[r] - lq + (tok - qs);
+  const int b = P.block_ids[P.bt_start[r] + (pos >> 4)];
+  const int t = pos & 15;
+  const size_t src = ((size_t)tok * P.Hkv + g) * kHeadDim + x;
+  uint16_t* kd = const_cast<uint16_t*>(k_slice(P.cache, b, P.Hkv, g));
+  uint16_t* vd = const_cast<uint16_t*>(v_slice(P.cache, b, P.Hkv, g));
+  kd[t * kHeadDim + x] = P.k_new[src];
+  vd[x * kBlockTokens + t] = P.v_new[src];
+}
+
+// ------------------------------------------------------------------------------------ decode
+// Split-K decode attention, HBM-bound.  grid (n_items, Hkv), 256 threads = 4 waves.
+// The workgroup owns KV tokens [t0, t1) of one request for one kv-head and all G query heads
+// of that head (padded to the 16 columns of a 16x16x32 MFMA), so every K/V byte is read once.
+// Wave w streams the 32-token tiles w, w+4, ...; per tile it issues 16 x 16-byte loads per
+// lane (8 KiB K + 8 KiB V), 8 MFMAs for S^T and 8 for O^T.  The four waves' running
+// (m, l, O) states are combined through LDS; the result is either the final output (single
+// partition) or an unnormalised partial for the merge kernel.
+__global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
+  extern __shared__ float smem[];  // [4][G][128] O, then [4][16] m, [4][16] l
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int j = lane & 15;   // token row of the K operand / query-head column of Q, P, O
+  const int kg = lane >> 4;  // k-group of the MFMA operands
+  const DecodeItem it = P.ditems[blockIdx.x];
+  const int g = blockIdx.y;
+  const int G = P.G, Hkv = P.Hkv;
+  const int* table = P.block_ids + P.bt_start[it.req];
+  const int nblk = (P.kv_len[it.req] + kBlockTokens - 1) >> 4;
+
+  // Q^T operand: lane (head j, k-group kg) holds dims (c*4+kg)*8 .. +7 for chunk c.
+  bf16x8 qop[4];
+  {
+    const uint16_t* qrow = P.q + ((size_t)it.tok * P.Hq + g * G + (j < G ? j : 0)) * kHeadDim;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      uint4 v = *(const uint4*)(qrow + (c * 4 + kg) * 8);
+      if (j >= G) v = make_uint4(0, 0, 0, 0);
+      qop[c] = as_bf16x8(v);
+    }
+  }
+
+  float m = PS_NEG_INF, l = 0.f;
+  f32x4 acc[8];
+#pragma unroll
+  for (int n = 0; n < 8; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const int ntiles = (it.t1 - it.t0 + kTileTokens - 1) / kTileTokens;
+  for (int tile = wave; tile < ntiles; tile += 4) {
+    const int ts = it.t0 + tile * kTileTokens;
+    const int bA = ts >> 4;
+    const int idA = table[bA];
+    const int idB = (bA + 1 < nblk) ? table[bA + 1] : idA;  // absent second block: masked below
+    const uint16_t* kA = k_slice(P.cache, idA, Hkv, g);
+    const uint16_t* kB = k_slice(P.cache, idB, Hkv, g);
+    const uint16_t* vA = v_slice(P.cache, idA, Hkv, g);
+    const uint16_t* vB = v_slice(P.cache, idB, Hkv, g);
+
+    uint4 ka[4], kb[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      ka[c] = *(const uint4*)(kA + j * kHeadDim + (c * 4 + kg) * 8);
+      kb[c] = *(const uint4*)(kB + j * kHeadDim + (c * 4 + kg) * 8);
+    }
+    uint2 va[8], vb[8];
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      va[n] = *(const uint2*)(vA + (n * 16 + j) * kBlockTokens + kg * 4);
+      vb[n] = *(const uint2*)(vB + (n * 16 + j) * kBlockTokens + kg * 4);
+    }
+
+    f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[c]), qop[c], sA, 0, 0, 0);
+      sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[c]), qop[c], sB, 0, 0, 0);
+    }
+    // sA[e]: token ts + 4*kg + e, head j.   sB[e]: token ts + 16 + 4*kg + e.
+    float s[8];
+    const int tokA = ts + 4 * kg, tokB = ts + 16 + 4 * kg;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      s[e] = (tokA + e < it.t1) ? sA[e] * P.scale_log2 : PS_NEG_INF;
+      s[4 + e] = (tokB + e < it.t1) ? sB[e] * P.scale_log2 : PS_NEG_INF;
+    }
+    if (ts + kTileTokens > it.t1) {  // ragged tail: slots past kv_len may hold anything
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        va[n] = zero_from(va[n], tokA, it.t1);
+        vb[n] = zero_from(vb[n], tokB, it.t1);
+      }
+    }
+    float tmax = s[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, s[e]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float m_new = fmaxf(m, tmax);  // finite: every tile holds at least one valid token
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    float p[8], psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = __builtin_amdgcn_exp2f(s[e] - m_new);
+      psum += p[e];
+    }
+    l = l * alpha + psum;
+    m = m_new;
+    uint4 pv = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
+                pack_bf16x2(p[6], p[7])};
+    const bf16x8 pop = as_bf16x8(pv);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      acc[n] *= alpha;
+      acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(join_bf16x4(va[n], vb[n]), pop, acc[n], 0, 0, 0);
+    }
+  }
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+
+  // combine the four waves
+  float* sm_o = smem;                     // [4][G][128]
+  float* sm_m = smem + 4 * G * kHeadDim;  // [4][16]
+  float* sm_l = sm_m + 64;
+  if (j < G) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+      *(f32x4*)(sm_o + ((wave * G + j) * kHeadDim) + n * 16 + kg * 4) = acc[n];
+    if (kg == 0) {
+      sm_m[wave * 16 + j] = m;
+      sm_l[wave * 16 + j] = l;
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 256) {
+    const int h = idx >> 7, x = idx & 127;
+    float mw[4], mstar = PS_NEG_INF;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      mw[w] = sm_m[w * 16 + h];
+      mstar = fmaxf(mstar, mw[w]);
+    }
+    float L = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = __builtin_amdgcn_exp2f(mw[w] - mstar);  // idle wave: m = -inf -> 0
+      L += sm_l[w * 16 + h] * f;
+      o += sm_o[(w * G + h) * kHeadDim + x] * f;
+    }
+    const int head = g * G + h;
+    if (it.part < 0) {
+      const size_t oi = ((size_t)it.tok * P.Hq + head) * kHeadDim + x;
+      const float r = o / L;
+      if (P.out_f32)
+        ((float*)P.out)[oi] = r;
+      else
+        ((uint16_t*)P.out)[oi] = (uint16_t)(pack_bf16x2(r, 0.f) & 0xFFFFu);
+    } else {
+      float* dst = P.partials + ((size_t)it.part * P.Hq + head) * kPartStride;
+      dst[x] = o;
+      if (x == 0) {
+        dst[128] = mstar;
+        dst[129] = L;
+      }
+    }
+  }
+}
+
+// Combines the split-K partials of one decode token.  grid (n_merge, Hq), 128 threads (dims).
+__global__ __launch_bounds__(128) void merge_kernel(StepParams P) {
+  const MergeItem it = P.mitems[blockIdx.x];
+  const int head = blockIdx.y, x = threadIdx.x;
+  const float* base = P.partials + ((size_t)it.part0 * P.Hq + head) * kPartStride;
+  const size_t stride = (size_t)P.Hq * kPartStride;
+  float mstar = PS_NEG_INF;
+  for (int k = 0; k < it.n_parts; ++k) mstar = fmaxf(mstar, base[k * stride + 128]);
+  float L = 0.f, o = 0.f;
+  for (int k = 0; k < it.n_parts; ++k) {
+    const float f = __builtin_amdgcn_exp2f(base[k * stride + 128] - mstar);
+    L += base[k * stride + 129] * f;
+    o += base[k * stride + x] * f;
+  }
+  const size_t oi = ((size_t)it.tok * P.Hq + head) * kHeadDim + x;
+  const float r = o / L;
+  if (P.out_f32)
+    ((float*)P.out)[oi] = r;
+  else
+    ((uint16_t*)P.out)[oi] = (uint16_t)(pack_bf16x2(r, 0.f) & 0xFFFFu);
+}
+
+// ------------------------------------------------------------------------------------ prefill
+// Causal attention of prefill chunks on 32x32x16 bf16 MFMA.  grid (n_tiles, Hkv, G / HW),
+// 256 threads = 4 waves.  Wave w owns NB*32 consecutive query tokens of one query head:
+// head = g*G + z*HW + w % HW, token sub-tile w / HW (HW = heads per workgroup).  All waves of a
+// workgroup walk the same KV tiles of the same kv-head.
+template <int NB>
+__global__ __launch_bounds__(256) void prefill_kernel(StepParams P, int HW) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int j = lane & 31;   // token row of the K operand / query column of Q, P, O
+  const int h2 = lane >> 5;  // k-group
+  const PrefillTile t = P.ptiles[blockIdx.x];
+  const int g = blockIdx.y;
+  const int G = P.G, Hkv = P.Hkv;
+  const int head = g * G + blockIdx.z * HW + wave % HW;
+  const int r = t.req;
+  const int qs = P.q_start[r];
+  const int lq = P.q_start[r + 1] - qs;
+  const int L = P.kv_len[r];
+  const int p = L - lq;
+  const int q0 = t.q0 + (wave / HW) * (NB * 32);
+  if (q0 >= lq) return;  // nothing for this wave (no workgroup barrier is used below)
+  const int* table = P.block_ids + P.bt_start[r];
+  const int nblk = (L + kBlockTokens - 1) >> 4;
+
+  // Q^T operands: lane (query j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.
+  bf16x8 qop[NB][8];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    int row = q0 + nb * 32 + j;
+    row = row < lq ? row : lq - 1;
+    const uint16_t* qrow = P.q + ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) qop[nb][c] = as_bf16x8(*(const uint4*)(qrow + (c * 2 + h2) * 8));
+  }
+
+  float m[NB], l[NB];
+  f32x16 acc[NB][4];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    m[nb] = PS_NEG_INF;
+    l[nb] = 0.f;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[nb][n][e] = 0.f;
+  }
+
+  const int q_last = (q0 + NB * 32 < lq ? q0 + NB * 32 : lq) - 1;
+  const int ntiles = (p + q_last) / kTileTokens + 1;
+  for (int tile = 0; tile < ntiles; ++tile) {
+    const int ts = tile * kTileTokens;
+    const int bA = ts >> 4;
+    const int idA = table[bA];
+    const int idB = (bA + 1 < nblk) ? table[bA + 1] : idA;
+    // K operand: lane (token j, k-group h2); tokens 0..15 from block A, 16..31 from block B
+    const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + (j & 15) * kHeadDim;
+    uint4 kop[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) kop[c] = *(const uint4*)(krow + (c * 2 + h2) * 8);
+    // V^T operand of step u (block A, B), dim tile n: lane (dim 32n+j, k-group h2) holds tokens
+    // 4*h2..+3 and 8+4*h2..+3 of that block
+    uint2 vlo[2][4], vhi[2][4];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const uint16_t* vs = v_slice(P.cache, u == 0 ? idA : idB, Hkv, g);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        vlo[u][n] = *(const uint2*)(vs + (n * 32 + j) * kBlockTokens + h2 * 4);
+        vhi[u][n] = *(const uint2*)(vs + (n * 32 + j) * kBlockTokens + 8 + h2 * 4);
+      }
+    }
+    if (ts + kTileTokens > L) {  // slots past kv_len may hold anything
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+          vlo[u][n] = zero_from(vlo[u][n], ts + 16 * u + 4 * h2, L);
+          vhi[u][n] = zero_from(vhi[u][n], ts + 16 * u + 8 + 4 * h2, L);
+        }
+    }
+
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      f32x16 s;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kop[c]), qop[nb][c], s, 0, 0, 0);
+      // s[e]: token ts + 8*(e/4) + 4*h2 + e%4, query q0 + nb*32 + j
+      const int qpos = p + q0 + nb * 32 + j;
+      const bool diag = ts + kTileTokens - 1 > p + q0 + nb * 32;  // wave-uniform
+      float tmax = PS_NEG_INF;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int tok = ts + 8 * (e >> 2) + 4 * h2 + (e & 3);
+        float v = s[e] * P.scale_log2;
+        if (diag && tok > qpos) v = PS_NEG_INF;
+        s[e] = v;
+        tmax = fmaxf(tmax, v);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m[nb], tmax);  // finite from the first tile on (token 0 is visible)
+      const float alpha = __builtin_amdgcn_exp2f(m[nb] - m_new);
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        s[e] = __builtin_amdgcn_exp2f(s[e] - m_new);
+        psum += s[e];
+      }
+      l[nb] = l[nb] * alpha + psum;
+      m[nb] = m_new;
+#pragma unroll
+      for (int n = 0; n < 4; ++n) acc[nb][n] *= alpha;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        uint4 pv = {pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
+                    pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7])};
+        const bf16x8 pop = as_bf16x8(pv);
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+          acc[nb][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(join_bf16x4(vlo[u][n], vhi[u][n]), pop,
+                                                               acc[nb][n], 0, 0, 0);
+      }
+    }
+  }
+
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    float ls = l[nb] + __shfl_xor(l[nb], 32);
+    const float inv = 1.f / ls;
+    const int row = q0 + nb * 32 + j;
+    if (row < lq) {
+      const size_t ob = ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
+#pragma unroll
+      for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          const int x = n * 32 + a * 8 + h2 * 4;  // acc[..][n][4a+b] is dim x + b
+          const float o0 = acc[nb][n][4 * a + 0] * inv, o1 = acc[nb][n][4 * a + 1] * inv;
+          const float o2 = acc[nb][n][4 * a + 2] * inv, o3 = acc[nb][n][4 * a + 3] * inv;
+          if (P.out_f32) {
+            *(f32x4*)((float*)P.out + ob + x) = (f32x4){o0, o1, o2, o3};
+          } else {
+            uint2 w = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
+            *(uint2*)((uint16_t*)P.out + ob + x) = w;
+          }
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------ block copy
+// dst_pool[dst_ids[k]] <- src_pool[src_ids[k]] for k < n, whole blocks.  Either pool may be
+// pinned host memory addressed over the host link.  Unit of work = 8 KiB (two 16-byte loads in
+// flight per lane; a block is Hkv * 8 KiB); two units per pass; grid-stride over unit pairs.
+constexpr int kCopyUnit = 8192;
+
+__global__ __launch_bounds__(256) void block_copy_kernel(const int32_t* __restrict__ src_ids,
+                                                         const int32_t* __restrict__ dst_ids, int n,
+                                                         const char* __restrict__ src_pool,
+                                                         char* __restrict__ dst_pool, size_t block_bytes) {
+  const int upb = (int)(block_bytes / kCopyUnit);
+  const long total = (long)n * upb;
+  for (long u = 2L * blockIdx.x; u < total; u += 2L * gridDim.x) {
+    const bool two = u + 1 < total;
+    const long u1 = two ? u + 1 : u;
+    const int k0 = (int)(u / upb), k1 = (int)(u1 / upb);
+    const size_t o0 = (size_t)(u % upb) * kCopyUnit + threadIdx.x * 16;
+    const size_t o1 = (size_t)(u1 % upb) * kCopyUnit + threadIdx.x * 16;
+    const char* s0 = src_pool + (size_t)src_ids[k0] * block_bytes + o0;
+    const char* s1 = src_pool + (size_t)src_ids[k1] * block_bytes + o1;
+    char* d0 = dst_pool + (size_t)dst_ids[k0] * block_bytes + o0;
+    char* d1 = dst_pool + (size_t)dst_ids[k1] * block_bytes + o1;
+    const uint4 a0 = *(const uint4*)(s0);
+    const uint4 a1 = *(const uint4*)(s0 + 4096);
+    const uint4 b0 = *(const uint4*)(s1);
+    const uint4 b1 = *(const uint4*)(s1 + 4096);
+    *(uint4*)(d0) = a0;
+    *(uint4*)(d0 + 4096) = a1;
+    if (two) {
+      *(uint4*)(d1) = b0;
+      *(uint4*)(d1 + 4096) = b1;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------ launchers
+hipError_t launch_append(const StepParams& p, int n_tokens, hipStream_t s) {
+  if (n_tokens <= 0) return hipSuccess;
+  hipLaunchKernelGGL(append_kernel, dim3(n_tokens, p.Hkv), dim3(128), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s) {
+  if (n_items <= 0) return hipSuccess;
+  const size_t smem = (size_t)(4 * p.G * kHeadDim + 128) * sizeof(float);
+  hipLaunchKernelGGL(decode_kernel, dim3(n_items, p.Hkv), dim3(256), smem, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge(const StepParams& p, int n_merge, hipStream_t s) {
+  if (n_merge <= 0) return hipSuccess;
+  hipLaunchKernelGGL(merge_kernel, dim3(n_merge, p.Hq), dim3(128), 0, s, p);
+  return hipGetLastError();
+}
+
+constexpr int kPrefillNB = 1;
+
+int prefill_heads_per_wg(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
+int prefill_tile_tokens(int G) { return (4 / prefill_heads_per_wg(G)) * kPrefillNB * 32; }
+
+hipError_t launch_prefill(const StepParams& p, int n_tiles, hipStream_t s) {
+  if (n_tiles <= 0) return hipSuccess;
+  const int HW = prefill_heads_per_wg(p.G);
+  hipLaunchKernelGGL(prefill_kernel<kPrefillNB>, dim3(n_tiles, p.Hkv, p.G / HW), dim3(256), 0, s, p, HW);
+  return hipGetLastError();
+}
+
+hipError_t launch_block_copy(const int32_t* src_ids, const int32_t* dst_ids, int n, const void* src_pool,
+                             void* dst_pool, size_t block_bytes, int workgroups, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const long pairs = ((long)n * (long)(block_bytes / kCopyUnit) + 1) / 2;
+  int grid = (int)(pairs < workgroups ? pairs : workgroups);
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(block_copy_kernel, dim3(grid), dim3(256), 0, s, src_ids, dst_ids, n,
+                     (const char*)src_pool, (char*)dst_pool, block_bytes);
+  return hipGetLastError();
+}
+
+}  // namespace ps

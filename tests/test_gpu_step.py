@@ -1,0 +1,195 @@
+"""GPU parity of ps_step (append + decode split-K + merge + prefill MFMA) against the fp64 oracle,
+element by element, through the C ABI.  Tolerance: max-abs 1e-2 on the f32 output path (bf16
+inputs, fp32 accumulation); on the bf16 output path 1e-2 + 2^-8 |o| (half an ulp of the output
+format), plus o_bf16 == RNE(o_f32) bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as A
+from paper_2512_12928_amd import binding as B
+from paper_2512_12928_amd import workloads as W
+from gpu_harness import DEV, Layer, check_close, dev_to_u16, oracle_cache, run_prefilled, u16_to_dev
+from kvlayout import from_device_layout, to_device_layout
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_out(batch, tens, cache):
+    return A.paged_attention(tens.q, cache, batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids)
+
+
+def custom_batch(Hq, Hkv, items, seed, prios=None, M=None):
+    rng = np.random.default_rng(seed)
+    b = W.build_batch(W.LayerShape(Hq, Hkv), items, prios or [1] * len(items), rng, n_device_blocks=M, seed=seed)
+    return b, W.make_tensors(b)
+
+
+def test_cfg1_prefilled_f32():
+    b = W.make_workload(1)
+    t = W.make_tensors(b)
+    got, cache = run_prefilled(b, t)
+    print("cfg1 max err", check_close(got, oracle_out(b, t, cache), False))
+
+
+def test_cfg1_bf16_output_is_rounded_f32_output():
+    b = W.make_workload(1)
+    t = W.make_tensors(b)
+    g32, cache = run_prefilled(b, t, out_f32=True)
+    cache_dev = u16_to_dev(to_device_layout(cache.pool))
+    lay = Layer(b, out_f32=False)
+    o16 = lay.step(b, u16_to_dev(t.q), cache_dev)
+    lay.close()
+    bits = dev_to_u16(o16.view(torch.int16))
+    assert np.array_equal(bits, W.f32_to_bf16_bits(g32.astype(np.float32)))
+    check_close(W.bf16_bits_to_f32(bits).astype(np.float64), oracle_out(b, t, cache), True)
+
+
+def test_cfg1_append_path_matches_and_pool_is_bit_exact():
+    b = W.make_workload(1)
+    t = W.make_tensors(b)
+    full = oracle_cache(b, t)
+    pre = oracle_cache(b, t, upto_prefix=True)
+    cache_dev = u16_to_dev(to_device_layout(pre.pool))
+    k_new, v_new = t.new_rows(b)
+    lay = Layer(b)
+    out = lay.step(b, u16_to_dev(t.q), cache_dev, u16_to_dev(k_new), u16_to_dev(v_new))
+    lay.close()
+    check_close(out.cpu().numpy().astype(np.float64), oracle_out(b, t, full), False)
+    # the append is a copy: the whole pool (NaN-filled elsewhere) must equal the oracle's bit for bit
+    assert np.array_equal(from_device_layout(dev_to_u16(cache_dev), b.shape.n_kv_heads), full.pool)
+
+
+@pytest.mark.parametrize("chunk", [32, 64, 256])
+def test_split_k_partitions_and_merge(chunk):
+    b = W.make_workload(1)
+    t = W.make_tensors(b)
+    got, cache = run_prefilled(b, t, decode_chunk=chunk)
+    check_close(got, oracle_out(b, t, cache), False)
+
+
+@pytest.mark.parametrize("idx,scale", [(2, 0.08), (4, 0.04), (5, 0.06)])
+def test_scaled_workloads(idx, scale):
+    b = W.make_workload(idx, scale=scale)
+    t = W.make_tensors(b)
+    got, cache = run_prefilled(b, t)
+    print(b.name, "n_req", b.n_req, "tokens", b.n_tokens, "max err", check_close(got, oracle_out(b, t, cache), False))
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (2, 1), (4, 1), (8, 1), (16, 1), (6, 2), (12, 4)])
+def test_group_sizes(Hq, Hkv):
+    items = [(1, 1), (1, 16), (1, 33), (1, 300), (7, 7), (40, 77), (1, 1)]
+    b, t = custom_batch(Hq, Hkv, items, seed=100 + Hq)
+    got, cache = run_prefilled(b, t, decode_chunk=64)
+    check_close(got, oracle_out(b, t, cache), False)
+
+
+def test_ragged_and_degenerate_shapes():
+    # kv_len 1; one-token prompt (l_q = 1, p = 0: o == v_0); lengths on and off block / tile
+    # boundaries; chunks whose prefix is not a multiple of 16 or 32; chunk sizes that leave a
+    # ragged last query tile
+    items = [(1, 1), (1, 15), (1, 16), (1, 17), (1, 31), (1, 32), (1, 33), (1, 511), (1, 512), (1, 513),
+             (2, 2), (33, 33), (95, 95 + 13), (64, 64 + 48), (31, 31 + 16), (129, 129 + 7), (5, 700)]
+    b, t = custom_batch(8, 2, items, seed=7)
+    got, cache = run_prefilled(b, t)
+    want = oracle_out(b, t, cache)
+    check_close(got, want, False)
+    # single visible key: output is exactly v_0 of the matching kv-head (P = 1 exactly)
+    v0 = A.bf16_to_f64(t.v[0])[0]
+    assert np.array_equal(got[0], np.repeat(v0, 4, axis=0))
+
+
+def test_block_relabelling_is_bit_identical():
+    b = W.make_workload(1)
+    t = W.make_tensors(b)
+    g1, _ = run_prefilled(b, t)
+    rng = np.random.default_rng(3)
+    relabel = rng.permutation(b.n_device_blocks).astype(np.int32)
+    b2 = W.MixedBatch(**{**b.__dict__, "block_ids": relabel[b.block_ids]})
+    g2, _ = run_prefilled(b2, t)
+    assert np.array_equal(g1, g2)
+
+
+def test_chunk_split_invariance_on_gpu():
+    """64-token chunk == 32 + 32 (second with prefix 32) == 63 prefill + 1 decode, within tolerance."""
+    b = W.make_workload(1)
+    t = W.make_tensors(b)
+    whole, cache = run_prefilled(b, t)
+    rows = whole[int(b.q_start[4]):int(b.q_start[5])]
+    want = oracle_out(b, t, cache)[int(b.q_start[4]):]
+    for cut in (32, 63):
+        shape = b.shape
+        # same physical table for the chunk request, processed as two requests sharing its blocks is not
+        # allowed (a block belongs to one request), so run two steps over the same cache instead
+        tab = b.table(4)
+        cache_dev = u16_to_dev(to_device_layout(cache.pool))
+        outs = []
+        for (lo, hi) in ((0, cut), (cut, 64)):
+            nb = -(-hi // 16)
+            bb = W.MixedBatch(shape=shape, n_device_blocks=b.n_device_blocks, q_start=np.array([0, hi - lo], np.int32),
+                              kv_len=np.array([hi], np.int32), bt_start=np.array([0, nb], np.int32),
+                              block_ids=tab[:nb].copy(), prio=np.array([1], np.uint8))
+            lay = Layer(bb)
+            q = t.q[int(b.q_start[4]) + lo:int(b.q_start[4]) + hi]
+            outs.append(lay.step(bb, u16_to_dev(q), cache_dev).cpu().numpy().astype(np.float64))
+            lay.close()
+        got = np.concatenate(outs)
+        check_close(got, want, False)
+        assert np.abs(got - rows).max() < 2e-3
+
+
+def test_empty_batch_and_validation_errors():
+    b = W.make_workload(1)
+    t = W.make_tensors(b)
+    lay = Layer(b)
+    ws = lay.workspace(b)
+    cache_dev = u16_to_dev(to_device_layout(oracle_cache(b, t).pool))
+    q = u16_to_dev(t.q)
+    out = torch.zeros((b.n_tokens, 8, 128), dtype=torch.float32, device=DEV)
+    empty = W.MixedBatch(shape=b.shape, n_device_blocks=64, q_start=np.zeros(1, np.int32), kv_len=np.zeros(0, np.int32),
+                         bt_start=np.zeros(1, np.int32), block_ids=np.zeros(0, np.int32), prio=np.zeros(0, np.uint8))
+    B.ps_step(lay.ctx, empty, q, None, None, cache_dev, out, ws, lay.ws_bytes)   # successful no-op
+
+    def expect(code, **chg):
+        d = {**b.__dict__}
+        d.update(chg)
+        with pytest.raises(B.PsError) as e:
+            B.ps_step(lay.ctx, W.MixedBatch(**d), q, None, None, cache_dev, out, ws, lay.ws_bytes)
+        assert e.value.code == code, str(e.value)
+
+    bad = b.block_ids.copy(); bad[5] = 64
+    expect(B.PS_EINVAL, block_ids=bad)
+    bad = b.block_ids.copy(); bad[0] = -1
+    expect(B.PS_EINVAL, block_ids=bad)
+    kv = b.kv_len.copy(); kv[0] = 33
+    expect(B.PS_EINVAL, kv_len=kv)                       # table length no longer matches
+    qs = b.q_start.copy(); qs[1] = 0
+    expect(B.PS_EINVAL, q_start=qs)                      # l_q = 0
+    kv = b.kv_len.copy(); kv[4] = 63
+    expect(B.PS_EINVAL, kv_len=kv)                       # l_q > kv_len
+    with pytest.raises(B.PsError) as e:
+        B.ps_step(lay.ctx, b, q, None, None, cache_dev, out, ws, 1024)
+    assert e.value.code == B.PS_ENOMEM
+    with pytest.raises(B.PsError) as e:
+        B.ps_step(lay.ctx, b, q, q, None, cache_dev, out, ws, lay.ws_bytes)
+    assert e.value.code == B.PS_EINVAL
+    with pytest.raises(B.PsError) as e:
+        B.ps_step(lay.ctx, b, q, None, None, cache_dev, out, ws, lay.ws_bytes, None, 12345)
+    assert e.value.code == B.PS_ESTATE
+    # after all the rejected calls a good one still works
+    B.ps_step(lay.ctx, b, q, None, None, cache_dev, out, ws, lay.ws_bytes)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    lay.close()
+
+
+def test_profiling_times_are_reported():
+    b = W.make_workload(2, scale=0.08)
+    t = W.make_tensors(b)
+    cache = oracle_cache(b, t)
+    lay = Layer(b)
+    B.ps_set_profiling(lay.ctx, True)
+    lay.step(b, u16_to_dev(t.q), u16_to_dev(to_device_layout(cache.pool)))
+    tm = B.ps_get_step_times(lay.ctx)
+    assert tm["total_ms"] > 0 and tm["decode_ms"] > 0 and tm["prefill_ms"] > 0
+    lay.close()

@@ -1,0 +1,127 @@
+"""GPU parity of ps_swap_out / ps_swap_in against the block-copy oracle: bit-exact blocks, whole-pool
+checks for stray writes, budget semantics, tickets, and reload -> attention ordering."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as A
+from oracle import blockcopy as C
+from paper_2512_12928_amd import binding as B
+from paper_2512_12928_amd import workloads as W
+from gpu_harness import DEV, Layer, check_close, dev_to_u16, oracle_cache, u16_to_dev
+from kvlayout import to_device_layout
+
+pytestmark = pytest.mark.gpu
+
+
+def pools(shape, M, Mh, seed):
+    rng = np.random.default_rng(seed)
+    bb = shape.block_bytes
+    dev = rng.integers(0, 256, (M, bb), dtype=np.uint8)
+    host = rng.integers(0, 256, (Mh, bb), dtype=np.uint8)
+    return dev, host
+
+
+@pytest.mark.parametrize("Hkv,n,budget", [(2, 5, -1), (8, 37, -1), (8, 37, 10), (8, 37, 0), (8, 37, 100), (1, 3, 2), (8, 600, -1)])
+def test_swap_out_then_in_matches_oracle(Hkv, n, budget):
+    shape = W.LayerShape(Hkv * 4, Hkv)
+    M, Mh = 700, 900
+    dev_np, host_np = pools(shape, M, Mh, n)
+    dev = torch.from_numpy(dev_np).to(DEV)
+    host = torch.from_numpy(host_np.copy()).pin_memory()
+    rng = np.random.default_rng(n + 1)
+    d_ids, h_ids = W.make_swap_lists(n, M, Mh, rng)
+    ctx = B.ps_create(shape.n_q_heads, Hkv, M, Mh)
+    side = torch.cuda.Stream()
+    nd, tk = B.ps_swap_out(ctx, d_ids, h_ids, budget, dev, host, side)
+    want_host = host_np.copy()
+    assert nd == C.swap_out(dev_np, want_host, d_ids, h_ids, budget)
+    if nd:
+        B.ps_ticket_wait(ctx, tk)
+        assert B.ps_ticket_query(ctx, tk) == B.PS_OK
+    else:
+        assert tk == 0
+    assert np.array_equal(host.numpy(), want_host)              # every byte of the host pool, listed or not
+    assert np.array_equal(dev.cpu().numpy(), dev_np)
+    # reload into different device blocks
+    d2, _ = W.make_swap_lists(n, M, Mh, np.random.default_rng(n + 2))
+    nd2, tk2 = B.ps_swap_in(ctx, h_ids, d2, budget, host, dev, side)
+    want_dev = dev_np.copy()
+    assert nd2 == C.swap_in(want_host, want_dev, h_ids, d2, budget)
+    if nd2:
+        B.ps_ticket_wait(ctx, tk2)
+    torch.cuda.synchronize()
+    assert np.array_equal(dev.cpu().numpy(), want_dev)
+    assert np.array_equal(host.numpy(), want_host)
+    B.ps_destroy(ctx)
+
+
+def test_swap_validation():
+    shape = W.LayerShape(8, 2)
+    M, Mh = 16, 8
+    dev = torch.zeros((M, shape.block_bytes), dtype=torch.uint8, device=DEV)
+    host = torch.zeros((Mh, shape.block_bytes), dtype=torch.uint8).pin_memory()
+    ctx = B.ps_create(8, 2, M, Mh)
+    for d_ids, h_ids in (([0, 16], [0, 1]), ([0, 1], [0, 8]), ([3, 3], [0, 1]), ([0, 1], [2, 2]), ([-1], [0])):
+        with pytest.raises(B.PsError) as e:
+            B.ps_swap_out(ctx, d_ids, h_ids, -1, dev, host)
+        assert e.value.code == B.PS_EINVAL
+    assert B.ps_swap_out(ctx, [], [], -1, dev, host) == (0, 0)
+    with pytest.raises(B.PsError) as e:
+        B.ps_ticket_wait(ctx, 99)
+    assert e.value.code == B.PS_ESTATE
+    B.ps_destroy(ctx)
+
+
+def test_many_tickets_recycle():
+    shape = W.LayerShape(8, 2)
+    M, Mh = 32, 32
+    dev_np, host_np = pools(shape, M, Mh, 5)
+    dev = torch.from_numpy(dev_np).to(DEV)
+    host = torch.from_numpy(host_np.copy()).pin_memory()
+    ctx = B.ps_create(8, 2, M, Mh)
+    side = torch.cuda.Stream()
+    tickets = []
+    for i in range(150):                                       # more than the ticket ring holds
+        nd, tk = B.ps_swap_out(ctx, [i % M], [(7 * i) % Mh], -1, dev, host, side)
+        C.swap_out(dev_np, host_np, [i % M], [(7 * i) % Mh])
+        tickets.append(tk)
+    assert tickets == list(range(1, 151))
+    B.ps_ticket_wait(ctx, tickets[-1])
+    for tk in (tickets[0], tickets[70], tickets[-1]):
+        assert B.ps_ticket_query(ctx, tk) == B.PS_OK
+    assert np.array_equal(host.numpy(), host_np)
+    B.ps_destroy(ctx)
+
+
+def test_reload_then_attention_waits_for_ticket():
+    """Evict a request's blocks to the host, poison the device copies, reload them into fresh blocks on
+    a side stream and run attention on the compute stream with the ticket: same output as never swapping."""
+    b = W.make_workload(2, scale=0.08)
+    t = W.make_tensors(b)
+    cache = oracle_cache(b, t)
+    want = A.paged_attention(t.q, cache, b.q_start, b.kv_len, b.bt_start, b.block_ids)
+    used = set(b.block_ids.tolist())
+    free = np.array([i for i in range(b.n_device_blocks) if i not in used], dtype=np.int32)
+    victim = int(np.argmax(b.kv_len))                           # longest request
+    tab = b.table(victim).copy()
+    assert len(free) >= len(tab)
+    Mh = len(tab) + 3
+    lay = Layer(b, n_host_blocks=Mh)
+    flat = to_device_layout(cache.pool)
+    cache_dev = u16_to_dev(flat)
+    host = torch.zeros((Mh, b.shape.block_bytes), dtype=torch.uint8).pin_memory()
+    side = torch.cuda.Stream()
+    slots = np.arange(len(tab), dtype=np.int32)[::-1].copy()
+    nd, tk = B.ps_swap_out(lay.ctx, tab, slots, -1, cache_dev, host, side)
+    B.ps_ticket_wait(lay.ctx, tk)
+    cache_dev.view(-1, flat.shape[1])[torch.from_numpy(tab.astype(np.int64)).to(DEV)] = 0x7FC0  # bf16 NaN bits
+    new_tab = free[:len(tab)]
+    ids = b.block_ids.copy()
+    ids[int(b.bt_start[victim]):int(b.bt_start[victim + 1])] = new_tab
+    b2 = W.MixedBatch(**{**b.__dict__, "block_ids": ids})
+    nd, tk = B.ps_swap_in(lay.ctx, slots, new_tab, -1, host, cache_dev, side)
+    assert nd == len(tab)
+    out = lay.step(b2, u16_to_dev(t.q), cache_dev, stream=torch.cuda.current_stream(), wait_ticket=tk)
+    check_close(out.cpu().numpy().astype(np.float64), want, False)
+    lay.close()
