@@ -1,0 +1,296 @@
+#!/usr/bin/env python3
+"""Benchmark of the engine-step hot path on one MI355X.
+
+A step is one pass of the hot path over one synthetic mixed batch: host batch description ->
+device, KV append, split-K decode attention + merge, prefill-chunk attention (ps_step).  The
+headline workload is the Qwen3-8B-shaped layer (256 decode requests + 2048 prefill tokens in 4
+chunks).  Prints ONE JSON line; see the design doc for the fields.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="workload index 1..5 (2 = headline)")
+    ap.add_argument("--decode-chunk", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads / swap figures")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2512_12928_amd import binding as B
+    from paper_2512_12928_amd import workloads as W
+    from paper_2512_12928_amd.kvlayout import request_kv
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def device_inputs(batch, seed):
+        s = batch.shape
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        pool_elems = batch.n_device_blocks * (s.block_bytes // 2)
+        pool = torch.empty(pool_elems, dtype=torch.bfloat16, device=dev)
+        step = 1 << 28
+        for a in range(0, pool_elems, step):       # N(0,1) in fp32, rounded to bf16, in slabs
+            n = min(step, pool_elems - a)
+            pool[a:a + n] = torch.randn(n, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        q = torch.randn((batch.n_tokens, s.n_q_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
+        kn = torch.randn((batch.n_tokens, s.n_kv_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
+        vn = torch.randn((batch.n_tokens, s.n_kv_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
+        return pool.view(batch.n_device_blocks, -1), q, kn, vn
+
+    def algorithmic(batch):
+        s = batch.shape
+        dec = batch.decode_reqs
+        kv_bytes = int(batch.kv_len[dec].astype(np.int64).sum()) * s.n_kv_heads * s.head_dim * 2 * 2
+        qo_bytes = len(dec) * 2 * s.n_q_heads * s.head_dim * 2
+        tab_bytes = int(sum(4 * -(-int(batch.kv_len[r]) // s.block_tokens) for r in dec))
+        flops = 4 * s.head_dim * s.n_q_heads * batch.causal_pairs()
+        return kv_bytes + qo_bytes + tab_bytes, flops
+
+    def run(batch, steps, warmup, decode_chunk=0, profile_steps=20):
+        s = batch.shape
+        pool, q, kn, vn = device_inputs(batch, batch.seed)
+        ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, 0, out_dtype=B.PS_BF16,
+                          decode_chunk=decode_chunk)
+        nbytes = B.ps_workspace_bytes(ctx, batch.n_req, batch.n_tokens, len(batch.block_ids))
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        out = torch.empty((batch.n_tokens, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+        cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
+        stream = torch.cuda.current_stream()
+        for _ in range(warmup):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        # per-kernel durations: HIP events recorded by the library on the launch stream
+        B.ps_set_profiling(ctx, True)
+        acc = {}
+        for _ in range(profile_steps):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+            for k, v in B.ps_get_step_times(ctx).items():
+                acc[k] = acc.get(k, 0.0) + v / profile_steps
+        B.ps_set_profiling(ctx, False)
+        res = dict(ms_per_step=dt / steps * 1e3, phases_ms=acc, ctx=ctx, pool=pool, q=q, out=out, kn=kn, vn=vn)
+        return res
+
+    def rooflines(batch, res):
+        bytes_dec, flops_pre = algorithmic(batch)
+        ph = res["phases_ms"]
+        dec_s = (ph["decode_ms"] + ph["merge_ms"]) * 1e-3
+        pre_s = ph["prefill_ms"] * 1e-3
+        dec_gbs = bytes_dec / dec_s / 1e9 if dec_s > 0 else 0.0
+        pre_tf = flops_pre / pre_s / 1e12 if pre_s > 0 else 0.0
+        return dict(decode_GBps=dec_gbs, decode_frac=dec_gbs / HBM_PEAK_GBS, prefill_TFLOPs=pre_tf,
+                    prefill_frac=pre_tf / MFMA_BF16_PEAK_TFLOPS, decode_bytes=bytes_dec, prefill_flops=flops_pre,
+                    decode_ms=ph["decode_ms"], merge_ms=ph["merge_ms"], prefill_ms=ph["prefill_ms"],
+                    append_ms=ph["append_ms"], upload_ms=ph["upload_ms"])
+
+    batch = W.make_workload(args.workload)
+    res = run(batch, args.steps, args.warmup, args.decode_chunk)
+    rl = rooflines(batch, res)
+    tokens_per_s = batch.n_tokens / (res["ms_per_step"] * 1e-3)
+
+    # ---- CPU baseline: the fp64 oracle, as it stands, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import attention as A
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        s = batch.shape
+        torch.cuda.synchronize()
+        dec = [int(r) for r in batch.decode_reqs[:24]]
+        pre = [int(r) for r in batch.prefill_reqs[:1]]
+        sample = dec + pre
+        q_host = res["q"].view(torch.int16).cpu().numpy().view(np.uint16)
+        pairs = 0
+        t_cpu = 0.0
+        for r in sample:
+            tab = torch.from_numpy(batch.table(r).astype(np.int64)).to(dev)
+            blocks = res["pool"][tab].view(torch.int16).cpu().numpy().view(np.uint16)
+            L, lq = int(batch.kv_len[r]), batch.l_q(r)
+            k_bits, v_bits = request_kv(blocks, s.n_kv_heads, L)
+            a = int(batch.q_start[r])
+            rows = min(lq, 128)                      # first 128 rows of the prefill chunk
+            t1 = time.perf_counter()
+            qf = A.bf16_to_f64(q_host[a:a + rows])
+            kf, vf = A.bf16_to_f64(k_bits[:L - lq + rows]), A.bf16_to_f64(v_bits[:L - lq + rows])
+            ref = A.dense_attention(qf, kf, vf)
+            t_cpu += time.perf_counter() - t1
+            p = L - lq
+            pairs += rows * p + rows * (rows + 1) // 2
+            got = res["out"][a:a + rows].float().cpu().numpy().astype(np.float64)
+            err = np.abs(got - ref)
+            assert (err <= 1e-2 + 2.0 ** -8 * np.abs(ref)).all(), "bench sample disagrees with the oracle"
+        total_pairs = batch.decode_kv_tokens() + batch.causal_pairs()
+        est_step_s = t_cpu * total_pairs / max(pairs, 1)
+        cpu = dict(value=batch.n_tokens / est_step_s, unit="tokens/s", cores=int(cores), kind="oracle",
+                   sample="%d decode requests + first %d rows of 1 prefill chunk of %s: %.2f s of numpy fp64; "
+                          "scaled to the whole batch by (query,key) pair count" % (len(dec), 128, batch.name, t_cpu))
+
+    extra = {}
+    if not args.no_extra:
+        extra["workload_%d" % args.workload] = rl
+        B.ps_destroy(res.pop("ctx"))
+        for k in ("pool", "q", "out", "kn", "vn"):
+            res.pop(k, None)
+        torch.cuda.empty_cache()
+        for idx in (4, 5):
+            if idx == args.workload:
+                continue
+            bb = W.make_workload(idx)
+            rr = run(bb, 20, 5, args.decode_chunk, profile_steps=10)
+            e = rooflines(bb, rr)
+            e["ms_per_step"] = rr["ms_per_step"]
+            e["tokens_per_s"] = bb.n_tokens / (rr["ms_per_step"] * 1e-3)
+            extra["workload_%d" % idx] = e
+            B.ps_destroy(rr.pop("ctx"))
+            del rr
+            torch.cuda.empty_cache()
+        extra["swap"] = swap_bench(B, W, torch, np, dev)
+
+    dominant_decode = rl["decode_ms"] + rl["merge_ms"] >= rl["prefill_ms"]
+    if dominant_decode:
+        roof = dict(bound="hbm", kernel="decode_kernel(+merge)", achieved=rl["decode_GBps"], peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=rl["decode_frac"], traffic=None)
+    else:
+        roof = dict(bound="mfma", kernel="prefill_kernel", achieved=rl["prefill_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=rl["prefill_frac"], traffic=None)
+    line = {
+        "metric": "mixed-batch paged-attn tokens/s per layer", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": batch.name, "n_decode": int(len(batch.decode_reqs)),
+                   "n_prefill_tokens": int(batch.n_tokens - len(batch.decode_reqs)),
+                   "decode_kv_tokens": batch.decode_kv_tokens(), "heads": "%dq/%dkv" % (batch.shape.n_q_heads, batch.shape.n_kv_heads)},
+        "roofline": roof, "cpu_baseline": cpu, "extra": extra,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+def swap_bench(B, W, torch, np, dev):
+    """Workload 3: 512 blocks out and 512 in per step on a side stream, alone and under attention."""
+    import time as _t
+    batch = W.make_workload(3)
+    s = batch.shape
+    Mh = 4096
+    bb = s.block_bytes
+    g = torch.Generator(device=dev)
+    g.manual_seed(3)
+    pool = torch.empty((batch.n_device_blocks, bb // 2), dtype=torch.bfloat16, device=dev).normal_(generator=g)
+    host = torch.empty((Mh, bb), dtype=torch.uint8).pin_memory()
+    host.zero_()
+    # measured host link: one large pinned copy each way
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    hbig = torch.empty(1 << 30, dtype=torch.uint8).pin_memory()
+    link = {}
+    for name, (dst, src) in (("d2h", (hbig, big)), ("h2d", (big, hbig))):
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        t0 = _t.perf_counter()
+        for _ in range(3):
+            dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        link[name] = 3 * (1 << 30) / (_t.perf_counter() - t0) / 1e9
+    del big, hbig
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, Mh)
+    rng = np.random.default_rng(33)
+    used = batch.block_ids
+    out_ids, out_slots = W.make_swap_lists(512, batch.n_device_blocks, Mh, rng, exclude_device=used)
+    free = np.setdiff1d(np.arange(batch.n_device_blocks, dtype=np.int32), np.concatenate([used, out_ids]))
+    in_ids = rng.permutation(free)[:512].astype(np.int32)
+    in_slots = np.setdiff1d(np.arange(Mh, dtype=np.int32), out_slots)[:512].astype(np.int32)
+    side_out, side_in = torch.cuda.Stream(), torch.cuda.Stream()
+    nbytes = B.ps_workspace_bytes(ctx, batch.n_req, batch.n_tokens, len(batch.block_ids))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    q = torch.randn((batch.n_tokens, s.n_q_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
+    res = {"link_d2h_GBps": link["d2h"], "link_h2d_GBps": link["h2d"]}
+
+    def swaps(n_iter):
+        tk = 0
+        for _ in range(n_iter):
+            _, t1 = B.ps_swap_out(ctx, out_ids, out_slots, -1, pool, host, side_out)
+            _, t2 = B.ps_swap_in(ctx, in_slots, in_ids, -1, host, pool, side_in)
+            tk = (t1, t2)
+        return tk
+
+    def attn(n_iter):
+        for _ in range(n_iter):
+            B.ps_step(ctx, cb, q, None, None, pool, out, ws, nbytes, torch.cuda.current_stream())
+
+    n_iter = 20
+    moved = n_iter * 512 * bb
+    # swaps alone (both directions concurrently)
+    swaps(2); torch.cuda.synchronize()
+    t0 = _t.perf_counter(); swaps(n_iter); torch.cuda.synchronize(); dt = _t.perf_counter() - t0
+    res["alone_each_way_GBps"] = moved / dt / 1e9
+    # one direction at a time
+    for name, fn in (("out", lambda: B.ps_swap_out(ctx, out_ids, out_slots, -1, pool, host, side_out)),
+                     ("in", lambda: B.ps_swap_in(ctx, in_slots, in_ids, -1, host, pool, side_in))):
+        fn(); torch.cuda.synchronize()
+        t0 = _t.perf_counter()
+        for _ in range(n_iter):
+            fn()
+        torch.cuda.synchronize()
+        res["alone_%s_only_GBps" % name] = moved / (_t.perf_counter() - t0) / 1e9
+    # attention alone
+    attn(5); torch.cuda.synchronize()
+    n_att = 200
+    t0 = _t.perf_counter(); attn(n_att); torch.cuda.synchronize(); t_att = (_t.perf_counter() - t0) / n_att
+    res["attn_ms_swaps_off"] = t_att * 1e3
+    # overlapped: keep attention running on the compute stream for as long as the swaps take
+    torch.cuda.synchronize()
+    t0 = _t.perf_counter()
+    swaps(n_iter)
+    n_done = 0
+    ev_out, ev_in = torch.cuda.Event(), torch.cuda.Event()
+    ev_out.record(side_out); ev_in.record(side_in)
+    while not (ev_out.query() and ev_in.query()):
+        attn(10)
+        n_done += 10
+        torch.cuda.current_stream().synchronize()
+    ev_out.synchronize(); ev_in.synchronize()
+    dt_swap = _t.perf_counter() - t0
+    torch.cuda.synchronize()
+    dt_all = _t.perf_counter() - t0
+    res["overlap_each_way_GBps"] = moved / dt_swap / 1e9
+    res["overlap_frac_of_link"] = min(res["overlap_each_way_GBps"] / link["d2h"], res["overlap_each_way_GBps"] / link["h2d"])
+    res["attn_ms_swaps_on"] = dt_all / max(n_done, 1) * 1e3
+    B.ps_destroy(ctx)
+    return res
+
+
+if __name__ == "__main__":
+    sys.exit(main())

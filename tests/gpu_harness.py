@@ -6,7 +6,7 @@ import torch
 from oracle import attention as A
 from paper_2512_12928_amd import binding as B
 from paper_2512_12928_amd import workloads as W
-from kvlayout import from_device_layout, to_device_layout
+from paper_2512_12928_amd.kvlayout import from_device_layout, to_device_layout
 
 DEV = "cuda:0"
 

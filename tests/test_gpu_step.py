@@ -10,7 +10,7 @@ from oracle import attention as A
 from paper_2512_12928_amd import binding as B
 from paper_2512_12928_amd import workloads as W
 from gpu_harness import DEV, Layer, check_close, dev_to_u16, oracle_cache, run_prefilled, u16_to_dev
-from kvlayout import from_device_layout, to_device_layout
+from paper_2512_12928_amd.kvlayout import from_device_layout, to_device_layout
 
 pytestmark = pytest.mark.gpu
 

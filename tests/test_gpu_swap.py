@@ -9,7 +9,7 @@ from oracle import blockcopy as C
 from paper_2512_12928_amd import binding as B
 from paper_2512_12928_amd import workloads as W
 from gpu_harness import DEV, Layer, check_close, dev_to_u16, oracle_cache, u16_to_dev
-from kvlayout import to_device_layout
+from paper_2512_12928_amd.kvlayout import to_device_layout
 
 pytestmark = pytest.mark.gpu
 
