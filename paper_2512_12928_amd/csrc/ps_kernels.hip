@@ -253,16 +253,18 @@ __global__ __launch_bounds__(128) void merge_kernel(StepParams P) {
 }
 
 // ------------------------------------------------------------------------------------ prefill
-// Causal attention of prefill chunks on 32x32x16 bf16 MFMA.  1-D grid, 256 threads = 4 waves.
-// A workgroup owns a tile of query tokens of one request for one kv-head and HW of its G query
-// heads; wave w owns kPrefillRows = 64 consecutive query tokens (two 32-column B tiles) of head
-// z*HW + w % HW, token sub-tile w / HW.  All four waves walk the same 32-token KV tiles.
+// Causal attention of prefill chunks on 32x32x16 bf16 MFMA.  1-D grid, 512 threads = 8 waves,
+// i.e. two waves per SIMD: on this chip a wave cannot overlap its own VALU work (softmax) with
+// its own MFMAs, two waves sharing a SIMD can, so each wave keeps its state within 256
+// registers.  A workgroup owns a tile of query tokens of one request for one kv-head and HW of
+// its G query heads; wave w owns 32 consecutive query tokens (one 32-column B tile) of head
+// z*HW + w % HW, token sub-tile w / HW.  All eight waves walk the same 32-token KV tiles.
 //
 // KV tiles go from the cache straight into LDS (global_load_lds_dwordx4, no VGPR round trip),
 // in MFMA operand order: fragment f of a tile is the 1 KiB that the 64 lanes of a wave feed to
 // one MFMA as its A operand, lane after lane, so it is read back with one conflict-free 16-byte
 // ds_read per lane.  A tile is 8 K fragments (dim chunks) + 8 V fragments (block u, 32 dims);
-// wave w fetches K and V fragments 2w, 2w+1.  The LDS ring holds kStages tiles; loads run
+// wave w fetches K fragment w and V fragment w.  The LDS ring holds kStages tiles; loads run
 // kStages-1 tiles ahead of the compute, one barrier per tile.
 //
 // Row i of a K fragment is token pi(i) of the tile (bits 2 and 3 of i swapped).  With the
@@ -273,8 +275,10 @@ __global__ __launch_bounds__(128) void merge_kernel(StepParams P) {
 // Workgroup -> work mapping: consecutive workgroup ids go to consecutive XCDs (8 of them, each
 // with its own L2), so the kv-head is taken from the low bits of the id: the workgroups that
 // share one XCD's L2 then walk the same K/V stream.
-constexpr int kPrefillRows = 64;  // query tokens per wave
-constexpr int kStages = 5;
+constexpr int kPrefillWaves = 8;
+constexpr int kPrefillRows = 32;  // query tokens per wave
+constexpr int kStages = 4;
+constexpr int kLoadsPerTile = 2;  // global->LDS loads each wave issues per tile
 
 // s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding)
 #define PS_VMCNT(n) (((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
@@ -293,25 +297,21 @@ __device__ __forceinline__ void load_ids(const int* pa, const int* pb, int& a, i
                : "s"(pa), "s"(pb));
 }
 
-// 32x32x16 bf16 MFMAs with the register file of each operand chosen by hand.  The compiler, left to
-// itself at this register pressure, shuttles the 128 output accumulators between the VGPR and
-// AGPR files on every tile.  Here the O^T accumulators live in VGPRs (the rare rescale is plain
-// VALU work), the Q^T operands (loaded once) and the raw scores of the NEXT tile live in AGPRs;
-// the scores move to VGPRs when they become the current tile.
-// The compiler does not see these as MFMAs and so inserts no hazard NOPs around them; every
-// consumer of a result below is separated from its producer by far more than the 19 wait
-// states the ISA asks for (noted at each use).
-#define PS_MFMA_SCORES_FIRST(s, k, q) \
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=a"(s) : "v"(k), "a"(q))
-#define PS_MFMA_SCORES(s, k, q) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(s) : "v"(k), "a"(q))
-#define PS_MFMA_OUT(o, v, p) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(o) : "v"(v), "v"(p))
+// max over lanes l and l ^ 32 (both lanes get it), on the VALU: v_permlane32_swap exchanges the upper
+// half of its first operand with the lower half of its second.
+__device__ __forceinline__ float xor32_max(float x) {
+  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+  asm volatile("" : "+v"(b));  // two distinct registers for the swap
+  auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+}
 
 struct PrefillStage {
   uint4 k[8][64];
   uint4 v[8][64];
 };
 
-__global__ __launch_bounds__(256) void prefill_kernel(StepParams P, int HW, int n_zsplit) {
+__global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams P, int HW, int n_zsplit) {
   __shared__ PrefillStage sm[kStages];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(StepParams P, int HW, int 
   const int z = (bid / Hkv) % n_zsplit;
   const PrefillTile t = P.ptiles[bid / (Hkv * n_zsplit)];
   const int head = g * G + z * HW + wave % HW;
-  const int SUB = 4 / HW;
+  const int SUB = kPrefillWaves / HW;
   const int r = t.req;
   const int qs = P.q_start[r];
   const int lq = P.q_start[r + 1] - qs;
@@ -334,32 +334,27 @@ __global__ __launch_bounds__(256) void prefill_kernel(StepParams P, int HW, int 
   const int* table = P.block_ids + P.bt_start[r];
   const int nblk = (L + kBlockTokens - 1) >> 4;
 
-  // Q^T operands: lane (query j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.
-  bf16x8 qop[2][8];
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    int row = q0 + nb * 32 + j;
+  // Q^T operand: lane (query j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.
+  bf16x8 qop[8];
+  {
+    int row = q0 + j;
     row = row < lq ? row : lq - 1;
     const uint16_t* qrow = P.q + ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) qop[nb][c] = as_bf16x8(*(const uint4*)(qrow + (c * 2 + h2) * 8));
+    for (int c = 0; c < 8; ++c) qop[c] = as_bf16x8(*(const uint4*)(qrow + (c * 2 + h2) * 8));
   }
 
-  float m[2], l[2];
-  f32x16 acc[2][4];
+  float m = PS_NEG_INF, l = 0.f;
+  f32x16 acc[4];
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    m[nb] = PS_NEG_INF;
-    l[nb] = 0.f;
+  for (int n = 0; n < 4; ++n)
 #pragma unroll
-    for (int n = 0; n < 4; ++n)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[nb][n][e] = 0.f;
-  }
+    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
 
   const int wg_last = (t.q0 + SUB * kPrefillRows < lq ? t.q0 + SUB * kPrefillRows : lq) - 1;
   const int ntiles = (p + wg_last) / kTileTokens + 1;                            // workgroup-uniform
   const int my_last = p + (q0 + kPrefillRows < lq ? q0 + kPrefillRows : lq) - 1;  // last visible key
+  const int qpos = p + q0 + j;
 
   // K row j of a fragment is token pi(j): block j>>4, slot 8*bit2(j) + 4*bit3(j) + (j&3)
   const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
@@ -372,19 +367,18 @@ __global__ __launch_bounds__(256) void prefill_kernel(StepParams P, int HW, int 
     const int bA = (tile * kTileTokens) >> 4;
     load_ids(table + bA, table + (bA + 1 < nblk ? bA + 1 : bA), idA, idB);
   };
-  // Issues this wave's 4 loads of one tile into ring slot `stage`.  Every call issues exactly 4
-  // (past the end the last tile is fetched again): the vmcnt bookkeeping below counts on it.
+  // Issues this wave's loads of one tile into ring slot `stage`: K fragment `wave` (dim chunk) and
+  // V fragment `wave` (block wave/4, dims 32*(wave%4)..).  Every call issues exactly
+  // kLoadsPerTile loads (past the end the last tile is fetched again): the vmcnt bookkeeping
+  // below counts on it.
   auto issue = [&](int stage, int idA, int idB) {
     const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + kslot * kHeadDim;
     const uint32_t st = sm_base + (uint32_t)stage * (uint32_t)sizeof(PrefillStage);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int f = 2 * wave + i;
-      load_to_lds16(krow + (f * 2 + h2) * 8, st + (uint32_t)f * 1024u);
-      const int u = f >> 2, n = f & 3;
-      const uint16_t* vs = v_slice(P.cache, u == 0 ? idA : idB, Hkv, g) + (n * 32 + j) * kBlockTokens + 8 * h2;
-      load_to_lds16(vs, st + 8192u + (uint32_t)f * 1024u);
-    }
+    const int f = wave;
+    load_to_lds16(krow + (f * 2 + h2) * 8, st + (uint32_t)f * 1024u);
+    const int u = f >> 2, n = f & 3;
+    const uint16_t* vs = v_slice(P.cache, u == 0 ? idA : idB, Hkv, g) + (n * 32 + j) * kBlockTokens + 8 * h2;
+    load_to_lds16(vs, st + 8192u + (uint32_t)f * 1024u);
   };
 
   // The Q loads above must be complete, and known to the compiler to be complete, before the ring
@@ -402,35 +396,13 @@ __global__ __launch_bounds__(256) void prefill_kernel(StepParams P, int HW, int 
   }
   lookup(kStages - 1, idA, idB);  // ids of the tile the first iteration will issue
 
-  // Software pipeline inside the wave: while the VALU turns the raw scores of tile t into
-  // probabilities, the matrix pipe already computes the raw scores of tile t+1.
-  f32x16 s_cur[2];
-  __builtin_amdgcn_s_waitcnt(PS_VMCNT(4 * (kStages - 2)));  // own loads of tile 0 have landed
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  {
-    bf16x8 kf[8];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) kf[c] = as_bf16x8(sm[0].k[c][lane]);
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) PS_MFMA_SCORES_FIRST(s_cur[nb], kf[0], qop[nb][0]);
-#pragma unroll
-    for (int c = 1; c < 8; ++c)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) PS_MFMA_SCORES(s_cur[nb], kf[c], qop[nb][c]);
-    // s_cur is first read by the VALU after the barrier and address arithmetic of iteration 0;
-    // make the distance explicit
-    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-  }
-
   for (int tile = 0; tile < ntiles; ++tile) {
     const int stage = tile % kStages;
     const int ts = tile * kTileTokens;
-    // own loads of tile+1 have landed (the 4*(kStages-3) younger ones may still fly) ...
-    __builtin_amdgcn_s_waitcnt(PS_VMCNT(4 * (kStages - 3)));
+    // own loads of this tile have landed (the younger ones may still fly) ...
+    __builtin_amdgcn_s_waitcnt(PS_VMCNT(kLoadsPerTile * (kStages - 2)));
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();  // ... and everybody's; everyone is done with V of tile-1
+    __builtin_amdgcn_s_barrier();  // ... and so have everybody's; everyone is done with tile-1
     asm volatile("" ::: "memory");
     issue((tile + kStages - 1) % kStages, idA, idB);  // tile + kStages-1 refills the slot of tile-1
     lookup(tile + kStages, idA, idB);                  // ids for the next iteration's issue
@@ -438,126 +410,85 @@ __global__ __launch_bounds__(256) void prefill_kernel(StepParams P, int HW, int 
     if (ts + kTileTokens > L) {
       // Last tile of the request: slots past kv_len may hold anything.  The wave that fetched a V
       // fragment zeroes those slots in LDS before anyone multiplies by them (0 * NaN is NaN).
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int f = 2 * wave + i, u = f >> 2;
-        const int first = ts + 16 * u + 8 * h2;
-        const uint4 vv = sm[stage].v[f][lane];
-        const uint2 lo = zero_from(make_uint2(vv.x, vv.y), first, L);
-        const uint2 hi = zero_from(make_uint2(vv.z, vv.w), first + 4, L);
-        sm[stage].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      }
+      const int f = wave, u = f >> 2;
+      const int first = ts + 16 * u + 8 * h2;
+      const uint4 vv = sm[stage].v[f][lane];
+      const uint2 lo = zero_from(make_uint2(vv.x, vv.y), first, L);
+      const uint2 hi = zero_from(make_uint2(vv.z, vv.w), first + 4, L);
+      sm[stage].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
       __syncthreads();  // workgroup-uniform branch
     }
 
     if (active && ts <= my_last) {
-      // operands of this iteration's 32 MFMAs: K of tile+1, V of tile
-      bf16x8 kf[8], vf[8];
+      const PrefillStage& S = sm[stage];
+      f32x16 s;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) kf[c] = as_bf16x8(sm[(tile + 1) % kStages].k[c][lane]);
+      for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-      for (int f = 0; f < 8; ++f) vf[f] = as_bf16x8(sm[stage].v[f][lane]);
-
-      // s_cur[nb][e]: token ts + 16*(e/8) + 8*h2 + e%8, query q0 + nb*32 + j (raw dot products),
-      // written by the score MFMAs of the previous iteration (16 output MFMAs ago)
+      for (int c = 0; c < 8; ++c)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(S.k[c][lane]), qop[c], s, 0, 0, 0);
+      // s[e]: token ts + 16*(e/8) + 8*h2 + e%8, query q0 + j (raw dot products)
+      if (ts + kTileTokens - 1 > p + q0) {  // diagonal tile (wave-uniform test)
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const int qpos = p + q0 + nb * 32 + j;
-        if (ts + kTileTokens - 1 > p + q0 + nb * 32) {  // diagonal tile (wave-uniform test)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int tok = ts + 16 * (e >> 3) + 8 * h2 + (e & 7);
-            if (tok > qpos) s_cur[nb][e] = PS_NEG_INF;
-          }
-        }
-        float tmax = s_cur[nb][0];
-#pragma unroll
-        for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, s_cur[nb][e]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * P.scale_log2;
-        // m is finite from the first tile on (key 0 is visible to every query); a row that sees
-        // nothing in this tile keeps its m
-        if (__builtin_amdgcn_ballot_w64(tmax > m[nb]) != 0) {  // rescale only when some row's max grew
-          const float m_new = fmaxf(m[nb], tmax);
-          const float alpha = __builtin_amdgcn_exp2f(m[nb] - m_new);
-          l[nb] *= alpha;
-          m[nb] = m_new;
-          // acc was last written by the output MFMAs of the previous iteration, a barrier, the
-          // load issue and the row maxima ago
-#pragma unroll
-          for (int n = 0; n < 4; ++n) acc[nb][n] *= alpha;
+        for (int e = 0; e < 16; ++e) {
+          const int tok = ts + 16 * (e >> 3) + 8 * h2 + (e & 7);
+          if (tok > qpos) s[e] = PS_NEG_INF;
         }
       }
-
-      // 16 score MFMAs of tile+1, interleaved in program order with the exps of this tile
-      f32x16 s_next[2];
-      bf16x8 pop[2][2];
+      float tmax = s[0];
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        if (c == 0) {
-          PS_MFMA_SCORES_FIRST(s_next[0], kf[0], qop[0][0]);
-          PS_MFMA_SCORES_FIRST(s_next[1], kf[0], qop[1][0]);
-        } else {
-          PS_MFMA_SCORES(s_next[0], kf[c], qop[0][c]);
-          PS_MFMA_SCORES(s_next[1], kf[c], qop[1][c]);
-        }
-        const int nb = c >> 2, e0 = (c & 3) * 4;
+      for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, s[e]);
+      tmax = xor32_max(tmax) * P.scale_log2;
+      // m is finite from the first tile on (key 0 is visible to every query); a row that sees
+      // nothing in this tile keeps its m
+      if (__builtin_amdgcn_ballot_w64(tmax > m) != 0) {  // rescale only when some row's max grew
+        const float m_new = fmaxf(m, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        l *= alpha;
+        m = m_new;
 #pragma unroll
-        for (int e = e0; e < e0 + 4; ++e)
-          s_cur[nb][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[nb][e], P.scale_log2, -m[nb]));
-        if ((c & 3) == 3) {
-          float psum = 0.f;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) psum += s_cur[nb][e];
-          l[nb] += psum;
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            uint4 pv = {pack_bf16x2(s_cur[nb][8 * u + 0], s_cur[nb][8 * u + 1]),
-                        pack_bf16x2(s_cur[nb][8 * u + 2], s_cur[nb][8 * u + 3]),
-                        pack_bf16x2(s_cur[nb][8 * u + 4], s_cur[nb][8 * u + 5]),
-                        pack_bf16x2(s_cur[nb][8 * u + 6], s_cur[nb][8 * u + 7])};
-            pop[nb][u] = as_bf16x8(pv);
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);  // keep this step's exps between its MFMAs and the next pair
+        for (int n = 0; n < 4; ++n) acc[n] *= alpha;
       }
-      // 16 output MFMAs; each accumulator is touched again only 4 MFMAs later
+      float psum = 0.f;
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+      for (int e = 0; e < 16; ++e) {
+        s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], P.scale_log2, -m));
+        psum += s[e];
+      }
+      l += psum;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < 2; ++u) {
+        uint4 pv = {pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
+                    pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7])};
+        const bf16x8 pop = as_bf16x8(pv);
 #pragma unroll
-          for (int n = 0; n < 4; ++n) PS_MFMA_OUT(acc[nb][n], vf[u * 4 + n], pop[nb][u]);
-      // the scores of tile+1 finished long before these 16 MFMAs did
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) s_cur[nb] = s_next[nb];
+        for (int n = 0; n < 4; ++n)
+          acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(S.v[u * 4 + n][lane]), pop, acc[n], 0, 0, 0);
+      }
     }
   }
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // last output MFMA -> epilogue reads of acc
   __builtin_amdgcn_s_waitcnt(PS_VMCNT(0));  // no load may still be writing LDS when the wave ends
 
   if (!active) return;
+  const float ls = l + __shfl_xor(l, 32);
+  const float inv = 1.f / ls;
+  const int row = q0 + j;
+  if (row < lq) {
+    const size_t ob = ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    const float ls = l[nb] + __shfl_xor(l[nb], 32);
-    const float inv = 1.f / ls;
-    const int row = q0 + nb * 32 + j;
-    if (row < lq) {
-      const size_t ob = ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
+    for (int n = 0; n < 4; ++n)
 #pragma unroll
-      for (int n = 0; n < 4; ++n)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          const int x = n * 32 + a * 8 + h2 * 4;  // acc[..][n][4a+b] is dim x + b
-          const float o0 = acc[nb][n][4 * a + 0] * inv, o1 = acc[nb][n][4 * a + 1] * inv;
-          const float o2 = acc[nb][n][4 * a + 2] * inv, o3 = acc[nb][n][4 * a + 3] * inv;
-          if (P.out_f32) {
-            *(f32x4*)((float*)P.out + ob + x) = (f32x4){o0, o1, o2, o3};
-          } else {
-            uint2 w = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
-            *(uint2*)((uint16_t*)P.out + ob + x) = w;
-          }
+      for (int a = 0; a < 4; ++a) {
+        const int x = n * 32 + a * 8 + h2 * 4;  // acc[n][4a+b] is dim x + b
+        const float o0 = acc[n][4 * a + 0] * inv, o1 = acc[n][4 * a + 1] * inv;
+        const float o2 = acc[n][4 * a + 2] * inv, o3 = acc[n][4 * a + 3] * inv;
+        if (P.out_f32) {
+          *(f32x4*)((float*)P.out + ob + x) = (f32x4){o0, o1, o2, o3};
+        } else {
+          uint2 w = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
+          *(uint2*)((uint16_t*)P.out + ob + x) = w;
         }
-    }
+      }
   }
 }
 
@@ -616,8 +547,8 @@ hipError_t launch_merge(const StepParams& p, int n_merge, hipStream_t s) {
   return hipGetLastError();
 }
 
-int prefill_heads_per_wg(int G) { return G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1); }
-int prefill_tile_tokens(int G) { return (4 / prefill_heads_per_wg(G)) * kPrefillRows; }
+int prefill_heads_per_wg(int G) { return G % 8 == 0 ? 8 : (G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1)); }
+int prefill_tile_tokens(int G) { return (kPrefillWaves / prefill_heads_per_wg(G)) * kPrefillRows; }
 
 hipError_t launch_prefill(const StepParams& p, int n_tiles, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
@@ -625,7 +556,7 @@ hipError_t launch_prefill(const StepParams& p, int n_tiles, hipStream_t s) {
   const int nz = p.G / HW;
   const long grid = (long)n_tiles * p.Hkv * nz;
   if (grid > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)grid), dim3(256), 0, s, p, HW, nz);
+  hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)grid), dim3(kPrefillWaves * 64), 0, s, p, HW, nz);
   return hipGetLastError();
 }
 
