@@ -258,16 +258,17 @@ __global__ __launch_bounds__(128) void merge_kernel(StepParams P) {
 // its own MFMAs, two waves sharing a SIMD can, so each wave keeps its state within 256
 // registers.  A workgroup owns a tile of query tokens of one request for one kv-head and HW of
 // its G query heads; wave w owns 32 consecutive query tokens (one 32-column B tile) of head
-// z*HW + w % HW, token sub-tile w / HW.  All eight waves walk the same 32-token KV tiles.
+// z*HW + w % HW, token sub-tile w / HW.  All eight waves walk the same 64-token KV tiles.
 //
 // KV tiles go from the cache straight into LDS (global_load_lds_dwordx4, no VGPR round trip),
-// in MFMA operand order: fragment f of a tile is the 1 KiB that the 64 lanes of a wave feed to
-// one MFMA as its A operand, lane after lane, so it is read back with one conflict-free 16-byte
-// ds_read per lane.  A tile is 8 K fragments (dim chunks) + 8 V fragments (block u, 32 dims);
-// wave w fetches K fragment w and V fragment w.  The LDS ring holds kStages tiles; loads run
-// kStages-1 tiles ahead of the compute, one barrier per tile.
+// in MFMA operand order: a fragment is the 1 KiB that the 64 lanes of a wave feed to one MFMA as
+// its A operand, lane after lane, so it is read back with one conflict-free 16-byte ds_read per
+// lane.  A 64-token tile is two halves of 32 tokens (two blocks each); a half is 8 K fragments
+// (dim chunks) + 8 V fragments (block u, 32 dims).  Wave w fetches K and V fragment w of both
+// halves.  The LDS ring holds kStages tiles; loads run kStages-1 tiles ahead of the compute,
+// one barrier per tile.
 //
-// Row i of a K fragment is token pi(i) of the tile (bits 2 and 3 of i swapped).  With the
+// Row i of a K fragment is token pi(i) of its half (bits 2 and 3 of i swapped).  With the
 // 32x32 result layout this makes the 8 probabilities a lane holds for MFMA step u the 8
 // consecutive tokens 16u + 8*h2 .. +7, so its V operand is one contiguous 16-byte run of the
 // dim-major V block.
@@ -276,9 +277,10 @@ __global__ __launch_bounds__(128) void merge_kernel(StepParams P) {
 // with its own L2), so the kv-head is taken from the low bits of the id: the workgroups that
 // share one XCD's L2 then walk the same K/V stream.
 constexpr int kPrefillWaves = 8;
-constexpr int kPrefillRows = 32;  // query tokens per wave
-constexpr int kStages = 4;
-constexpr int kLoadsPerTile = 2;  // global->LDS loads each wave issues per tile
+constexpr int kPrefillRows = 32;    // query tokens per wave
+constexpr int kPrefillKV = 64;      // KV tokens per pipeline step
+constexpr int kStages = 3;
+constexpr int kLoadsPerTile = 4;    // global->LDS loads each wave issues per tile
 
 // s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding)
 #define PS_VMCNT(n) (((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
@@ -288,13 +290,15 @@ __device__ __forceinline__ void load_to_lds16(const void* gptr, uint32_t lds_bas
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
 }
 
-// Two block-table entries through the scalar cache.  Written as asm because the compiler will not
-// use scalar loads next to the memory-clobbering LDS loads above, and its vector-load fallback
-// would wait for vmcnt(0), i.e. for every tile still in flight.
-__device__ __forceinline__ void load_ids(const int* pa, const int* pb, int& a, int& b) {
-  asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
-               : "=&s"(a), "=&s"(b)
-               : "s"(pa), "s"(pb));
+// Four block-table entries through the scalar cache.  Written as asm because the compiler will
+// not use scalar loads next to the memory-clobbering LDS loads above, and its vector-load
+// fallback would wait for vmcnt(0), i.e. for every tile still in flight.
+__device__ __forceinline__ void load_ids(const int* p0, const int* p1, const int* p2, const int* p3, int (&id)[4]) {
+  asm volatile(
+      "s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %5, 0x0\n\ts_load_dword %2, %6, 0x0\n\t"
+      "s_load_dword %3, %7, 0x0\n\ts_waitcnt lgkmcnt(0)"
+      : "=&s"(id[0]), "=&s"(id[1]), "=&s"(id[2]), "=&s"(id[3])
+      : "s"(p0), "s"(p1), "s"(p2), "s"(p3));
 }
 
 // max over lanes l and l ^ 32 (both lanes get it), on the VALU: v_permlane32_swap exchanges the upper
@@ -306,9 +310,12 @@ __device__ __forceinline__ float xor32_max(float x) {
   return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
 }
 
-struct PrefillStage {
+struct PrefillHalf {
   uint4 k[8][64];
   uint4 v[8][64];
+};
+struct PrefillStage {
+  PrefillHalf h[2];
 };
 
 __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams P, int HW, int n_zsplit) {
@@ -352,33 +359,38 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
     for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
 
   const int wg_last = (t.q0 + SUB * kPrefillRows < lq ? t.q0 + SUB * kPrefillRows : lq) - 1;
-  const int ntiles = (p + wg_last) / kTileTokens + 1;                            // workgroup-uniform
+  const int ntiles = (p + wg_last) / kPrefillKV + 1;                            // workgroup-uniform
   const int my_last = p + (q0 + kPrefillRows < lq ? q0 + kPrefillRows : lq) - 1;  // last visible key
   const int qpos = p + q0 + j;
 
-  // K row j of a fragment is token pi(j): block j>>4, slot 8*bit2(j) + 4*bit3(j) + (j&3)
+  // K row j of a fragment is token pi(j) of its half: block j>>4, slot 8*bit2(j) + 4*bit3(j) + (j&3)
   const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
   const uint32_t sm_base = (uint32_t)(uintptr_t)(&sm[0]);  // LDS byte address of the ring
 
-  // Block ids of tile `tile` (clamped to the last tile; an absent second block repeats the first
-  // and is fully masked).
-  auto lookup = [&](int tile, int& idA, int& idB) {
+  // Block ids of tile `tile` (clamped to the last tile; absent blocks repeat the last present one
+  // and are fully masked).
+  auto lookup = [&](int tile, int (&id)[4]) {
     tile = tile < ntiles ? tile : ntiles - 1;
-    const int bA = (tile * kTileTokens) >> 4;
-    load_ids(table + bA, table + (bA + 1 < nblk ? bA + 1 : bA), idA, idB);
+    const int b0 = tile * (kPrefillKV / kBlockTokens);
+    const int last = nblk - 1;
+    load_ids(table + b0, table + (b0 + 1 < last ? b0 + 1 : last), table + (b0 + 2 < last ? b0 + 2 : last),
+             table + (b0 + 3 < last ? b0 + 3 : last), id);
   };
   // Issues this wave's loads of one tile into ring slot `stage`: K fragment `wave` (dim chunk) and
-  // V fragment `wave` (block wave/4, dims 32*(wave%4)..).  Every call issues exactly
+  // V fragment `wave` (block wave/4, dims 32*(wave%4)..) of each half.  Every call issues exactly
   // kLoadsPerTile loads (past the end the last tile is fetched again): the vmcnt bookkeeping
   // below counts on it.
-  auto issue = [&](int stage, int idA, int idB) {
-    const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + kslot * kHeadDim;
+  auto issue = [&](int stage, const int (&id)[4]) {
     const uint32_t st = sm_base + (uint32_t)stage * (uint32_t)sizeof(PrefillStage);
-    const int f = wave;
-    load_to_lds16(krow + (f * 2 + h2) * 8, st + (uint32_t)f * 1024u);
-    const int u = f >> 2, n = f & 3;
-    const uint16_t* vs = v_slice(P.cache, u == 0 ? idA : idB, Hkv, g) + (n * 32 + j) * kBlockTokens + 8 * h2;
-    load_to_lds16(vs, st + 8192u + (uint32_t)f * 1024u);
+    const int f = wave, u = f >> 2, n = f & 3;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int idA = id[2 * hf], idB = id[2 * hf + 1];
+      const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + kslot * kHeadDim;
+      load_to_lds16(krow + (f * 2 + h2) * 8, st + (uint32_t)hf * 16384u + (uint32_t)f * 1024u);
+      const uint16_t* vs = v_slice(P.cache, u == 0 ? idA : idB, Hkv, g) + (n * 32 + j) * kBlockTokens + 8 * h2;
+      load_to_lds16(vs, st + (uint32_t)hf * 16384u + 8192u + (uint32_t)f * 1024u);
+    }
   };
 
   // The Q loads above must be complete, and known to the compiler to be complete, before the ring
@@ -388,56 +400,64 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
   __builtin_amdgcn_s_waitcnt(PS_VMCNT(0));
   asm volatile("" ::: "memory");
 
-  int idA, idB;
+  int id[4];
 #pragma unroll
   for (int i = 0; i < kStages - 1; ++i) {
-    lookup(i, idA, idB);
-    issue(i, idA, idB);
+    lookup(i, id);
+    issue(i, id);
   }
-  lookup(kStages - 1, idA, idB);  // ids of the tile the first iteration will issue
+  lookup(kStages - 1, id);  // ids of the tile the first iteration will issue
 
   for (int tile = 0; tile < ntiles; ++tile) {
     const int stage = tile % kStages;
-    const int ts = tile * kTileTokens;
+    const int ts = tile * kPrefillKV;
     // own loads of this tile have landed (the younger ones may still fly) ...
     __builtin_amdgcn_s_waitcnt(PS_VMCNT(kLoadsPerTile * (kStages - 2)));
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();  // ... and so have everybody's; everyone is done with tile-1
     asm volatile("" ::: "memory");
-    issue((tile + kStages - 1) % kStages, idA, idB);  // tile + kStages-1 refills the slot of tile-1
-    lookup(tile + kStages, idA, idB);                  // ids for the next iteration's issue
+    issue((tile + kStages - 1) % kStages, id);  // tile + kStages-1 refills the slot of tile-1
+    lookup(tile + kStages, id);                  // ids for the next iteration's issue
 
-    if (ts + kTileTokens > L) {
+    if (ts + kPrefillKV > L) {
       // Last tile of the request: slots past kv_len may hold anything.  The wave that fetched a V
       // fragment zeroes those slots in LDS before anyone multiplies by them (0 * NaN is NaN).
       const int f = wave, u = f >> 2;
-      const int first = ts + 16 * u + 8 * h2;
-      const uint4 vv = sm[stage].v[f][lane];
-      const uint2 lo = zero_from(make_uint2(vv.x, vv.y), first, L);
-      const uint2 hi = zero_from(make_uint2(vv.z, vv.w), first + 4, L);
-      sm[stage].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int first = ts + 32 * hf + 16 * u + 8 * h2;
+        const uint4 vv = sm[stage].h[hf].v[f][lane];
+        const uint2 lo = zero_from(make_uint2(vv.x, vv.y), first, L);
+        const uint2 hi = zero_from(make_uint2(vv.z, vv.w), first + 4, L);
+        sm[stage].h[hf].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
       __syncthreads();  // workgroup-uniform branch
     }
 
     if (active && ts <= my_last) {
       const PrefillStage& S = sm[stage];
-      f32x16 s;
+      f32x16 s[2];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[e] = 0.f;
+      for (int hf = 0; hf < 2; ++hf) {
 #pragma unroll
-      for (int c = 0; c < 8; ++c)
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(S.k[c][lane]), qop[c], s, 0, 0, 0);
-      // s[e]: token ts + 16*(e/8) + 8*h2 + e%8, query q0 + j (raw dot products)
-      if (ts + kTileTokens - 1 > p + q0) {  // diagonal tile (wave-uniform test)
+        for (int e = 0; e < 16; ++e) s[hf][e] = 0.f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int tok = ts + 16 * (e >> 3) + 8 * h2 + (e & 7);
-          if (tok > qpos) s[e] = PS_NEG_INF;
-        }
+        for (int c = 0; c < 8; ++c)
+          s[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(S.h[hf].k[c][lane]), qop[c], s[hf], 0, 0, 0);
       }
-      float tmax = s[0];
+      // s[hf][e]: token ts + 32*hf + 16*(e/8) + 8*h2 + e%8, query q0 + j (raw dot products)
+      if (ts + kPrefillKV - 1 > p + q0) {  // diagonal tile (wave-uniform test)
 #pragma unroll
-      for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, s[e]);
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int tok = ts + 32 * hf + 16 * (e >> 3) + 8 * h2 + (e & 7);
+            if (tok > qpos) s[hf][e] = PS_NEG_INF;
+          }
+      }
+      float tmax = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+      for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, fmaxf(s[0][e], s[1][e]));
       tmax = xor32_max(tmax) * P.scale_log2;
       // m is finite from the first tile on (key 0 is visible to every query); a row that sees
       // nothing in this tile keeps its m
@@ -449,21 +469,24 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
 #pragma unroll
         for (int n = 0; n < 4; ++n) acc[n] *= alpha;
       }
-      float psum = 0.f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], P.scale_log2, -m));
-        psum += s[e];
-      }
-      l += psum;
+      for (int hf = 0; hf < 2; ++hf) {
+        float psum = 0.f;
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        uint4 pv = {pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
-                    pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7])};
-        const bf16x8 pop = as_bf16x8(pv);
+        for (int e = 0; e < 16; ++e) {
+          s[hf][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[hf][e], P.scale_log2, -m));
+          psum += s[hf][e];
+        }
+        l += psum;
 #pragma unroll
-        for (int n = 0; n < 4; ++n)
-          acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(S.v[u * 4 + n][lane]), pop, acc[n], 0, 0, 0);
+        for (int u = 0; u < 2; ++u) {
+          uint4 pv = {pack_bf16x2(s[hf][8 * u + 0], s[hf][8 * u + 1]), pack_bf16x2(s[hf][8 * u + 2], s[hf][8 * u + 3]),
+                      pack_bf16x2(s[hf][8 * u + 4], s[hf][8 * u + 5]), pack_bf16x2(s[hf][8 * u + 6], s[hf][8 * u + 7])};
+          const bf16x8 pop = as_bf16x8(pv);
+#pragma unroll
+          for (int n = 0; n < 4; ++n)
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(S.h[hf].v[u * 4 + n][lane]), pop, acc[n], 0, 0, 0);
+        }
       }
     }
   }
