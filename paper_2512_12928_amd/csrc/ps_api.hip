@@ -76,12 +76,13 @@ namespace {
 
 int pick_decode_chunk(const ps_ctx* c, int64_t decode_kv_tokens) {
   if (c->cfg.decode_chunk > 0) return c->cfg.decode_chunk;
-  // aim at ~8 workgroups per CU over 256 CUs; partitions are multiples of 128 tokens so the
-  // four waves of a workgroup get whole 32-token tiles
-  int64_t ch = decode_kv_tokens * c->cfg.n_kv_heads / 2048;
+  // aim at ~3500 workgroups per launch (about 14 per CU over 256 CUs): long partitions keep the
+  // per-partition start-up and the partials traffic small, enough of them keep every CU fed.
+  // Partitions are multiples of 128 tokens so the four waves of a workgroup get whole tiles.
+  int64_t ch = decode_kv_tokens * c->cfg.n_kv_heads / 3500;
   ch = (ch + 127) / 128 * 128;
   if (ch < 256) ch = 256;
-  if (ch > 1024) ch = 1024;
+  if (ch > 2048) ch = 2048;
   return (int)ch;
 }
 

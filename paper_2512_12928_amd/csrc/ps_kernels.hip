@@ -77,15 +77,36 @@ __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
 // Split-K decode attention, HBM-bound.  grid (n_items, Hkv), 256 threads = 4 waves.
 // The workgroup owns KV tokens [t0, t1) of one request for one kv-head and all G query heads
 // of that head (padded to the 16 columns of a 16x16x32 MFMA), so every K/V byte is read once.
-// Wave w streams the 32-token tiles w, w+4, ...; per tile it issues 16 x 16-byte loads per
-// lane (8 KiB K + 8 KiB V), 8 MFMAs for S^T and 8 for O^T.  The four waves' running
-// (m, l, O) states are combined through LDS; the result is either the final output (single
-// partition) or an unnormalised partial for the merge kernel.
+// Wave w streams the 32-token tiles w, w+4, ...; per tile it issues 16 non-temporal 16-byte
+// loads per lane (8 KiB K + 8 KiB V; the cache is read once, nothing is worth keeping in L2),
+// 8 MFMAs for S^T and 8 for O^T.  The four waves' running (m, l, O) states are combined through
+// LDS; the result is either the final output (single partition) or an unnormalised partial for
+// the merge kernel.
+//
+// Token order inside a tile: the tile is blocks A, B.  Row i = 4q+b of the first score MFMA is
+// slot 8*(q&1)+b of block (q<2 ? A : B), of the second one slot 8*(q&1)+4+b.  In the 16x16 result
+// layout lane (head j, k-group kg) then holds the 8 consecutive tokens ts + 8*kg .. +7, which is
+// one contiguous 16-byte run of the dim-major V block: its V operand is a single load.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 load_stream16(const uint16_t* p) {
+  return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4*)p));
+}
+
+// Zero the 16-bit elements e (0..7) of v whose token index first+e is >= limit.
+__device__ __forceinline__ bf16x8 zero_from8(bf16x8 v, int first, int limit) {
+  u32x4 w = __builtin_bit_cast(u32x4, v);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    w[i] &= (first + 2 * i < limit ? 0x0000FFFFu : 0u) | (first + 2 * i + 1 < limit ? 0xFFFF0000u : 0u);
+  return __builtin_bit_cast(bf16x8, w);
+}
+
 __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
   extern __shared__ float smem[];  // [4][G][128] O, then [4][16] m, [4][16] l
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int j = lane & 15;   // token row of the K operand / query-head column of Q, P, O
+  const int j = lane & 15;   // row of the K operand / query-head column of Q, P, O
   const int kg = lane >> 4;  // k-group of the MFMA operands
   const DecodeItem it = P.ditems[blockIdx.x];
   const int g = blockIdx.y;
@@ -110,50 +131,47 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
 #pragma unroll
   for (int n = 0; n < 8; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
+  // per-lane element offsets inside a (block, head) slice
+  const int krow_off = (8 * ((j >> 2) & 1) + (j & 3)) * kHeadDim + kg * 8;  // first score MFMA; second: +4 rows
+  const bool k_in_b = (j >> 3) != 0;                                         // K rows 8..15 come from block B
+  const int v_off = j * kBlockTokens + 8 * (kg & 1);                         // + n*16 dims
+  const bool v_in_b = kg >= 2;
+
   const int ntiles = (it.t1 - it.t0 + kTileTokens - 1) / kTileTokens;
   for (int tile = wave; tile < ntiles; tile += 4) {
     const int ts = it.t0 + tile * kTileTokens;
     const int bA = ts >> 4;
     const int idA = table[bA];
     const int idB = (bA + 1 < nblk) ? table[bA + 1] : idA;  // absent second block: masked below
-    const uint16_t* kA = k_slice(P.cache, idA, Hkv, g);
-    const uint16_t* kB = k_slice(P.cache, idB, Hkv, g);
-    const uint16_t* vA = v_slice(P.cache, idA, Hkv, g);
-    const uint16_t* vB = v_slice(P.cache, idB, Hkv, g);
+    const uint16_t* kp = k_slice(P.cache, k_in_b ? idB : idA, Hkv, g) + krow_off;
+    const uint16_t* vp = v_slice(P.cache, v_in_b ? idB : idA, Hkv, g) + v_off;
 
-    uint4 ka[4], kb[4];
+    bf16x8 k1[4], k2[4], vv[8];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      ka[c] = *(const uint4*)(kA + j * kHeadDim + (c * 4 + kg) * 8);
-      kb[c] = *(const uint4*)(kB + j * kHeadDim + (c * 4 + kg) * 8);
+      k1[c] = load_stream16(kp + c * 32);
+      k2[c] = load_stream16(kp + 4 * kHeadDim + c * 32);
     }
-    uint2 va[8], vb[8];
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-      va[n] = *(const uint2*)(vA + (n * 16 + j) * kBlockTokens + kg * 4);
-      vb[n] = *(const uint2*)(vB + (n * 16 + j) * kBlockTokens + kg * 4);
-    }
+    for (int n = 0; n < 8; ++n) vv[n] = load_stream16(vp + n * 16 * kBlockTokens);
 
-    f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
+    f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[c]), qop[c], sA, 0, 0, 0);
-      sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[c]), qop[c], sB, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[c], qop[c], s1, 0, 0, 0);
+      s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k2[c], qop[c], s2, 0, 0, 0);
     }
-    // sA[e]: token ts + 4*kg + e, head j.   sB[e]: token ts + 16 + 4*kg + e.
+    // s1[e]: token ts + 8*kg + e, head j.   s2[e]: token ts + 8*kg + 4 + e.
     float s[8];
-    const int tokA = ts + 4 * kg, tokB = ts + 16 + 4 * kg;
+    const int tok0 = ts + 8 * kg;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      s[e] = (tokA + e < it.t1) ? sA[e] * P.scale_log2 : PS_NEG_INF;
-      s[4 + e] = (tokB + e < it.t1) ? sB[e] * P.scale_log2 : PS_NEG_INF;
+      s[e] = (tok0 + e < it.t1) ? s1[e] * P.scale_log2 : PS_NEG_INF;
+      s[4 + e] = (tok0 + 4 + e < it.t1) ? s2[e] * P.scale_log2 : PS_NEG_INF;
     }
     if (ts + kTileTokens > it.t1) {  // ragged tail: slots past kv_len may hold anything
 #pragma unroll
-      for (int n = 0; n < 8; ++n) {
-        va[n] = zero_from(va[n], tokA, it.t1);
-        vb[n] = zero_from(vb[n], tokB, it.t1);
-      }
+      for (int n = 0; n < 8; ++n) vv[n] = zero_from8(vv[n], tok0, it.t1);
     }
     float tmax = s[0];
 #pragma unroll
@@ -176,7 +194,7 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       acc[n] *= alpha;
-      acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(join_bf16x4(va[n], vb[n]), pop, acc[n], 0, 0, 0);
+      acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[n], pop, acc[n], 0, 0, 0);
     }
   }
   l += __shfl_xor(l, 16);
