@@ -199,7 +199,9 @@ def main() -> int:
 
 
 def swap_bench(B, W, torch, np, dev):
-    """Workload 3: 512 blocks out and 512 in per step on a side stream, alone and under attention."""
+    """Workload 3: per engine step, 512 blocks out and 512 in (32 MiB each way) on side streams, issued
+    step by step next to the attention step as an engine would.  Reported against the host link as
+    measured on this machine with large pinned copies (one direction, and both directions at once)."""
     import time as _t
     batch = W.make_workload(3)
     s = batch.shape
@@ -210,19 +212,38 @@ def swap_bench(B, W, torch, np, dev):
     pool = torch.empty((batch.n_device_blocks, bb // 2), dtype=torch.bfloat16, device=dev).normal_(generator=g)
     host = torch.empty((Mh, bb), dtype=torch.uint8).pin_memory()
     host.zero_()
-    # measured host link: one large pinned copy each way
-    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    hbig = torch.empty(1 << 30, dtype=torch.uint8).pin_memory()
-    link = {}
-    for name, (dst, src) in (("d2h", (hbig, big)), ("h2d", (big, hbig))):
-        dst.copy_(src, non_blocking=True)
+    compute, side_out, side_in = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    res = {}
+    # ---- measured host link: 256 MiB pinned copies, one way and both ways at once
+    nbig = 1 << 28
+    d1 = torch.empty(nbig, dtype=torch.uint8, device=dev)
+    d2 = torch.empty(nbig, dtype=torch.uint8, device=dev)
+    h1 = torch.empty(nbig, dtype=torch.uint8).pin_memory()
+    h2 = torch.empty(nbig, dtype=torch.uint8).pin_memory()
+
+    def link(do_out, do_in, reps=6, own_streams=True):
         torch.cuda.synchronize()
         t0 = _t.perf_counter()
-        for _ in range(3):
-            dst.copy_(src, non_blocking=True)
+        for _ in range(reps):
+            if do_out:
+                with torch.cuda.stream(side_out if own_streams else torch.cuda.current_stream()):
+                    h1.copy_(d1, non_blocking=True)
+            if do_in:
+                with torch.cuda.stream(side_in if own_streams else torch.cuda.current_stream()):
+                    d2.copy_(h2, non_blocking=True)
         torch.cuda.synchronize()
-        link[name] = 3 * (1 << 30) / (_t.perf_counter() - t0) / 1e9
-    del big, hbig
+        return reps * nbig / (_t.perf_counter() - t0) / 1e9
+
+    link(True, True, 1)
+    link(True, True, 1, False)
+    # one direction at a time: best of the default stream and a side stream (they can land on
+    # different copy engines); both directions at once: one stream each
+    res["link_d2h_GBps"] = max(link(True, False), link(True, False, own_streams=False))
+    res["link_h2d_GBps"] = max(link(False, True), link(False, True, own_streams=False))
+    res["link_bidir_each_way_GBps"] = link(True, True)
+    del d1, d2, h1, h2
+    torch.cuda.empty_cache()
+
     ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, Mh)
     rng = np.random.default_rng(33)
     used = batch.block_ids
@@ -230,64 +251,46 @@ def swap_bench(B, W, torch, np, dev):
     free = np.setdiff1d(np.arange(batch.n_device_blocks, dtype=np.int32), np.concatenate([used, out_ids]))
     in_ids = rng.permutation(free)[:512].astype(np.int32)
     in_slots = np.setdiff1d(np.arange(Mh, dtype=np.int32), out_slots)[:512].astype(np.int32)
-    side_out, side_in = torch.cuda.Stream(), torch.cuda.Stream()
     nbytes = B.ps_workspace_bytes(ctx, batch.n_req, batch.n_tokens, len(batch.block_ids))
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     q = torch.randn((batch.n_tokens, s.n_q_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
+    kn = torch.randn((batch.n_tokens, s.n_kv_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
     out = torch.empty_like(q)
     cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
-    res = {"link_d2h_GBps": link["d2h"], "link_h2d_GBps": link["h2d"]}
 
-    def swaps(n_iter):
-        tk = 0
-        for _ in range(n_iter):
-            _, t1 = B.ps_swap_out(ctx, out_ids, out_slots, -1, pool, host, side_out)
-            _, t2 = B.ps_swap_in(ctx, in_slots, in_ids, -1, host, pool, side_in)
-            tk = (t1, t2)
-        return tk
-
-    def attn(n_iter):
-        for _ in range(n_iter):
-            B.ps_step(ctx, cb, q, None, None, pool, out, ws, nbytes, torch.cuda.current_stream())
-
-    n_iter = 20
-    moved = n_iter * 512 * bb
-    # swaps alone (both directions concurrently)
-    swaps(2); torch.cuda.synchronize()
-    t0 = _t.perf_counter(); swaps(n_iter); torch.cuda.synchronize(); dt = _t.perf_counter() - t0
-    res["alone_each_way_GBps"] = moved / dt / 1e9
-    # one direction at a time
-    for name, fn in (("out", lambda: B.ps_swap_out(ctx, out_ids, out_slots, -1, pool, host, side_out)),
-                     ("in", lambda: B.ps_swap_in(ctx, in_slots, in_ids, -1, host, pool, side_in))):
-        fn(); torch.cuda.synchronize()
-        t0 = _t.perf_counter()
-        for _ in range(n_iter):
-            fn()
+    def run(n, do_attn, do_out, do_in):
         torch.cuda.synchronize()
-        res["alone_%s_only_GBps" % name] = moved / (_t.perf_counter() - t0) / 1e9
-    # attention alone
-    attn(5); torch.cuda.synchronize()
-    n_att = 200
-    t0 = _t.perf_counter(); attn(n_att); torch.cuda.synchronize(); t_att = (_t.perf_counter() - t0) / n_att
-    res["attn_ms_swaps_off"] = t_att * 1e3
-    # overlapped: keep attention running on the compute stream for as long as the swaps take
-    torch.cuda.synchronize()
-    t0 = _t.perf_counter()
-    swaps(n_iter)
-    n_done = 0
-    ev_out, ev_in = torch.cuda.Event(), torch.cuda.Event()
-    ev_out.record(side_out); ev_in.record(side_in)
-    while not (ev_out.query() and ev_in.query()):
-        attn(10)
-        n_done += 10
-        torch.cuda.current_stream().synchronize()
-    ev_out.synchronize(); ev_in.synchronize()
-    dt_swap = _t.perf_counter() - t0
-    torch.cuda.synchronize()
-    dt_all = _t.perf_counter() - t0
-    res["overlap_each_way_GBps"] = moved / dt_swap / 1e9
-    res["overlap_frac_of_link"] = min(res["overlap_each_way_GBps"] / link["d2h"], res["overlap_each_way_GBps"] / link["h2d"])
-    res["attn_ms_swaps_on"] = dt_all / max(n_done, 1) * 1e3
+        t0 = _t.perf_counter()
+        for _ in range(n):
+            if do_out:
+                B.ps_swap_out(ctx, out_ids, out_slots, -1, pool, host, side_out)
+            if do_in:
+                B.ps_swap_in(ctx, in_slots, in_ids, -1, host, pool, side_in)
+            if do_attn:
+                B.ps_step(ctx, cb, q, kn, kn, pool, out, ws, nbytes, compute)
+        torch.cuda.synchronize()
+        return (_t.perf_counter() - t0) / n
+
+    step_bytes = 512 * bb
+    run(5, True, True, True)
+    n = 60
+    t = run(n, True, False, False)
+    res["attn_ms_swaps_off"] = t * 1e3
+    res["swap_out_only_GBps"] = step_bytes / run(n, False, True, False) / 1e9
+    res["swap_in_only_GBps"] = step_bytes / run(n, False, False, True) / 1e9
+    res["swap_both_each_way_GBps"] = step_bytes / run(n, False, True, True) / 1e9
+    t = run(n, True, True, True)
+    res["overlap_both_each_way_GBps"] = step_bytes / t / 1e9
+    res["overlap_both_step_ms"] = t * 1e3
+    t = run(n, True, True, False)
+    res["overlap_out_GBps"] = step_bytes / t / 1e9
+    res["overlap_out_step_ms"] = t * 1e3
+    t = run(n, True, False, True)
+    res["overlap_in_GBps"] = step_bytes / t / 1e9
+    res["overlap_in_step_ms"] = t * 1e3
+    res["overlap_both_frac_of_bidir_link"] = res["overlap_both_each_way_GBps"] / res["link_bidir_each_way_GBps"]
+    res["overlap_out_frac_of_link"] = res["overlap_out_GBps"] / res["link_d2h_GBps"]
+    res["overlap_in_frac_of_link"] = res["overlap_in_GBps"] / res["link_h2d_GBps"]
     B.ps_destroy(ctx)
     return res
 

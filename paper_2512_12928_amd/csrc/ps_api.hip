@@ -433,7 +433,8 @@ static int swap_common(ps_ctx* c, bool out_dir, const int32_t* dev_ids, const in
   std::memcpy(h + m, host_ids, (size_t)m * 4);
   int32_t* d = c->swap_ids_dev + (size_t)si * 2 * kMaxSwap;
   PS_HIP(hipMemcpyAsync(d, h, (size_t)2 * m * 4, hipMemcpyHostToDevice, stream));
-  const int wgs = c->cfg.swap_workgroups > 0 ? c->cfg.swap_workgroups : 64;
+  // measured next to a running attention step: 8 workgroups move more than 32 or 128 do
+  const int wgs = c->cfg.swap_workgroups > 0 ? c->cfg.swap_workgroups : 8;
   if (out_dir)
     PS_HIP(ps::launch_block_copy(d, d + m, m, kv_cache, const_cast<void*>(host_pool), c->block_bytes, wgs, stream));
   else

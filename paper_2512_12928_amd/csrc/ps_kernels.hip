@@ -535,36 +535,28 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
 
 // ------------------------------------------------------------------------------------ block copy
 // dst_pool[dst_ids[k]] <- src_pool[src_ids[k]] for k < n, whole blocks.  Either pool may be
-// pinned host memory addressed over the host link.  Unit of work = 8 KiB (two 16-byte loads in
-// flight per lane; a block is Hkv * 8 KiB); two units per pass; grid-stride over unit pairs.
-constexpr int kCopyUnit = 8192;
-
+// pinned host memory addressed over the host link.  A workgroup moves one unit of LPL * 4 KiB per
+// pass (LPL 16-byte loads in flight per lane, then LPL stores); grid-stride over units.  Few
+// workgroups with many loads in flight each: next to an attention kernel that saturates HBM the
+// copy's own read latency grows several-fold, and it is bytes in flight that keep the link busy.
+template <int LPL>
 __global__ __launch_bounds__(256) void block_copy_kernel(const int32_t* __restrict__ src_ids,
                                                          const int32_t* __restrict__ dst_ids, int n,
                                                          const char* __restrict__ src_pool,
                                                          char* __restrict__ dst_pool, size_t block_bytes) {
-  const int upb = (int)(block_bytes / kCopyUnit);
+  constexpr size_t kUnit = (size_t)LPL * 4096;
+  const int upb = (int)(block_bytes / kUnit);
   const long total = (long)n * upb;
-  for (long u = 2L * blockIdx.x; u < total; u += 2L * gridDim.x) {
-    const bool two = u + 1 < total;
-    const long u1 = two ? u + 1 : u;
-    const int k0 = (int)(u / upb), k1 = (int)(u1 / upb);
-    const size_t o0 = (size_t)(u % upb) * kCopyUnit + threadIdx.x * 16;
-    const size_t o1 = (size_t)(u1 % upb) * kCopyUnit + threadIdx.x * 16;
-    const char* s0 = src_pool + (size_t)src_ids[k0] * block_bytes + o0;
-    const char* s1 = src_pool + (size_t)src_ids[k1] * block_bytes + o1;
-    char* d0 = dst_pool + (size_t)dst_ids[k0] * block_bytes + o0;
-    char* d1 = dst_pool + (size_t)dst_ids[k1] * block_bytes + o1;
-    const uint4 a0 = *(const uint4*)(s0);
-    const uint4 a1 = *(const uint4*)(s0 + 4096);
-    const uint4 b0 = *(const uint4*)(s1);
-    const uint4 b1 = *(const uint4*)(s1 + 4096);
-    *(uint4*)(d0) = a0;
-    *(uint4*)(d0 + 4096) = a1;
-    if (two) {
-      *(uint4*)(d1) = b0;
-      *(uint4*)(d1 + 4096) = b1;
-    }
+  for (long u = blockIdx.x; u < total; u += gridDim.x) {
+    const int k = (int)(u / upb);
+    const size_t off = (size_t)(u % upb) * kUnit + threadIdx.x * 16;
+    const char* s = src_pool + (size_t)src_ids[k] * block_bytes + off;
+    char* d = dst_pool + (size_t)dst_ids[k] * block_bytes + off;
+    u32x4 v[LPL];
+#pragma unroll
+    for (int i = 0; i < LPL; ++i) v[i] = __builtin_nontemporal_load((const u32x4*)(s + i * 4096));
+#pragma unroll
+    for (int i = 0; i < LPL; ++i) __builtin_nontemporal_store(v[i], (u32x4*)(d + i * 4096));
   }
 }
 
@@ -604,11 +596,16 @@ hipError_t launch_prefill(const StepParams& p, int n_tiles, hipStream_t s) {
 hipError_t launch_block_copy(const int32_t* src_ids, const int32_t* dst_ids, int n, const void* src_pool,
                              void* dst_pool, size_t block_bytes, int workgroups, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  const long pairs = ((long)n * (long)(block_bytes / kCopyUnit) + 1) / 2;
-  int grid = (int)(pairs < workgroups ? pairs : workgroups);
+  const bool big = block_bytes % 32768 == 0;  // else a block is an odd multiple of 8 KiB
+  const long total = (long)n * (long)(block_bytes / (big ? 32768 : 8192));
+  int grid = (int)(total < workgroups ? total : workgroups);
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL(block_copy_kernel, dim3(grid), dim3(256), 0, s, src_ids, dst_ids, n,
-                     (const char*)src_pool, (char*)dst_pool, block_bytes);
+  if (big)
+    hipLaunchKernelGGL(block_copy_kernel<8>, dim3(grid), dim3(256), 0, s, src_ids, dst_ids, n,
+                       (const char*)src_pool, (char*)dst_pool, block_bytes);
+  else
+    hipLaunchKernelGGL(block_copy_kernel<2>, dim3(grid), dim3(256), 0, s, src_ids, dst_ids, n,
+                       (const char*)src_pool, (char*)dst_pool, block_bytes);
   return hipGetLastError();
 }
 
