@@ -147,6 +147,78 @@ int ps_swap_in(ps_ctx* ctx, const int32_t* host_slot_ids, const int32_t* dev_blo
 int ps_ticket_query(ps_ctx* ctx, uint64_t ticket); /* PS_OK done | PS_EBUSY | PS_ESTATE */
 int ps_ticket_wait(ps_ctx* ctx, uint64_t ticket);  /* host blocks until done            */
 
+/* ------------------------------------------------------------------------------------------
+ * Host-only batch former: SlideBatching (Alg. 1) with the block management of Sec. 4.3.
+ * All times are integer picoseconds; all arithmetic is exact (128-bit intermediates), so two
+ * implementations of the same rules agree bit for bit. No GPU call is made by these functions.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct ps_sched ps_sched;
+
+typedef struct {
+  int32_t n_classes;        /* priority classes 1..n_classes (1 = highest), at most 8        */
+  int32_t block_tokens;     /* s_blk, 16                                                      */
+  int64_t class_weight[8];  /* w_{p}: priority weight of class p at index p-1 (Sec. 2)        */
+  int64_t w_first;          /* w_p of Eq. 3: weight of the first token                        */
+  int64_t w_decode;         /* w_d of Eq. 3: weight of every later token                      */
+  int64_t ttft_slo_ps;      /* deadline_{r,i} = TTFT_SLO + (i-1) TPOT_SLO (Eq. 3)             */
+  int64_t tpot_slo_ps;
+  int64_t a_p, b_p, c_p;    /* T~_p = a_p l_q^2 + b_p l_q l_kv + c_p l_q   (Eq. 5), ps        */
+  int64_t a_d, b_d;         /* T~_d = a_d l_kv + b_d                       (Eq. 6), ps        */
+  int64_t t_c;              /* constant per-batch overhead (Eq. 4), ps                        */
+  int64_t eta_ps;           /* lower bound of the latency budget (Alg. 1 line 7); > t_c       */
+  int64_t tau_ps;           /* starvation threshold (Sec. 4.2)                                */
+  int64_t gamma_num, gamma_den; /* aggressiveness coefficient gamma as a fraction              */
+  int64_t beta_num, beta_den;   /* partial-copy threshold beta > 1 as a fraction (Sec. 4.3)    */
+  int64_t rho_num, rho_den;     /* a request that waited >= rho*tau is never an eviction victim */
+  int64_t t_block_ps;       /* profiled copy time of one block (Sec. 4.3)                     */
+  int32_t n_off_base;       /* offload threshold n_off of class 1; halves per class, floor 1  */
+  int32_t reserved;
+} ps_sched_cfg;
+
+/* Result of one scheduling round. Every pointer refers to memory owned by the scheduler and
+ * stays valid until the next call on the same ps_sched. `batch` can be handed to ps_step as is:
+ * members in admission order, l_q tokens each, kv_len including them, their device block tables. */
+typedef struct {
+  ps_batch batch;
+  const int64_t* req_ids;            /* [batch.n_req]                                        */
+  int64_t t_budget_ps;               /* max(t_min, eta)                                      */
+  int64_t phi_ps;                    /* load judgment phi(Q), Eq. 8                          */
+  int64_t t_batch_ps;                /* T_pd(B), Eq. 7; 0 if nothing was admitted            */
+  int64_t copy_budget;               /* B_copy                                               */
+  int32_t n_order;                   /* sorted queue                                         */
+  int32_t n_urgent;
+  const int64_t* order;              /* [n_order] request ids in scheduling order            */
+  const int64_t* urgent;             /* [n_urgent] ids classified URGENT, in that order      */
+  int32_t n_swap_in, n_swap_out;
+  const int32_t* swap_in_host_slots; /* reload list for ps_swap_in (already within budget)   */
+  const int32_t* swap_in_dev_blocks;
+  const int32_t* swap_out_dev_blocks;/* offload list for ps_swap_out                         */
+  const int32_t* swap_out_host_slots;
+  int32_t n_evicted, n_emitted;
+  const int64_t* evicted;            /* requests whose device blocks were freed              */
+  const int64_t* emitted_req;        /* tokens delivered at now + t_batch: request ...       */
+  const int32_t* emitted_index;      /* ... and 1-based token index                          */
+  int32_t n_finished, reserved;
+  const int64_t* finished;           /* requests that delivered their last token             */
+} ps_batch_out;
+
+/* dev_free_order / host_free_order: the block ids of the two pools in the order they are to be
+ * handed out (each pool is a LIFO stack; a request's blocks are returned in logical order).
+ * PS_EINVAL: bad cfg (eta <= t_c, zero denominators, n_classes outside 1..8, duplicates). */
+int ps_sched_create(const ps_sched_cfg* cfg, const int32_t* dev_free_order, int32_t n_dev,
+                    const int32_t* host_free_order, int32_t n_host, ps_sched** out);
+void ps_sched_destroy(ps_sched* s);
+/* Adds a request to the queue. PS_EINVAL: duplicate id, prio outside 1..n_classes,
+ * prompt_len < 1, out_len < 1. */
+int ps_sched_add_request(ps_sched* s, int64_t rid, int64_t arrival_ps, int32_t prio,
+                         int32_t prompt_len, int32_t out_len);
+/* One round of Alg. 1 at time now_ps over the requests that have arrived: orders the queue,
+ * computes the copy budget, admits requests (evicting from the tail under memory pressure),
+ * and applies the round to the state (blocks, computed tokens, delivered tokens, offloads). */
+int ps_form_batch(ps_sched* s, int64_t now_ps, ps_batch_out* out);
+/* Queue and pool occupancy, for tests and monitoring. Any pointer may be NULL. */
+int ps_sched_counts(const ps_sched* s, int32_t* n_queued, int32_t* n_dev_free, int32_t* n_host_free);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,6 +24,7 @@ PS_BF16, PS_F32 = 0, 1
 EXPORTS = [
     "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_set_profiling",
     "ps_get_step_times", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
+    "ps_sched_create", "ps_sched_destroy", "ps_sched_add_request", "ps_form_batch", "ps_sched_counts",
 ]
 
 
@@ -42,6 +43,28 @@ class ps_batch(C.Structure):
 
 class ps_step_times(C.Structure):
     _fields_ = [(n, C.c_float) for n in ("upload_ms", "append_ms", "decode_ms", "merge_ms", "prefill_ms", "total_ms")]
+
+
+class ps_sched_cfg(C.Structure):
+    _fields_ = [("n_classes", C.c_int32), ("block_tokens", C.c_int32), ("class_weight", C.c_int64 * 8),
+                ("w_first", C.c_int64), ("w_decode", C.c_int64), ("ttft_slo_ps", C.c_int64),
+                ("tpot_slo_ps", C.c_int64), ("a_p", C.c_int64), ("b_p", C.c_int64), ("c_p", C.c_int64),
+                ("a_d", C.c_int64), ("b_d", C.c_int64), ("t_c", C.c_int64), ("eta_ps", C.c_int64),
+                ("tau_ps", C.c_int64), ("gamma_num", C.c_int64), ("gamma_den", C.c_int64),
+                ("beta_num", C.c_int64), ("beta_den", C.c_int64), ("rho_num", C.c_int64), ("rho_den", C.c_int64),
+                ("t_block_ps", C.c_int64), ("n_off_base", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ps_batch_out(C.Structure):
+    _fields_ = [("batch", ps_batch), ("req_ids", C.POINTER(C.c_int64)), ("t_budget_ps", C.c_int64),
+                ("phi_ps", C.c_int64), ("t_batch_ps", C.c_int64), ("copy_budget", C.c_int64),
+                ("n_order", C.c_int32), ("n_urgent", C.c_int32), ("order", C.POINTER(C.c_int64)),
+                ("urgent", C.POINTER(C.c_int64)), ("n_swap_in", C.c_int32), ("n_swap_out", C.c_int32),
+                ("swap_in_host_slots", C.POINTER(C.c_int32)), ("swap_in_dev_blocks", C.POINTER(C.c_int32)),
+                ("swap_out_dev_blocks", C.POINTER(C.c_int32)), ("swap_out_host_slots", C.POINTER(C.c_int32)),
+                ("n_evicted", C.c_int32), ("n_emitted", C.c_int32), ("evicted", C.POINTER(C.c_int64)),
+                ("emitted_req", C.POINTER(C.c_int64)), ("emitted_index", C.POINTER(C.c_int32)),
+                ("n_finished", C.c_int32), ("reserved", C.c_int32), ("finished", C.POINTER(C.c_int64))]
 
 
 class PsError(RuntimeError):
@@ -74,6 +97,13 @@ def lib():
         L.ps_swap_in.argtypes = swap_args
         L.ps_ticket_query.argtypes = [C.c_void_p, C.c_uint64]
         L.ps_ticket_wait.argtypes = [C.c_void_p, C.c_uint64]
+        L.ps_sched_create.argtypes = [C.POINTER(ps_sched_cfg), C.POINTER(C.c_int32), C.c_int32,
+                                      C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_void_p)]
+        L.ps_sched_destroy.argtypes = [C.c_void_p]
+        L.ps_sched_destroy.restype = None
+        L.ps_sched_add_request.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32]
+        L.ps_form_batch.argtypes = [C.c_void_p, C.c_int64, C.POINTER(ps_batch_out)]
+        L.ps_sched_counts.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 3
         _lib = L
     return _lib
 
@@ -193,3 +223,57 @@ def ps_ticket_query(ctx: int, ticket: int) -> int:
 
 def ps_ticket_wait(ctx: int, ticket: int) -> None:
     _check(lib().ps_ticket_wait(ctx, ticket))
+
+
+# ---------------------------------------------------------------------------- batch former
+def ps_sched_create(cfg: dict, dev_free_order, host_free_order) -> int:
+    """cfg: field name -> integer for ps_sched_cfg (class_weight as a list)."""
+    c = ps_sched_cfg()
+    for k, v in cfg.items():
+        if k == "class_weight":
+            for i, w in enumerate(v):
+                c.class_weight[i] = int(w)
+        else:
+            setattr(c, k, int(v))
+    d, h = _i32(dev_free_order), _i32(host_free_order)
+    out = C.c_void_p()
+    _check(lib().ps_sched_create(C.byref(c), _i32p(d), len(d), _i32p(h), len(h), C.byref(out)))
+    return out.value
+
+
+def ps_sched_destroy(s: int) -> None:
+    lib().ps_sched_destroy(s)
+
+
+def ps_sched_add_request(s: int, rid: int, arrival_ps: int, prio: int, prompt_len: int, out_len: int) -> None:
+    _check(lib().ps_sched_add_request(s, rid, arrival_ps, prio, prompt_len, out_len))
+
+
+def ps_sched_counts(s: int) -> Tuple[int, int, int]:
+    a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().ps_sched_counts(s, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def ps_form_batch(s: int, now_ps: int) -> dict:
+    """Runs one scheduling round and copies the result out of the scheduler's buffers."""
+    o = ps_batch_out()
+    _check(lib().ps_form_batch(s, now_ps, C.byref(o)))
+
+    def arr(p, n, dt):
+        return np.ctypeslib.as_array(p, shape=(n,)).astype(dt) if n > 0 else np.zeros(0, dtype=dt)
+
+    n = o.batch.n_req
+    nt = int(o.batch.bt_start[n]) if n > 0 else 0
+    return dict(
+        n_req=n, n_tokens=o.batch.n_tokens, q_start=arr(o.batch.q_start, n + 1, np.int32),
+        kv_len=arr(o.batch.kv_len, n, np.int32), bt_start=arr(o.batch.bt_start, n + 1, np.int32),
+        block_ids=arr(o.batch.block_ids, nt, np.int32), prio=arr(o.batch.prio, n, np.uint8),
+        req_ids=arr(o.req_ids, n, np.int64), t_budget=o.t_budget_ps, phi=o.phi_ps, t_batch=o.t_batch_ps,
+        copy_budget=o.copy_budget, order=arr(o.order, o.n_order, np.int64), urgent=arr(o.urgent, o.n_urgent, np.int64),
+        swap_in_host_slots=arr(o.swap_in_host_slots, o.n_swap_in, np.int32),
+        swap_in_dev_blocks=arr(o.swap_in_dev_blocks, o.n_swap_in, np.int32),
+        swap_out_dev_blocks=arr(o.swap_out_dev_blocks, o.n_swap_out, np.int32),
+        swap_out_host_slots=arr(o.swap_out_host_slots, o.n_swap_out, np.int32),
+        evicted=arr(o.evicted, o.n_evicted, np.int64), emitted_req=arr(o.emitted_req, o.n_emitted, np.int64),
+        emitted_index=arr(o.emitted_index, o.n_emitted, np.int32), finished=arr(o.finished, o.n_finished, np.int64))

@@ -136,6 +136,9 @@ extern "C" {
 
 const char* ps_last_error(void) { return g_err.c_str(); }
 
+// used by the host-only scheduler translation unit
+void ps_internal_set_error(const char* text) { g_err = text ? text : ""; }
+
 int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   if (!cfg || !out) return fail(PS_EINVAL, "ps_create: NULL argument");
   *out = nullptr;

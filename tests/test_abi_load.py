@@ -30,6 +30,8 @@ def test_struct_sizes_match_header():
     assert C.sizeof(B.ps_layer_cfg) == 40
     assert C.sizeof(B.ps_batch) == 8 + 5 * 8
     assert C.sizeof(B.ps_step_times) == 24
+    assert C.sizeof(B.ps_sched_cfg) == 8 + 8 * 8 + 20 * 8 + 8
+    assert C.sizeof(B.ps_batch_out) == 48 + 8 + 4 * 8 + 8 + 2 * 8 + 8 + 4 * 8 + 8 + 3 * 8 + 8 + 8
 
 
 @pytest.mark.parametrize("kw", [dict(head_dim=64), dict(block_tokens=32), dict(n_q_heads=6, n_kv_heads=4),
