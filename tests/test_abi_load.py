@@ -26,12 +26,18 @@ def test_header_symbols_are_exported_and_bound():
     assert sorted(B.EXPORTS) == names
 
 
-def test_struct_sizes_match_header():
-    assert C.sizeof(B.ps_layer_cfg) == 40
-    assert C.sizeof(B.ps_batch) == 8 + 5 * 8
-    assert C.sizeof(B.ps_step_times) == 24
-    assert C.sizeof(B.ps_sched_cfg) == 8 + 8 * 8 + 20 * 8 + 8
-    assert C.sizeof(B.ps_batch_out) == 48 + 8 + 4 * 8 + 8 + 2 * 8 + 8 + 4 * 8 + 8 + 3 * 8 + 8 + 8
+def test_struct_sizes_match_header(tmp_path):
+    """ctypes mirrors against sizeof() as a C compiler sees the header."""
+    import subprocess
+    src = tmp_path / "sz.c"
+    src.write_text('#include <stdio.h>\n#include "ps.h"\nint main(void){printf("%zu %zu %zu %zu %zu\\n", sizeof(ps_layer_cfg), '
+                   'sizeof(ps_batch), sizeof(ps_step_times), sizeof(ps_sched_cfg), sizeof(ps_batch_out));return 0;}\n')
+    exe = tmp_path / "sz"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    sizes = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    assert sizes == [C.sizeof(B.ps_layer_cfg), C.sizeof(B.ps_batch), C.sizeof(B.ps_step_times),
+                     C.sizeof(B.ps_sched_cfg), C.sizeof(B.ps_batch_out)]
+    assert sizes[:3] == [40, 48, 24]
 
 
 @pytest.mark.parametrize("kw", [dict(head_dim=64), dict(block_tokens=32), dict(n_q_heads=6, n_kv_heads=4),
