@@ -48,19 +48,7 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     def device_inputs(batch, seed):
-        s = batch.shape
-        g = torch.Generator(device=dev)
-        g.manual_seed(seed)
-        pool_elems = batch.n_device_blocks * (s.block_bytes // 2)
-        pool = torch.empty(pool_elems, dtype=torch.bfloat16, device=dev)
-        step = 1 << 28
-        for a in range(0, pool_elems, step):       # N(0,1) in fp32, rounded to bf16, in slabs
-            n = min(step, pool_elems - a)
-            pool[a:a + n] = torch.randn(n, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
-        q = torch.randn((batch.n_tokens, s.n_q_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
-        kn = torch.randn((batch.n_tokens, s.n_kv_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
-        vn = torch.randn((batch.n_tokens, s.n_kv_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
-        return pool.view(batch.n_device_blocks, -1), q, kn, vn
+        return W.device_inputs(batch, seed, dev)
 
     def algorithmic(batch):
         s = batch.shape

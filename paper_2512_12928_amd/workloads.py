@@ -295,3 +295,26 @@ def make_trace(index: int, n_requests: int, rate_per_s: float, seed: Optional[in
     reqs.sort(key=lambda x: x[0])
     return [TraceRequest(rid=i, arrival_ps=int(round(a * 1e12)), prio=c, prompt_len=pl, out_len=ol)
             for i, (a, c, pl, ol) in enumerate(reqs)]
+
+
+# --------------------------------------------------------------------------- full-size device inputs
+def device_inputs(batch: MixedBatch, seed: int, device: str = "cuda:0"):
+    """Full-size inputs generated on the GPU with torch's seeded generator (plumbing, not the HIP
+    path): the whole device pool, q, and this step's k_new / v_new, all N(0,1) rounded to bf16.
+    Returns (pool [M, block_elems], q, k_new, v_new) as bf16 tensors.  Filling the raw pool with
+    i.i.d. values makes every logical K/V entry N(0,1) whatever the in-block layout."""
+    import torch
+    s = batch.shape
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    pool_elems = batch.n_device_blocks * (s.block_bytes // 2)
+    pool = torch.empty(pool_elems, dtype=torch.bfloat16, device=device)
+    step = 1 << 28
+    for a in range(0, pool_elems, step):       # N(0,1) in fp32, rounded to bf16, in slabs
+        n = min(step, pool_elems - a)
+        pool[a:a + n] = torch.randn(n, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+
+    def rows(heads):
+        return torch.randn((batch.n_tokens, heads, s.head_dim), generator=g, device=device).to(torch.bfloat16)
+
+    return pool.view(batch.n_device_blocks, -1), rows(s.n_q_heads), rows(s.n_kv_heads), rows(s.n_kv_heads)
