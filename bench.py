@@ -18,6 +18,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of decode_kernel + merge_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by a plain 1 GiB copy; summary in profiles/attention_kernels_hbm_traffic_pmc.md), by workload index.
+MEASURED_DECODE_TRAFFIC = {2: 1.555e9 + 1.179e7, 4: 3.181e9 + 9.299e6}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
@@ -31,6 +34,9 @@ def main() -> int:
     ap.add_argument("--decode-chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads / swap figures")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also launch one plain 1 GiB device copy (a known amount of HBM traffic) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1",
@@ -100,6 +106,14 @@ def main() -> int:
                     decode_ms=ph["decode_ms"], merge_ms=ph["merge_ms"], prefill_ms=ph["prefill_ms"],
                     append_ms=ph["append_ms"], upload_ms=ph["upload_ms"])
 
+    if args.pmc_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     batch = W.make_workload(args.workload)
     res = run(batch, args.steps, args.warmup, args.decode_chunk)
     rl = rooflines(batch, res)
@@ -165,11 +179,12 @@ def main() -> int:
             del rr
             torch.cuda.empty_cache()
         extra["swap"] = swap_bench(B, W, torch, np, dev)
+        extra["sched"] = sched_bench(B, W, np, res["ms_per_step"])
 
     dominant_decode = rl["decode_ms"] + rl["merge_ms"] >= rl["prefill_ms"]
     if dominant_decode:
         roof = dict(bound="hbm", kernel="decode_kernel(+merge)", achieved=rl["decode_GBps"], peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=rl["decode_frac"], traffic=None)
+                    unit="GB/s", frac=rl["decode_frac"], traffic=MEASURED_DECODE_TRAFFIC.get(args.workload))
     else:
         roof = dict(bound="mfma", kernel="prefill_kernel", achieved=rl["prefill_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=rl["prefill_frac"], traffic=None)
@@ -281,6 +296,47 @@ def swap_bench(B, W, torch, np, dev):
     res["overlap_in_frac_of_link"] = res["overlap_in_GBps"] / res["link_h2d_GBps"]
     B.ps_destroy(ctx)
     return res
+
+
+def sched_bench(B, W, np, step_ms):
+    """Host time of ps_form_batch (SlideBatching + block management) on a steady synthetic trace whose
+    batches resemble the headline workload (a few hundred decoding requests plus prefill chunks)."""
+    import time as _t
+    MS, US, NS, L = 10 ** 9, 10 ** 6, 10 ** 3, 36
+    cfg = dict(n_classes=3, block_tokens=16, class_weight=[4, 2, 1], w_first=4, w_decode=1, ttft_slo_ps=2000 * MS,
+               tpot_slo_ps=100 * MS, a_p=(13 * L) // 2, b_p=13 * L, c_p=50 * NS * L, a_d=730 * L, b_d=1 * US * L,
+               t_c=2 * MS, eta_ps=10 * MS, tau_ps=30_000 * MS, gamma_num=9, gamma_den=10, beta_num=2, beta_den=1,
+               rho_num=9, rho_den=10, t_block_ps=1200 * NS * L, n_off_base=8)
+    trace = W.make_trace(2, 4000, rate_per_s=60.0, out_mean=256.0)
+    rng = np.random.default_rng(1)
+    M = 40_000
+    s = B.ps_sched_create(cfg, rng.permutation(M).astype(np.int32), rng.permutation(2 * M).astype(np.int32))
+    pending = sorted(trace, key=lambda x: (x.arrival_ps, x.rid))
+    nxt, now, calls, t_sched, members, queued = 0, 0, 0, 0.0, 0, 0
+    import ctypes as _C
+    raw = B.ps_batch_out()
+    while calls < 1500 and (nxt < len(pending) or B.ps_sched_counts(s)[0] > 0):
+        while nxt < len(pending) and pending[nxt].arrival_ps <= now:
+            p = pending[nxt]
+            B.ps_sched_add_request(s, p.rid, p.arrival_ps, p.prio, p.prompt_len, p.out_len)
+            nxt += 1
+        if B.ps_sched_counts(s)[0] == 0:
+            now = pending[nxt].arrival_ps
+            continue
+        t0 = _t.perf_counter()
+        B.lib().ps_form_batch(s, now, _C.byref(raw))       # the C call alone, no copy-out
+        dt = _t.perf_counter() - t0
+        calls += 1
+        if calls > 500:                      # steady state only
+            t_sched += dt
+            members += raw.batch.n_req
+            queued += raw.n_order
+        now += raw.t_batch_ps if raw.t_batch_ps > 0 else cfg["eta_ps"]
+    B.ps_sched_destroy(s)
+    n = max(calls - 500, 1)
+    us = t_sched / n * 1e6
+    return {"form_batch_us_per_call": us, "mean_batch_members": members / n, "mean_queue_len": queued / n,
+            "frac_of_one_layer_step": us * 1e-3 / step_ms, "frac_of_36_layer_step": us * 1e-3 / (36 * step_ms)}
 
 
 if __name__ == "__main__":
