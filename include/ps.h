@@ -65,6 +65,12 @@ typedef struct {
   int32_t decode_chunk;    /* KV tokens per split-K partition; 0 => library picks; else a
                               multiple of 32 in [32, 65536]                               */
   int32_t swap_workgroups; /* workgroups used by a swap kernel; 0 => library picks        */
+  int32_t serial_kernels;  /* 0 (default): the HBM-bound decode kernels and the MFMA-bound
+                              prefill kernel of one step run concurrently (the prefill kernel
+                              on a stream owned by the context, forked from and joined to the
+                              caller's stream with events); 1: every kernel on the caller's
+                              stream, one after another. Profiled steps are always serial.   */
+  int32_t reserved;
 } ps_layer_cfg;
 
 /* One mixed batch (the output of Alg. 1 as the attention layer sees it). HOST arrays. */

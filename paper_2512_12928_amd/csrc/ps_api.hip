@@ -61,6 +61,8 @@ struct ps_ctx {
   hipEvent_t ticket_ev[kTicketRing];
   uint64_t ticket_id[kTicketRing];
   uint64_t next_ticket = 1;
+  hipStream_t side = nullptr;  // prefill kernel of a step, concurrent with its decode kernels
+  hipEvent_t fork_ev = nullptr, join_ev = nullptr;
   bool profiling = false;
   hipEvent_t prof_ev[6];
   bool prof_valid = false;
@@ -159,6 +161,7 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
       (cfg->decode_chunk < kMinChunk || cfg->decode_chunk > 65536 || cfg->decode_chunk % 32 != 0))
     return fail(PS_EINVAL, "decode_chunk must be 0 or a multiple of 32 in [32, 65536]");
   if (cfg->swap_workgroups < 0 || cfg->swap_workgroups > 65536) return fail(PS_EINVAL, "bad swap_workgroups");
+  if (cfg->serial_kernels != 0 && cfg->serial_kernels != 1) return fail(PS_EINVAL, "serial_kernels must be 0 or 1");
   if (!(cfg->softmax_scale >= 0.f) || std::isinf(cfg->softmax_scale))
     return fail(PS_EINVAL, "softmax_scale must be finite and >= 0");
 
@@ -181,6 +184,9 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   for (int i = 0; i < kTicketRing && e == hipSuccess; ++i)
     e = hipEventCreateWithFlags(&c->ticket_ev[i], hipEventDisableTiming);
   for (int i = 0; i < 6 && e == hipSuccess; ++i) e = hipEventCreate(&c->prof_ev[i]);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);  // default priority
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
   if (e != hipSuccess) {
     int rc = fail(PS_EHIP, "ps_create: %s", hipGetErrorString(e));
     ps_destroy(c);
@@ -205,6 +211,9 @@ void ps_destroy(ps_ctx* c) {
     if (e) (void)hipEventDestroy(e);
   for (auto& e : c->prof_ev)
     if (e) (void)hipEventDestroy(e);
+  if (c->fork_ev) (void)hipEventDestroy(c->fork_ev);
+  if (c->join_ev) (void)hipEventDestroy(c->join_ev);
+  if (c->side) (void)hipStreamDestroy(c->side);
   if (c->swap_ids_dev) (void)hipFree(c->swap_ids_dev);
   delete c;
 }
@@ -385,11 +394,23 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
 
   if (k_new) PS_HIP(ps::launch_append(P, b->n_tokens, stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
+  // Decode streams the cache at HBM speed and leaves the matrix pipes idle, prefill is the
+  // opposite: with both kinds of work in the batch, run them side by side.
+  const bool fork = !prof && !c->cfg.serial_kernels && !c->ditems.empty() && !c->ptiles.empty();
+  if (fork) {
+    PS_HIP(hipEventRecord(c->fork_ev, stream));
+    PS_HIP(hipStreamWaitEvent(c->side, c->fork_ev, 0));
+    PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), c->side));
+    PS_HIP(hipEventRecord(c->join_ev, c->side));
+  }
   PS_HIP(ps::launch_decode(P, (int)c->ditems.size(), stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[3], stream));
   PS_HIP(ps::launch_merge(P, (int)c->mitems.size(), stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[4], stream));
-  PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), stream));
+  if (fork)
+    PS_HIP(hipStreamWaitEvent(stream, c->join_ev, 0));
+  else
+    PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), stream));
   if (prof) {
     PS_HIP(hipEventRecord(c->prof_ev[5], stream));
     c->prof_valid = true;
