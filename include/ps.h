@@ -93,13 +93,16 @@ typedef struct {
 
 const char* ps_last_error(void);
 
-/* Creates a context on the current HIP device. The context owns only small pinned staging
- * buffers, events and a few KB of device memory. PS_EINVAL on a bad cfg. */
+/* Creates a context on the current HIP device. The context owns small pinned staging buffers,
+ * events, two internal streams (default priority) and two device copies of the batch description
+ * (the arrays of ps_batch plus work lists, about 5 bytes per block-table entry; they grow, with
+ * a hipMalloc inside ps_step, when a batch is larger than any before). PS_EINVAL on a bad cfg. */
 int ps_create(const ps_layer_cfg* cfg, ps_ctx** out);
 void ps_destroy(ps_ctx* ctx);
 
-/* Device workspace needed by ps_step for any batch with n_req <= max_req,
- * n_tokens <= max_tokens and at most max_table_entries block-table entries. */
+/* Device workspace (split-K partial results of the decode kernels) needed by ps_step for any
+ * batch with n_req <= max_req, n_tokens <= max_tokens and at most max_table_entries block-table
+ * entries. */
 int ps_workspace_bytes(const ps_ctx* ctx, int32_t max_req, int32_t max_tokens,
                        int64_t max_table_entries, size_t* out_bytes);
 
@@ -114,8 +117,13 @@ int ps_workspace_bytes(const ps_ctx* ctx, int32_t max_req, int32_t max_tokens,
  *   kv_cache DEVICE, layout above, n_device_blocks blocks
  *   out      DEVICE [n_tokens][Hq][d], bf16 or f32 per cfg.out_dtype
  *   workspace DEVICE, 256-byte aligned, at least ps_workspace_bytes(...) bytes; its contents
- *            are scratch and may be reused by the next call on the same stream
- *   hip_stream  hipStream_t (NULL = default stream); all work is enqueued there
+ *            are scratch and may be reused by the next call on the same stream (calls on
+ *            different streams need different workspaces)
+ *   hip_stream  hipStream_t (NULL = default stream); the step is ordered on it: it starts after
+ *            the stream's earlier work and the stream's later work starts after it. Inside the
+ *            step the batch description is uploaded on the context's copy stream (so the upload
+ *            of one step overlaps the kernels of the previous one) and, unless
+ *            cfg.serial_kernels, the prefill kernel runs on the context's second stream
  *   wait_ticket 0, or a ticket from ps_swap_in/ps_swap_out: the stream waits for that copy
  *            to complete before any kernel of this step runs (Appendix B: compute
  *            synchronises on the reload's event only just before it needs the blocks)

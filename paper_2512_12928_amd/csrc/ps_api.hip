@@ -61,6 +61,17 @@ struct ps_ctx {
   hipEvent_t ticket_ev[kTicketRing];
   uint64_t ticket_id[kTicketRing];
   uint64_t next_ticket = 1;
+  // Device copies of the batch description, double-buffered so that the upload of step n+1 (on the
+  // context's copy stream) runs while the kernels of step n still read theirs.
+  struct MetaBuf {
+    char* dev = nullptr;
+    size_t cap = 0;
+    hipEvent_t uploaded = nullptr;  // on the copy stream, after the upload
+    hipEvent_t done = nullptr;      // on the caller's stream, after the last kernel that reads it
+    bool used = false;
+  } meta[2];
+  int meta_next = 0;
+  hipStream_t copy = nullptr;
   hipStream_t side = nullptr;  // prefill kernel of a step, concurrent with its decode kernels
   hipEvent_t fork_ev = nullptr, join_ev = nullptr;
   bool profiling = false;
@@ -185,6 +196,11 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
     e = hipEventCreateWithFlags(&c->ticket_ev[i], hipEventDisableTiming);
   for (int i = 0; i < 6 && e == hipSuccess; ++i) e = hipEventCreate(&c->prof_ev[i]);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);  // default priority
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
+  for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+    e = hipEventCreateWithFlags(&c->meta[i].uploaded, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->meta[i].done, hipEventDisableTiming);
+  }
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
   if (e != hipSuccess) {
@@ -214,6 +230,12 @@ void ps_destroy(ps_ctx* c) {
   if (c->fork_ev) (void)hipEventDestroy(c->fork_ev);
   if (c->join_ev) (void)hipEventDestroy(c->join_ev);
   if (c->side) (void)hipStreamDestroy(c->side);
+  if (c->copy) (void)hipStreamDestroy(c->copy);
+  for (auto& mb : c->meta) {
+    if (mb.dev) (void)hipFree(mb.dev);
+    if (mb.uploaded) (void)hipEventDestroy(mb.uploaded);
+    if (mb.done) (void)hipEventDestroy(mb.done);
+  }
   if (c->swap_ids_dev) (void)hipFree(c->swap_ids_dev);
   delete c;
 }
@@ -226,8 +248,8 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
   const int min_chunk = c->cfg.decode_chunk > 0 ? c->cfg.decode_chunk : 256;
   const size_t max_parts = (size_t)max_req + (size_t)(max_table_entries * ps::kBlockTokens / min_chunk);
   const size_t max_tiles = (size_t)max_req + (size_t)max_tokens / 32;
-  const MetaLayout m = meta_layout(max_req, max_tokens, max_table_entries, max_parts, (size_t)max_req, max_tiles);
-  *out_bytes = m.total + align_up(max_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256);
+  (void)max_tiles;
+  *out_bytes = align_up(max_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256) + 256;
   return PS_OK;
 }
 
@@ -344,8 +366,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
 
   const MetaLayout ml = meta_layout(n_req, b->n_tokens, n_table, c->ditems.size(), c->mitems.size(), c->ptiles.size());
   const size_t part_bytes = align_up((size_t)n_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256);
-  if (ml.total + part_bytes > workspace_bytes)
-    return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", ml.total + part_bytes, workspace_bytes);
+  if (part_bytes > workspace_bytes)
+    return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", part_bytes, workspace_bytes);
 
   // ---- stage + upload metadata
   StageSlot& slot = c->step_slot[c->step_next];
@@ -362,14 +384,34 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   if (!c->mitems.empty()) std::memcpy(h + ml.mitems, c->mitems.data(), c->mitems.size() * sizeof(ps::MergeItem));
   if (!c->ptiles.empty()) std::memcpy(h + ml.ptiles, c->ptiles.data(), c->ptiles.size() * sizeof(ps::PrefillTile));
 
+  // upload on the copy stream into the buffer that step n-2 used, once that step is done with it
+  ps_ctx::MetaBuf& mb = c->meta[c->meta_next];
+  c->meta_next ^= 1;
+  if (mb.cap < ml.total) {  // grow (rare): nothing may still be reading the old buffer
+    if (mb.dev) {
+      PS_HIP(hipDeviceSynchronize());
+      PS_HIP(hipFree(mb.dev));
+      mb.dev = nullptr;
+      mb.cap = 0;
+    }
+    const size_t cap = align_up(ml.total + ml.total / 2, 1 << 16);
+    PS_HIP(hipMalloc((void**)&mb.dev, cap));
+    mb.cap = cap;
+    mb.used = false;
+  }
+  if (mb.used) PS_HIP(hipStreamWaitEvent(c->copy, mb.done, 0));
+  PS_HIP(hipMemcpyAsync(mb.dev, h, ml.total, hipMemcpyHostToDevice, c->copy));
+  PS_HIP(hipEventRecord(slot.ev, c->copy));
+  slot.in_flight = true;
+  PS_HIP(hipEventRecord(mb.uploaded, c->copy));
+  mb.used = true;
+
   if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
   const bool prof = c->profiling;
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
-  char* w = (char*)workspace;
-  PS_HIP(hipMemcpyAsync(w, h, ml.total, hipMemcpyHostToDevice, stream));
-  PS_HIP(hipEventRecord(slot.ev, stream));
-  slot.in_flight = true;
+  PS_HIP(hipStreamWaitEvent(stream, mb.uploaded, 0));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[1], stream));
+  char* w = mb.dev;
 
   ps::StepParams P;
   P.q_start = (const int32_t*)(w + ml.q_start);
@@ -380,7 +422,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   P.ditems = (const ps::DecodeItem*)(w + ml.ditems);
   P.mitems = (const ps::MergeItem*)(w + ml.mitems);
   P.ptiles = (const ps::PrefillTile*)(w + ml.ptiles);
-  P.partials = (float*)(w + ml.total);
+  P.partials = (float*)workspace;
   P.q = (const uint16_t*)q;
   P.k_new = (const uint16_t*)k_new;
   P.v_new = (const uint16_t*)v_new;
@@ -415,6 +457,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     PS_HIP(hipEventRecord(c->prof_ev[5], stream));
     c->prof_valid = true;
   }
+  PS_HIP(hipEventRecord(mb.done, stream));
   return PS_OK;
 }
 

@@ -297,7 +297,7 @@ __global__ __launch_bounds__(128) void merge_kernel(StepParams P) {
 constexpr int kPrefillWaves = 8;
 constexpr int kPrefillRows = 32;    // query tokens per wave
 constexpr int kPrefillKV = 64;      // KV tokens per pipeline step
-constexpr int kStages = 3;
+constexpr int kStages = 4;
 constexpr int kLoadsPerTile = 4;    // global->LDS loads each wave issues per tile
 
 // s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding)
@@ -338,6 +338,9 @@ struct PrefillStage {
 
 __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams P, int HW, int n_zsplit) {
   __shared__ PrefillStage sm[kStages];
+  // This kernel may share the chip with the HBM-bound decode kernel of the same step, whose many
+  // waves mostly wait on memory: let the SIMD arbiter prefer these compute-bound waves.
+  __builtin_amdgcn_s_setprio(3);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 31;   // row of the K operand / query column of Q, P, O

@@ -167,9 +167,11 @@ def test_empty_batch_and_validation_errors():
     expect(B.PS_EINVAL, q_start=qs)                      # l_q = 0
     kv = b.kv_len.copy(); kv[4] = 63
     expect(B.PS_EINVAL, kv_len=kv)                       # l_q > kv_len
+    small = Layer(b, decode_chunk=32)                    # split-K partials need a workspace
     with pytest.raises(B.PsError) as e:
-        B.ps_step(lay.ctx, b, q, None, None, cache_dev, out, ws, 1024)
+        B.ps_step(small.ctx, b, q, None, None, cache_dev, out, ws, 1024)
     assert e.value.code == B.PS_ENOMEM
+    small.close()
     with pytest.raises(B.PsError) as e:
         B.ps_step(lay.ctx, b, q, q, None, cache_dev, out, ws, lay.ws_bytes)
     assert e.value.code == B.PS_EINVAL
