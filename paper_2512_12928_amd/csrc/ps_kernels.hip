@@ -328,6 +328,14 @@ __device__ __forceinline__ float xor32_max(float x) {
   return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
 }
 
+// max of three without the NaN-quieting moves the compiler wraps around fmaxf of MFMA results
+// (the inputs here are never NaN: finite scores or -inf)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 struct PrefillHalf {
   uint4 k[8][64];
   uint4 v[8][64];
@@ -457,6 +465,15 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
 
     if (active && ts <= my_last) {
       const PrefillStage& S = sm[stage];
+      // all 16 K fragments of the tile are requested from LDS before the first MFMA needs one,
+      // and the 16 V fragments right behind them, so that LDS latency is paid once per tile, not
+      // once per MFMA (left alone, the compiler sinks every ds_read next to its MFMA)
+      bf16x8 kf[2][8], vf[2][8];
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) kf[hf][c] = as_bf16x8(S.h[hf].k[c][lane]);
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 s[2];
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
@@ -464,8 +481,13 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
         for (int e = 0; e < 16; ++e) s[hf][e] = 0.f;
 #pragma unroll
         for (int c = 0; c < 8; ++c)
-          s[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(S.h[hf].k[c][lane]), qop[c], s[hf], 0, 0, 0);
+          s[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[hf][c], qop[c], s[hf], 0, 0, 0);
       }
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int f = 0; f < 8; ++f) vf[hf][f] = as_bf16x8(S.h[hf].v[f][lane]);
+      __builtin_amdgcn_sched_barrier(0);
       // s[hf][e]: token ts + 32*hf + 16*(e/8) + 8*h2 + e%8, query q0 + j (raw dot products)
       if (ts + kPrefillKV - 1 > p + q0) {  // diagonal tile (wave-uniform test)
 #pragma unroll
@@ -476,9 +498,12 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
             if (tok > qpos) s[hf][e] = PS_NEG_INF;
           }
       }
-      float tmax = fmaxf(s[0][0], s[1][0]);
+      float tmax = max3(s[0][0], s[0][1], s[1][0]);
 #pragma unroll
-      for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, fmaxf(s[0][e], s[1][e]));
+      for (int e = 2; e < 16; e += 2) tmax = max3(tmax, s[0][e], s[0][e + 1]);
+#pragma unroll
+      for (int e = 1; e < 15; e += 2) tmax = max3(tmax, s[1][e], s[1][e + 1]);
+      tmax = fmaxf(tmax, s[1][15]);
       tmax = xor32_max(tmax) * P.scale_log2;
       // m is finite from the first tile on (key 0 is visible to every query); a row that sees
       // nothing in this tile keeps its m
@@ -506,7 +531,7 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
           const bf16x8 pop = as_bf16x8(pv);
 #pragma unroll
           for (int n = 0; n < 4; ++n)
-            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(S.h[hf].v[u * 4 + n][lane]), pop, acc[n], 0, 0, 0);
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][u * 4 + n], pop, acc[n], 0, 0, 0);
         }
       }
     }
