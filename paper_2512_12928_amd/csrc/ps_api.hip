@@ -81,7 +81,7 @@ struct ps_ctx {
   std::vector<ps::DecodeItem> ditems;
   std::vector<ps::MergeItem> mitems;
   std::vector<ps::PrefillTile> ptiles;
-  std::vector<int32_t> tok_req;
+  std::vector<ps::AppendItem> aitems;
   std::vector<int32_t> seen;  // duplicate detection in swap lists
 };
 
@@ -101,10 +101,10 @@ int pick_decode_chunk(const ps_ctx* c, int64_t decode_kv_tokens) {
 
 // Bytes of the metadata block for given sizes (also the layout used by ps_step).
 struct MetaLayout {
-  size_t q_start, kv_len, bt_start, block_ids, tok_req, ditems, mitems, ptiles, total;
+  size_t q_start, kv_len, bt_start, block_ids, aitems, ditems, mitems, ptiles, total;
 };
 
-MetaLayout meta_layout(int n_req, int n_tokens, int64_t n_table, size_t n_ditems, size_t n_mitems,
+MetaLayout meta_layout(int n_req, size_t n_aitems, int64_t n_table, size_t n_ditems, size_t n_mitems,
                        size_t n_ptiles) {
   MetaLayout m;
   size_t o = 0;
@@ -117,7 +117,7 @@ MetaLayout meta_layout(int n_req, int n_tokens, int64_t n_table, size_t n_ditems
   m.kv_len = put((size_t)n_req * 4);
   m.bt_start = put((size_t)(n_req + 1) * 4);
   m.block_ids = put((size_t)n_table * 4);
-  m.tok_req = put((size_t)n_tokens * 4);
+  m.aitems = put((size_t)n_aitems * sizeof(ps::AppendItem));
   m.ditems = put(n_ditems * sizeof(ps::DecodeItem));
   m.mitems = put(n_mitems * sizeof(ps::MergeItem));
   m.ptiles = put(n_ptiles * sizeof(ps::PrefillTile));
@@ -336,7 +336,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   c->ditems.clear();
   c->mitems.clear();
   c->ptiles.clear();
-  c->tok_req.resize((size_t)b->n_tokens);
+  c->aitems.clear();
   int n_parts = 0;
   struct TileKey {
     int64_t reach;
@@ -345,7 +345,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   std::vector<TileKey> tiles;
   for (int r = 0; r < n_req; ++r) {
     const int qs = b->q_start[r], lq = b->q_start[r + 1] - qs, L = b->kv_len[r];
-    for (int t = 0; t < lq; ++t) c->tok_req[(size_t)qs + t] = r;
+    if (k_new)
+      for (int lb = (L - lq) / ps::kBlockTokens; lb * ps::kBlockTokens < L; ++lb) c->aitems.push_back(ps::AppendItem{r, lb});
     if (lq == 1) {
       const int np = (L + CH - 1) / CH;
       if (np == 1) {
@@ -364,7 +365,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
   for (auto& t : tiles) c->ptiles.push_back(t.t);
 
-  const MetaLayout ml = meta_layout(n_req, b->n_tokens, n_table, c->ditems.size(), c->mitems.size(), c->ptiles.size());
+  const MetaLayout ml = meta_layout(n_req, c->aitems.size(), n_table, c->ditems.size(), c->mitems.size(), c->ptiles.size());
   const size_t part_bytes = align_up((size_t)n_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256);
   if (part_bytes > workspace_bytes)
     return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", part_bytes, workspace_bytes);
@@ -379,7 +380,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   std::memcpy(h + ml.kv_len, b->kv_len, (size_t)n_req * 4);
   std::memcpy(h + ml.bt_start, b->bt_start, (size_t)(n_req + 1) * 4);
   std::memcpy(h + ml.block_ids, b->block_ids, (size_t)n_table * 4);
-  std::memcpy(h + ml.tok_req, c->tok_req.data(), c->tok_req.size() * 4);
+  if (!c->aitems.empty()) std::memcpy(h + ml.aitems, c->aitems.data(), c->aitems.size() * sizeof(ps::AppendItem));
   if (!c->ditems.empty()) std::memcpy(h + ml.ditems, c->ditems.data(), c->ditems.size() * sizeof(ps::DecodeItem));
   if (!c->mitems.empty()) std::memcpy(h + ml.mitems, c->mitems.data(), c->mitems.size() * sizeof(ps::MergeItem));
   if (!c->ptiles.empty()) std::memcpy(h + ml.ptiles, c->ptiles.data(), c->ptiles.size() * sizeof(ps::PrefillTile));
@@ -418,7 +419,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   P.kv_len = (const int32_t*)(w + ml.kv_len);
   P.bt_start = (const int32_t*)(w + ml.bt_start);
   P.block_ids = (const int32_t*)(w + ml.block_ids);
-  P.tok_req = (const int32_t*)(w + ml.tok_req);
+  P.aitems = (const ps::AppendItem*)(w + ml.aitems);
   P.ditems = (const ps::DecodeItem*)(w + ml.ditems);
   P.mitems = (const ps::MergeItem*)(w + ml.mitems);
   P.ptiles = (const ps::PrefillTile*)(w + ml.ptiles);
@@ -434,7 +435,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   P.out_f32 = c->cfg.out_dtype == PS_F32;
   P.scale_log2 = c->scale_log2;
 
-  if (k_new) PS_HIP(ps::launch_append(P, b->n_tokens, stream));
+  if (k_new) PS_HIP(ps::launch_append(P, (int)c->aitems.size(), stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
   // Decode streams the cache at HBM speed and leaves the matrix pipes idle, prefill is the
   // opposite: with both kinds of work in the batch, run them side by side.

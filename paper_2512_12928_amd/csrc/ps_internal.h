@@ -31,6 +31,12 @@ struct MergeItem {
   int32_t pad;
 };
 
+// The new rows of one request that fall into one of its logical blocks.
+struct AppendItem {
+  int32_t req;
+  int32_t lblock;  // logical block index of the request
+};
+
 // One tile of consecutive query tokens of a prefill chunk.
 struct PrefillTile {
   int32_t req;
@@ -43,7 +49,7 @@ struct StepParams {
   const int32_t* kv_len;
   const int32_t* bt_start;
   const int32_t* block_ids;
-  const int32_t* tok_req;  // [n_tokens] request index of each batch token
+  const AppendItem* aitems;
   const DecodeItem* ditems;
   const MergeItem* mitems;
   const PrefillTile* ptiles;
@@ -60,7 +66,7 @@ struct StepParams {
 };
 
 // Launchers (ps_kernels.hip). Each checks its own launch and returns the hipError_t.
-hipError_t launch_append(const StepParams& p, int n_tokens, hipStream_t s);
+hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s);
 hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s);
 hipError_t launch_merge(const StepParams& p, int n_merge, hipStream_t s);
 // tile_tokens: query tokens per workgroup tile as returned by prefill_tile_tokens(G).

@@ -56,21 +56,39 @@ __device__ __forceinline__ const uint16_t* v_slice(const uint16_t* cache, int bl
 }
 
 // ------------------------------------------------------------------------------------ append
-// Writes this step's new K/V rows into the paged cache.  grid (n_tokens, Hkv), 128 threads:
-// thread x moves dim x.  K rows stay contiguous; V goes to the dim-major slot (stride 16).
+// Writes this step's new K/V rows into the paged cache.  grid (n_items, Hkv), 128 threads: a
+// workgroup owns the new rows of one request that fall into one logical block, thread x moves
+// dim x.  K rows stay contiguous.  V is dim-major inside a block: when the chunk covers the
+// whole block, thread x gathers its dim from the 16 rows and writes one full 32-byte run;
+// otherwise (a decode token, the ragged ends of a chunk) it writes 2-byte elements at stride 16.
 __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
-  const int tok = blockIdx.x, g = blockIdx.y, x = threadIdx.x;
-  const int r = P.tok_req[tok];
+  const AppendItem it = P.aitems[blockIdx.x];
+  const int g = blockIdx.y, x = threadIdx.x;
+  const int r = it.req;
   const int qs = P.q_start[r];
-  const int lq = P.q_start[r + 1] - qs;
-  const int pos = P.kv_len[r] - lq + (tok - qs);
-  const int b = P.block_ids[P.bt_start[r] + (pos >> 4)];
-  const int t = pos & 15;
-  const size_t src = ((size_t)tok * P.Hkv + g) * kHeadDim + x;
+  const int L = P.kv_len[r];
+  const int p = L - (P.q_start[r + 1] - qs);
+  const int b0 = it.lblock * kBlockTokens;
+  const int lo = p > b0 ? p : b0;                                    // first new position in this block
+  const int hi = L < b0 + kBlockTokens ? L : b0 + kBlockTokens;      // one past the last
+  const int b = P.block_ids[P.bt_start[r] + it.lblock];
   uint16_t* kd = const_cast<uint16_t*>(k_slice(P.cache, b, P.Hkv, g));
   uint16_t* vd = const_cast<uint16_t*>(v_slice(P.cache, b, P.Hkv, g));
-  kd[t * kHeadDim + x] = P.k_new[src];
-  vd[x * kBlockTokens + t] = P.v_new[src];
+  const size_t row0 = ((size_t)(qs + lo - p) * P.Hkv + g) * kHeadDim + x;  // batch token of position lo
+  const size_t rstride = (size_t)P.Hkv * kHeadDim;
+  for (int t = lo; t < hi; ++t) kd[(t - b0) * kHeadDim + x] = P.k_new[row0 + (size_t)(t - lo) * rstride];
+  if (hi - lo == kBlockTokens) {
+    uint32_t w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      w[i] = (uint32_t)P.v_new[row0 + (size_t)(2 * i) * rstride] |
+             ((uint32_t)P.v_new[row0 + (size_t)(2 * i + 1) * rstride] << 16);
+    uint4* dst = (uint4*)(vd + x * kBlockTokens);
+    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+  } else {
+    for (int t = lo; t < hi; ++t) vd[x * kBlockTokens + (t - b0)] = P.v_new[row0 + (size_t)(t - lo) * rstride];
+  }
 }
 
 // ------------------------------------------------------------------------------------ decode
@@ -589,9 +607,9 @@ __global__ __launch_bounds__(256) void block_copy_kernel(const int32_t* __restri
 }
 
 // ------------------------------------------------------------------------------------ launchers
-hipError_t launch_append(const StepParams& p, int n_tokens, hipStream_t s) {
-  if (n_tokens <= 0) return hipSuccess;
-  hipLaunchKernelGGL(append_kernel, dim3(n_tokens, p.Hkv), dim3(128), 0, s, p);
+hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s) {
+  if (n_items <= 0) return hipSuccess;
+  hipLaunchKernelGGL(append_kernel, dim3(n_items, p.Hkv), dim3(128), 0, s, p);
   return hipGetLastError();
 }
 
