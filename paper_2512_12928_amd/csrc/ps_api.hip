@@ -361,6 +361,9 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       for (int q0 = 0; q0 < lq; q0 += TT) tiles.push_back(TileKey{(int64_t)p + q0, ps::PrefillTile{r, q0}});
     }
   }
+  // longest partitions first, so that the tail of the decode launch is made of short ones
+  std::stable_sort(c->ditems.begin(), c->ditems.end(),
+                   [](const ps::DecodeItem& a, const ps::DecodeItem& b2) { return a.t1 - a.t0 > b2.t1 - b2.t0; });
   // heaviest tiles (longest causal reach) first, so the tail of the launch is made of short ones
   std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
   for (auto& t : tiles) c->ptiles.push_back(t.t);
