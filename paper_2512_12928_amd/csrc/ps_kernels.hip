@@ -156,11 +156,21 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
   const bool v_in_b = kg >= 2;
 
   const int ntiles = (it.t1 - it.t0 + kTileTokens - 1) / kTileTokens;
+  // block ids are fetched one tile ahead, so the table lookup is off the address path of the loads
+  int nextA = 0, nextB = 0;
+  if (wave < ntiles) {
+    const int bA = (it.t0 + wave * kTileTokens) >> 4;
+    nextA = table[bA];
+    nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;  // absent second block: masked below
+  }
   for (int tile = wave; tile < ntiles; tile += 4) {
     const int ts = it.t0 + tile * kTileTokens;
-    const int bA = ts >> 4;
-    const int idA = table[bA];
-    const int idB = (bA + 1 < nblk) ? table[bA + 1] : idA;  // absent second block: masked below
+    const int idA = nextA, idB = nextB;
+    if (tile + 4 < ntiles) {
+      const int bA = (ts + 4 * kTileTokens) >> 4;
+      nextA = table[bA];
+      nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;
+    }
     const uint16_t* kp = k_slice(P.cache, k_in_b ? idB : idA, Hkv, g) + krow_off;
     const uint16_t* vp = v_slice(P.cache, v_in_b ? idB : idA, Hkv, g) + v_off;
 
