@@ -19,10 +19,12 @@
  *
  * KV cache layout (device, bf16), chosen so that both attention contractions read their
  * operands as contiguous 16-byte runs:
- *     cache[b][0][g][t][x]   K of block b, kv-head g, token slot t (0..15), dim x   (token-major)
- *     cache[b][1][g][x][t]   V of block b, kv-head g, dim x, token slot t           (dim-major)
+ *     cache[b][0][g][x/8][t][x%8]  K of block b, kv-head g, token slot t (0..15), dim x
+ *                                  (groups of 8 dims; inside a group token-major)
+ *     cache[b][1][g][x][t]         V of block b, kv-head g, dim x, token slot t   (dim-major)
  *   i.e. element offsets, with blk = block_tokens and d = head_dim:
- *     K: (((b*2 + 0)*Hkv + g)*blk + t)*d + x        V: (((b*2 + 1)*Hkv + g)*d + x)*blk + t
+ *     K: ((((b*2 + 0)*Hkv + g)*(d/8) + x/8)*blk + t)*8 + x%8
+ *     V: (((b*2 + 1)*Hkv + g)*d + x)*blk + t
  *   One block is one contiguous run of 2*Hkv*blk*d*2 bytes (64 KiB at Hkv = 8); a swap moves
  *   whole runs, so the host copy of a block has the same internal layout.
  *   Token j of a request lives in block  block_ids[bt_start[r] + j / blk], slot j % blk.

@@ -7,9 +7,9 @@
 // probabilities that lane computes are then, without any cross-lane movement, exactly the
 // B operand of the second product
 //   O^T[dim][qrow] += V^T[dim][token] . P^T[token][qrow]   (A = V^T tile, B = P^T)
-// and the per-row rescale factors of the online softmax are per-lane scalars.  K is stored
-// token-major and V dim-major inside a block, so both A operands are plain 16-byte (K) or
-// 8-byte (V) loads from the cache.
+// and the per-row rescale factors of the online softmax are per-lane scalars.  Inside a block K
+// is stored [dim/8][token][8 dims] and V [dim][token], so every A-operand lane is one 16-byte
+// load and the lanes of one load instruction cover runs of 256 bytes or more.
 #include "ps_internal.h"
 
 namespace ps {
@@ -58,7 +58,7 @@ __device__ __forceinline__ const uint16_t* v_slice(const uint16_t* cache, int bl
 // ------------------------------------------------------------------------------------ append
 // Writes this step's new K/V rows into the paged cache.  grid (n_items, Hkv), 128 threads: a
 // workgroup owns the new rows of one request that fall into one logical block, thread x moves
-// dim x.  K rows stay contiguous.  V is dim-major inside a block: when the chunk covers the
+// dim x.  K goes to [dim/8][token][8].  V is dim-major inside a block: when the chunk covers the
 // whole block, thread x gathers its dim from the 16 rows and writes one full 32-byte run;
 // otherwise (a decode token, the ragged ends of a chunk) it writes 2-byte elements at stride 16.
 __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
@@ -76,7 +76,8 @@ __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
   uint16_t* vd = const_cast<uint16_t*>(v_slice(P.cache, b, P.Hkv, g));
   const size_t row0 = ((size_t)(qs + lo - p) * P.Hkv + g) * kHeadDim + x;  // batch token of position lo
   const size_t rstride = (size_t)P.Hkv * kHeadDim;
-  for (int t = lo; t < hi; ++t) kd[(t - b0) * kHeadDim + x] = P.k_new[row0 + (size_t)(t - lo) * rstride];
+  for (int t = lo; t < hi; ++t)
+    kd[(x >> 3) * (kBlockTokens * 8) + (t - b0) * 8 + (x & 7)] = P.k_new[row0 + (size_t)(t - lo) * rstride];
   if (hi - lo == kBlockTokens) {
     uint32_t w[8];
 #pragma unroll
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
   for (int n = 0; n < 8; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   // per-lane element offsets inside a (block, head) slice
-  const int krow_off = (8 * ((j >> 2) & 1) + (j & 3)) * kHeadDim + kg * 8;  // first score MFMA; second: +4 rows
+  const int krow_off = kg * (kBlockTokens * 8) + (8 * ((j >> 2) & 1) + (j & 3)) * 8;  // first score MFMA; second: +4 slots
   const bool k_in_b = (j >> 3) != 0;                                         // K rows 8..15 come from block B
   const int v_off = j * kBlockTokens + 8 * (kg & 1);                         // + n*16 dims
   const bool v_in_b = kg >= 2;
@@ -177,8 +178,8 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
     bf16x8 k1[4], k2[4], vv[8];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      k1[c] = load_stream16(kp + c * 32);
-      k2[c] = load_stream16(kp + 4 * kHeadDim + c * 32);
+      k1[c] = load_stream16(kp + c * 4 * (kBlockTokens * 8));
+      k2[c] = load_stream16(kp + c * 4 * (kBlockTokens * 8) + 4 * 8);
     }
 #pragma unroll
     for (int n = 0; n < 8; ++n) vv[n] = load_stream16(vp + n * 16 * kBlockTokens);
@@ -443,8 +444,8 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
       const int idA = id[2 * hf], idB = id[2 * hf + 1];
-      const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + kslot * kHeadDim;
-      load_to_lds16(krow + (f * 2 + h2) * 8, st + (uint32_t)hf * 16384u + (uint32_t)f * 1024u);
+      const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + kslot * 8;
+      load_to_lds16(krow + (f * 2 + h2) * (kBlockTokens * 8), st + (uint32_t)hf * 16384u + (uint32_t)f * 1024u);
       const uint16_t* vs = v_slice(P.cache, u == 0 ? idA : idB, Hkv, g) + (n * 32 + j) * kBlockTokens + 8 * h2;
       load_to_lds16(vs, st + (uint32_t)hf * 16384u + 8192u + (uint32_t)f * 1024u);
     }

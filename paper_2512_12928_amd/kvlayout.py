@@ -1,5 +1,6 @@
 """The library's KV-cache layout (see include/ps.h) as numpy index permutations:
-K token-major  cache[b][0][g][t][x],  V dim-major  cache[b][1][g][x][t].
+K  cache[b][0][g][x/8][t][x%8]  (groups of 8 dims, token-major inside a group),
+V  cache[b][1][g][x][t]  (dim-major).
 
 Converts between that device layout and the plain logical array pool[M, 2, Hkv, blk, d]
 (0 = K, 1 = V; token-major for both), e.g. to import an existing cache or to read one back.
@@ -11,7 +12,7 @@ def to_device_layout(pool: np.ndarray) -> np.ndarray:
     """logical pool [M,2,Hkv,blk,d] (bf16 bits) -> flat uint16 [M, 2*Hkv*blk*d] in device layout."""
     M, two, Hkv, blk, d = pool.shape
     out = np.empty((M, 2, Hkv, blk * d), dtype=np.uint16)
-    out[:, 0] = pool[:, 0].reshape(M, Hkv, blk * d)
+    out[:, 0] = pool[:, 0].reshape(M, Hkv, blk, d // 8, 8).transpose(0, 1, 3, 2, 4).reshape(M, Hkv, blk * d)
     out[:, 1] = pool[:, 1].transpose(0, 1, 3, 2).reshape(M, Hkv, blk * d)
     return out.reshape(M, -1)
 
@@ -20,7 +21,7 @@ def from_device_layout(flat: np.ndarray, Hkv: int, blk: int = 16, d: int = 128) 
     M = flat.shape[0]
     v = flat.reshape(M, 2, Hkv, blk * d)
     pool = np.empty((M, 2, Hkv, blk, d), dtype=np.uint16)
-    pool[:, 0] = v[:, 0].reshape(M, Hkv, blk, d)
+    pool[:, 0] = v[:, 0].reshape(M, Hkv, d // 8, blk, 8).transpose(0, 1, 3, 2, 4).reshape(M, Hkv, blk, d)
     pool[:, 1] = v[:, 1].reshape(M, Hkv, d, blk).transpose(0, 1, 3, 2)
     return pool
 
