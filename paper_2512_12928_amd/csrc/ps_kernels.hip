@@ -95,17 +95,18 @@ __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
 // ------------------------------------------------------------------------------------ decode
 // Split-K decode attention, HBM-bound.  grid (n_items, Hkv), 256 threads = 4 waves.
 // The workgroup owns KV tokens [t0, t1) of one request for one kv-head and all G query heads
-// of that head (padded to the 16 columns of a 16x16x32 MFMA), so every K/V byte is read once.
-// Wave w streams the 32-token tiles w, w+4, ...; per tile it issues 16 non-temporal 16-byte
-// loads per lane (8 KiB K + 8 KiB V; the cache is read once, nothing is worth keeping in L2),
-// 8 MFMAs for S^T and 8 for O^T.  The four waves' running (m, l, O) states are combined through
-// LDS; the result is either the final output (single partition) or an unnormalised partial for
-// the merge kernel.
+// of that head (padded to the 32 columns of a 32x32x16 MFMA: the matrix pipe has ten times the
+// throughput this kernel can feed it), so every K/V byte is read once.  Wave w streams the
+// 32-token tiles w, w+4, ...; per tile it issues 16 non-temporal 16-byte loads per lane (8 KiB K
+// + 8 KiB V; the cache is read once, nothing is worth keeping in L2), 8 MFMAs for S^T and 8 for
+// O^T.  The four waves' running (m, l, O) states are combined through LDS; the result is either
+// the final output (single partition) or an unnormalised partial for the merge kernel.
 //
-// Token order inside a tile: the tile is blocks A, B.  Row i = 4q+b of the first score MFMA is
-// slot 8*(q&1)+b of block (q<2 ? A : B), of the second one slot 8*(q&1)+4+b.  In the 16x16 result
-// layout lane (head j, k-group kg) then holds the 8 consecutive tokens ts + 8*kg .. +7, which is
-// one contiguous 16-byte run of the dim-major V block: its V operand is a single load.
+// Operand order (same as the prefill kernel): row i of the K operand is token pi(i) of the tile
+// (bits 2 and 3 of i swapped; rows 0..15 block A, 16..31 block B).  One K load instruction then
+// covers, per 8-dim group, all 16 slots of a block: runs of 256 bytes.  In the 32x32 result
+// layout lane (head j, k-group h2) holds, for MFMA step u, the 8 consecutive tokens
+// 16u + 8*h2 .. +7: its V operand is one 16-byte run of the dim-major V block.
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 load_stream16(const uint16_t* p) {
@@ -121,40 +122,50 @@ __device__ __forceinline__ bf16x8 zero_from8(bf16x8 v, int first, int limit) {
   return __builtin_bit_cast(bf16x8, w);
 }
 
+// max over lanes l and l ^ 32 (both lanes get it), on the VALU: v_permlane32_swap exchanges the upper
+// half of its first operand with the lower half of its second.
+__device__ __forceinline__ float xor32_max(float x) {
+  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+  asm volatile("" : "+v"(b));  // two distinct registers for the swap
+  auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+}
+
 __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
-  extern __shared__ float smem[];  // [4][G][128] O, then [4][16] m, [4][16] l
+  extern __shared__ float smem[];  // [4][G][128] O, then [4][32] m, [4][32] l
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int j = lane & 15;   // row of the K operand / query-head column of Q, P, O
-  const int kg = lane >> 4;  // k-group of the MFMA operands
+  const int j = lane & 31;   // row of the K operand / query-head column of Q, P, O
+  const int h2 = lane >> 5;  // k-group of the MFMA operands
   const DecodeItem it = P.ditems[blockIdx.x];
   const int g = blockIdx.y;
   const int G = P.G, Hkv = P.Hkv;
   const int* table = P.block_ids + P.bt_start[it.req];
   const int nblk = (P.kv_len[it.req] + kBlockTokens - 1) >> 4;
 
-  // Q^T operand: lane (head j, k-group kg) holds dims (c*4+kg)*8 .. +7 for chunk c.
-  bf16x8 qop[4];
+  // Q^T operand: lane (head j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.
+  bf16x8 qop[8];
   {
     const uint16_t* qrow = P.q + ((size_t)it.tok * P.Hq + g * G + (j < G ? j : 0)) * kHeadDim;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      uint4 v = *(const uint4*)(qrow + (c * 4 + kg) * 8);
+    for (int c = 0; c < 8; ++c) {
+      uint4 v = *(const uint4*)(qrow + (c * 2 + h2) * 8);
       if (j >= G) v = make_uint4(0, 0, 0, 0);
       qop[c] = as_bf16x8(v);
     }
   }
 
   float m = PS_NEG_INF, l = 0.f;
-  f32x4 acc[8];
+  f32x16 acc[4];
 #pragma unroll
-  for (int n = 0; n < 8; ++n) acc[n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
 
   // per-lane element offsets inside a (block, head) slice
-  const int krow_off = kg * (kBlockTokens * 8) + (8 * ((j >> 2) & 1) + (j & 3)) * 8;  // first score MFMA; second: +4 slots
-  const bool k_in_b = (j >> 3) != 0;                                         // K rows 8..15 come from block B
-  const int v_off = j * kBlockTokens + 8 * (kg & 1);                         // + n*16 dims
-  const bool v_in_b = kg >= 2;
+  const int k_off = h2 * (kBlockTokens * 8) + (8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3)) * 8;  // + c*2 groups
+  const bool k_in_b = j >= 16;
+  const int v_off = j * kBlockTokens + 8 * h2;  // + n*32 dims
 
   const int ntiles = (it.t1 - it.t0 + kTileTokens - 1) / kTileTokens;
   // block ids are fetched one tile ahead, so the table lookup is off the address path of the loads
@@ -172,74 +183,76 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
       nextA = table[bA];
       nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;
     }
-    const uint16_t* kp = k_slice(P.cache, k_in_b ? idB : idA, Hkv, g) + krow_off;
-    const uint16_t* vp = v_slice(P.cache, v_in_b ? idB : idA, Hkv, g) + v_off;
+    const uint16_t* kp = k_slice(P.cache, k_in_b ? idB : idA, Hkv, g) + k_off;
+    const uint16_t* vA = v_slice(P.cache, idA, Hkv, g) + v_off;
+    const uint16_t* vB = v_slice(P.cache, idB, Hkv, g) + v_off;
 
-    bf16x8 k1[4], k2[4], vv[8];
+    bf16x8 kf[8], vf[2][4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      k1[c] = load_stream16(kp + c * 4 * (kBlockTokens * 8));
-      k2[c] = load_stream16(kp + c * 4 * (kBlockTokens * 8) + 4 * 8);
+    for (int c = 0; c < 8; ++c) kf[c] = load_stream16(kp + c * 2 * (kBlockTokens * 8));
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      vf[0][n] = load_stream16(vA + n * 32 * kBlockTokens);
+      vf[1][n] = load_stream16(vB + n * 32 * kBlockTokens);
     }
-#pragma unroll
-    for (int n = 0; n < 8; ++n) vv[n] = load_stream16(vp + n * 16 * kBlockTokens);
 
-    f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+    f32x16 s;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[c], qop[c], s1, 0, 0, 0);
-      s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k2[c], qop[c], s2, 0, 0, 0);
-    }
-    // s1[e]: token ts + 8*kg + e, head j.   s2[e]: token ts + 8*kg + 4 + e.
-    float s[8];
-    const int tok0 = ts + 8 * kg;
+    for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      s[e] = (tok0 + e < it.t1) ? s1[e] * P.scale_log2 : PS_NEG_INF;
-      s[4 + e] = (tok0 + 4 + e < it.t1) ? s2[e] * P.scale_log2 : PS_NEG_INF;
+    for (int c = 0; c < 8; ++c) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c], qop[c], s, 0, 0, 0);
+    // s[e]: token ts + 16*(e/8) + 8*h2 + e%8, head j
+    float tmax = PS_NEG_INF;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int tok = ts + 16 * (e >> 3) + 8 * h2 + (e & 7);
+      s[e] = tok < it.t1 ? s[e] * P.scale_log2 : PS_NEG_INF;
+      tmax = fmaxf(tmax, s[e]);
     }
     if (ts + kTileTokens > it.t1) {  // ragged tail: slots past kv_len may hold anything
 #pragma unroll
-      for (int n = 0; n < 8; ++n) vv[n] = zero_from8(vv[n], tok0, it.t1);
-    }
-    float tmax = s[0];
+      for (int u = 0; u < 2; ++u)
 #pragma unroll
-    for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, s[e]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        for (int n = 0; n < 4; ++n) vf[u][n] = zero_from8(vf[u][n], ts + 16 * u + 8 * h2, it.t1);
+    }
+    tmax = xor32_max(tmax);
     const float m_new = fmaxf(m, tmax);  // finite: every tile holds at least one valid token
     const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-    float p[8], psum = 0.f;
+    float psum = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      p[e] = __builtin_amdgcn_exp2f(s[e] - m_new);
-      psum += p[e];
+    for (int e = 0; e < 16; ++e) {
+      s[e] = __builtin_amdgcn_exp2f(s[e] - m_new);
+      psum += s[e];
     }
     l = l * alpha + psum;
     m = m_new;
-    uint4 pv = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]),
-                pack_bf16x2(p[6], p[7])};
-    const bf16x8 pop = as_bf16x8(pv);
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-      acc[n] *= alpha;
-      acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[n], pop, acc[n], 0, 0, 0);
+    for (int n = 0; n < 4; ++n) acc[n] *= alpha;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      uint4 pv = {pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
+                  pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7])};
+      const bf16x8 pop = as_bf16x8(pv);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u][n], pop, acc[n], 0, 0, 0);
     }
   }
-  l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
 
   // combine the four waves
   float* sm_o = smem;                     // [4][G][128]
-  float* sm_m = smem + 4 * G * kHeadDim;  // [4][16]
-  float* sm_l = sm_m + 64;
+  float* sm_m = smem + 4 * G * kHeadDim;  // [4][32]
+  float* sm_l = sm_m + 128;
   if (j < G) {
 #pragma unroll
-    for (int n = 0; n < 8; ++n)
-      *(f32x4*)(sm_o + ((wave * G + j) * kHeadDim) + n * 16 + kg * 4) = acc[n];
-    if (kg == 0) {
-      sm_m[wave * 16 + j] = m;
-      sm_l[wave * 16 + j] = l;
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int a = 0; a < 4; ++a)  // acc[n][4a+b] is dim 32n + 8a + 4*h2 + b
+        *(f32x4*)(sm_o + ((wave * G + j) * kHeadDim) + n * 32 + a * 8 + h2 * 4) =
+            (f32x4){acc[n][4 * a], acc[n][4 * a + 1], acc[n][4 * a + 2], acc[n][4 * a + 3]};
+    if (h2 == 0) {
+      sm_m[wave * 32 + j] = m;
+      sm_l[wave * 32 + j] = l;
     }
   }
   __syncthreads();
@@ -248,14 +261,14 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
     float mw[4], mstar = PS_NEG_INF;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      mw[w] = sm_m[w * 16 + h];
+      mw[w] = sm_m[w * 32 + h];
       mstar = fmaxf(mstar, mw[w]);
     }
     float L = 0.f, o = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const float f = __builtin_amdgcn_exp2f(mw[w] - mstar);  // idle wave: m = -inf -> 0
-      L += sm_l[w * 16 + h] * f;
+      L += sm_l[w * 32 + h] * f;
       o += sm_o[(w * G + h) * kHeadDim + x] * f;
     }
     const int head = g * G + h;
@@ -346,15 +359,6 @@ __device__ __forceinline__ void load_ids(const int* p0, const int* p1, const int
       "s_load_dword %3, %7, 0x0\n\ts_waitcnt lgkmcnt(0)"
       : "=&s"(id[0]), "=&s"(id[1]), "=&s"(id[2]), "=&s"(id[3])
       : "s"(p0), "s"(p1), "s"(p2), "s"(p3));
-}
-
-// max over lanes l and l ^ 32 (both lanes get it), on the VALU: v_permlane32_swap exchanges the upper
-// half of its first operand with the lower half of its second.
-__device__ __forceinline__ float xor32_max(float x) {
-  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
-  asm volatile("" : "+v"(b));  // two distinct registers for the swap
-  auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
-  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
 }
 
 // max of three without the NaN-quieting moves the compiler wraps around fmaxf of MFMA results
@@ -626,7 +630,7 @@ hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s) {
 
 hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
-  const size_t smem = (size_t)(4 * p.G * kHeadDim + 128) * sizeof(float);
+  const size_t smem = (size_t)(4 * p.G * kHeadDim + 256) * sizeof(float);
   hipLaunchKernelGGL(decode_kernel, dim3(n_items, p.Hkv), dim3(256), smem, s, p);
   return hipGetLastError();
 }
