@@ -131,7 +131,7 @@ __device__ __forceinline__ float xor32_max(float x) {
   return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
 }
 
-__global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
+__global__ __launch_bounds__(256, 3) void decode_kernel(StepParams P) {
   extern __shared__ float smem[];  // [4][G][128] O, then [4][32] m, [4][32] l
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -143,17 +143,20 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
   const int* table = P.block_ids + P.bt_start[it.req];
   const int nblk = (P.kv_len[it.req] + kBlockTokens - 1) >> 4;
 
-  // Q^T operand: lane (head j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.
-  bf16x8 qop[8];
-  {
+  // Q^T operand: lane (head j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.  It is the same
+  // for the four waves and is kept in LDS in operand order (one conflict-free 16-byte read per lane
+  // and MFMA) rather than in 32 registers per lane: that is what lets three waves share a SIMD.
+  __shared__ uint4 q_lds[8][64];
+  if (wave == 0) {
     const uint16_t* qrow = P.q + ((size_t)it.tok * P.Hq + g * G + (j < G ? j : 0)) * kHeadDim;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       uint4 v = *(const uint4*)(qrow + (c * 2 + h2) * 8);
       if (j >= G) v = make_uint4(0, 0, 0, 0);
-      qop[c] = as_bf16x8(v);
+      q_lds[c][lane] = v;
     }
   }
+  __syncthreads();
 
   float m = PS_NEG_INF, l = 0.f;
   f32x16 acc[4];
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(256) void decode_kernel(StepParams P) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c], qop[c], s, 0, 0, 0);
+    for (int c = 0; c < 8; ++c) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c], as_bf16x8(q_lds[c][lane]), s, 0, 0, 0);
     // s[e]: token ts + 16*(e/8) + 8*h2 + e%8, head j
     float tmax = PS_NEG_INF;
 #pragma unroll
