@@ -89,13 +89,13 @@ namespace {
 
 int pick_decode_chunk(const ps_ctx* c, int64_t decode_kv_tokens) {
   if (c->cfg.decode_chunk > 0) return c->cfg.decode_chunk;
-  // aim at ~3500 workgroups per launch (about 14 per CU over 256 CUs): long partitions keep the
-  // per-partition start-up and the partials traffic small, enough of them keep every CU fed.
-  // Partitions are multiples of 128 tokens so the four waves of a workgroup get whole tiles.
-  int64_t ch = decode_kv_tokens * c->cfg.n_kv_heads / 3500;
+  // aim at ~1800 workgroups per launch (7 per CU over 256 CUs; measured sweep): long partitions
+  // keep the per-partition start-up and the partials traffic small, enough of them keep every CU
+  // fed.  Partitions are multiples of 128 tokens so the four waves of a workgroup get whole tiles.
+  int64_t ch = decode_kv_tokens * c->cfg.n_kv_heads / 1800;
   ch = (ch + 127) / 128 * 128;
   if (ch < 256) ch = 256;
-  if (ch > 2048) ch = 2048;
+  if (ch > 4096) ch = 4096;
   return (int)ch;
 }
 
