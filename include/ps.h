@@ -72,7 +72,10 @@ typedef struct {
                               on a stream owned by the context, forked from and joined to the
                               caller's stream with events); 1: every kernel on the caller's
                               stream, one after another. Profiled steps are always serial.   */
-  int32_t reserved;
+  int32_t prefill_split_tiles; /* 0 (default): the library splits the KV range of long prefill
+                              rows over several workgroups (partials merged like decode's) when
+                              the launch would otherwise be unbalanced; N > 0: always split into
+                              partitions of N 64-token KV tiles; -1: never split               */
 } ps_layer_cfg;
 
 /* One mixed batch (the output of Alg. 1 as the attention layer sees it). HOST arrays. */

@@ -173,6 +173,8 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
     return fail(PS_EINVAL, "decode_chunk must be 0 or a multiple of 32 in [32, 65536]");
   if (cfg->swap_workgroups < 0 || cfg->swap_workgroups > 65536) return fail(PS_EINVAL, "bad swap_workgroups");
   if (cfg->serial_kernels != 0 && cfg->serial_kernels != 1) return fail(PS_EINVAL, "serial_kernels must be 0 or 1");
+  if (cfg->prefill_split_tiles < -1 || cfg->prefill_split_tiles > 65536)
+    return fail(PS_EINVAL, "prefill_split_tiles must be -1, 0 or a positive tile count");
   if (!(cfg->softmax_scale >= 0.f) || std::isinf(cfg->softmax_scale))
     return fail(PS_EINVAL, "softmax_scale must be finite and >= 0");
 
@@ -249,7 +251,8 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
   const size_t max_parts = (size_t)max_req + (size_t)(max_table_entries * ps::kBlockTokens / min_chunk);
   const size_t max_tiles = (size_t)max_req + (size_t)max_tokens / 32;
   (void)max_tiles;
-  *out_bytes = align_up(max_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256) + 256;
+  // + up to two partial slots per batch token for prefill rows whose KV range is split
+  *out_bytes = align_up((max_parts + 2 * (size_t)max_tokens) * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256) + 256;
   return PS_OK;
 }
 
@@ -358,13 +361,64 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       }
     } else {
       const int p = L - lq;
-      for (int q0 = 0; q0 < lq; q0 += TT) tiles.push_back(TileKey{(int64_t)p + q0, ps::PrefillTile{r, q0}});
+      for (int q0 = 0; q0 < lq; q0 += TT) {
+        const int last = std::min(q0 + TT, lq) - 1;  // KV tiles (64 tokens) any query of the tile can see
+        tiles.push_back(TileKey{(p + last) / 64 + 1, ps::PrefillTile{r, q0, 0, 0, -1, 1, 0, 0}});
+      }
     }
   }
   // longest partitions first, so that the tail of the decode launch is made of short ones
   std::stable_sort(c->ditems.begin(), c->ditems.end(),
                    [](const ps::DecodeItem& a, const ps::DecodeItem& b2) { return a.t1 - a.t0 > b2.t1 - b2.t0; });
-  // heaviest tiles (longest causal reach) first, so the tail of the launch is made of short ones
+
+  // Prefill: a query tile walks `reach` KV tiles.  When the longest walk is much longer than a CU's
+  // fair share of all walks, the launch ends with a few workgroups running alone; then the long
+  // walks are cut into partitions whose partial results the merge kernel combines.
+  const int n_decode_merge = (int)c->mitems.size();
+  {
+    const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
+    int64_t total = 0, longest = 0;
+    for (auto& t : tiles) {
+      total += t.reach;
+      longest = std::max(longest, t.reach);
+    }
+    const int64_t share = (total * wg_per_tile + 255) / 256;  // KV tiles per CU if spread evenly
+    int64_t split = 0;                                        // partition length in KV tiles; 0 = none
+    if (c->cfg.prefill_split_tiles > 0)
+      split = c->cfg.prefill_split_tiles;
+    else if (c->cfg.prefill_split_tiles == 0 && longest * 4 > share * 5 + 16)
+      split = std::max<int64_t>(8, share);
+    // partial slots: budget of two per batch token, and whatever the caller's workspace holds
+    const size_t slot_bytes = (size_t)c->cfg.n_q_heads * ps::kPartStride * sizeof(float);
+    int64_t budget = std::min<int64_t>(2 * (int64_t)b->n_tokens, (int64_t)(workspace_bytes / slot_bytes) - n_parts);
+    std::vector<TileKey> cut;
+    for (auto& t : tiles) {
+      const int qs = b->q_start[t.t.req], lq = b->q_start[t.t.req + 1] - qs;
+      const int rows = std::min(TT, lq - t.t.q0);
+      int np = split > 0 ? (int)std::min<int64_t>((t.reach + split - 1) / split, 8) : 1;
+      if (np > 1 && (int64_t)rows * np > budget) np = 1;
+      if (np == 1) {
+        t.t.tile_end = (int32_t)t.reach;
+        cut.push_back(t);
+        continue;
+      }
+      budget -= (int64_t)rows * np;
+      const int len = (int)((t.reach + np - 1) / np);
+      for (int k = 0; k < np; ++k) {
+        ps::PrefillTile q = t.t;
+        q.tile_begin = k * len;
+        q.tile_end = (int32_t)std::min<int64_t>((int64_t)(k + 1) * len, t.reach);
+        q.part = n_parts;
+        q.n_parts = np;
+        q.k = k;
+        cut.push_back(TileKey{q.tile_end - q.tile_begin, q});
+      }
+      for (int row = 0; row < rows; ++row) c->mitems.push_back(ps::MergeItem{qs + t.t.q0 + row, n_parts + row * np, np, 0});
+      n_parts += rows * np;
+    }
+    tiles.swap(cut);
+  }
+  // heaviest partitions first, so the tail of the launch is made of short ones
   std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
   for (auto& t : tiles) c->ptiles.push_back(t.t);
 
@@ -447,16 +501,19 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     PS_HIP(hipEventRecord(c->fork_ev, stream));
     PS_HIP(hipStreamWaitEvent(c->side, c->fork_ev, 0));
     PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), c->side));
+    PS_HIP(ps::launch_merge(P, n_decode_merge, (int)c->mitems.size() - n_decode_merge, c->side));  // split prefill rows
     PS_HIP(hipEventRecord(c->join_ev, c->side));
   }
   PS_HIP(ps::launch_decode(P, (int)c->ditems.size(), stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[3], stream));
-  PS_HIP(ps::launch_merge(P, (int)c->mitems.size(), stream));
+  PS_HIP(ps::launch_merge(P, 0, n_decode_merge, stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[4], stream));
-  if (fork)
+  if (fork) {
     PS_HIP(hipStreamWaitEvent(stream, c->join_ev, 0));
-  else
+  } else {
     PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), stream));
+    PS_HIP(ps::launch_merge(P, n_decode_merge, (int)c->mitems.size() - n_decode_merge, stream));
+  }
   if (prof) {
     PS_HIP(hipEventRecord(c->prof_ev[5], stream));
     c->prof_valid = true;

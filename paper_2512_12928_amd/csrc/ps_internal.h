@@ -37,10 +37,16 @@ struct AppendItem {
   int32_t lblock;  // logical block index of the request
 };
 
-// One tile of consecutive query tokens of a prefill chunk.
+// One tile of consecutive query tokens of a prefill chunk, over one range of its KV tiles.
 struct PrefillTile {
   int32_t req;
-  int32_t q0;  // chunk-relative index of the tile's first query token
+  int32_t q0;          // chunk-relative index of the tile's first query token
+  int32_t tile_begin;  // first 64-token KV tile of this partition
+  int32_t tile_end;    // one past its last KV tile (the kernel also stops at the causal reach)
+  int32_t part;        // -1: the only partition, write the output; else first partials slot of the tile
+  int32_t n_parts;     // partitions of this query tile
+  int32_t k;           // index of this partition: token t of the tile uses slot part + t*n_parts + k
+  int32_t pad;
 };
 
 struct StepParams {
@@ -68,7 +74,8 @@ struct StepParams {
 // Launchers (ps_kernels.hip). Each checks its own launch and returns the hipError_t.
 hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s);
 hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s);
-hipError_t launch_merge(const StepParams& p, int n_merge, hipStream_t s);
+// merges items [first, first + n_merge) of the merge list
+hipError_t launch_merge(const StepParams& p, int first, int n_merge, hipStream_t s);
 // tile_tokens: query tokens per workgroup tile as returned by prefill_tile_tokens(G).
 hipError_t launch_prefill(const StepParams& p, int n_tiles, hipStream_t s);
 int prefill_tile_tokens(int G);

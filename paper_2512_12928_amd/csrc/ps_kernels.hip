@@ -293,9 +293,9 @@ __global__ __launch_bounds__(256, 3) void decode_kernel(StepParams P) {
   }
 }
 
-// Combines the split-K partials of one decode token.  grid (n_merge, Hq), 128 threads (dims).
-__global__ __launch_bounds__(128) void merge_kernel(StepParams P) {
-  const MergeItem it = P.mitems[blockIdx.x];
+// Combines the split-K partials of one token (decode, or a prefill row whose KV range was split).  grid (n_merge, Hq), 128 threads (dims).
+__global__ __launch_bounds__(128) void merge_kernel(StepParams P, int first) {
+  const MergeItem it = P.mitems[first + blockIdx.x];
   const int head = blockIdx.y, x = threadIdx.x;
   const float* base = P.partials + ((size_t)it.part0 * P.Hq + head) * kPartStride;
   const size_t stride = (size_t)P.Hq * kPartStride;
@@ -424,7 +424,10 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
     for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
 
   const int wg_last = (t.q0 + SUB * kPrefillRows < lq ? t.q0 + SUB * kPrefillRows : lq) - 1;
-  const int ntiles = (p + wg_last) / kPrefillKV + 1;                            // workgroup-uniform
+  const int reach = (p + wg_last) / kPrefillKV + 1;  // KV tiles any query of the workgroup can see
+  const int tile0 = t.tile_begin;                    // this partition: tiles [tile0, tile1)
+  const int tile1 = t.tile_end < reach ? t.tile_end : reach;
+  const int ntiles = tile1 - tile0;                  // workgroup-uniform, >= 1
   const int my_last = p + (q0 + kPrefillRows < lq ? q0 + kPrefillRows : lq) - 1;  // last visible key
   const int qpos = p + q0 + j;
 
@@ -434,8 +437,8 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
 
   // Block ids of tile `tile` (clamped to the last tile; absent blocks repeat the last present one
   // and are fully masked).
-  auto lookup = [&](int tile, int (&id)[4]) {
-    tile = tile < ntiles ? tile : ntiles - 1;
+  auto lookup = [&](int i, int (&id)[4]) {  // i-th tile of the partition
+    const int tile = tile0 + (i < ntiles ? i : ntiles - 1);
     const int b0 = tile * (kPrefillKV / kBlockTokens);
     const int last = nblk - 1;
     load_ids(table + b0, table + (b0 + 1 < last ? b0 + 1 : last), table + (b0 + 2 < last ? b0 + 2 : last),
@@ -473,16 +476,16 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
   }
   lookup(kStages - 1, id);  // ids of the tile the first iteration will issue
 
-  for (int tile = 0; tile < ntiles; ++tile) {
-    const int stage = tile % kStages;
-    const int ts = tile * kPrefillKV;
+  for (int it = 0; it < ntiles; ++it) {
+    const int stage = it % kStages;
+    const int ts = (tile0 + it) * kPrefillKV;
     // own loads of this tile have landed (the younger ones may still fly) ...
     __builtin_amdgcn_s_waitcnt(PS_VMCNT(kLoadsPerTile * (kStages - 2)));
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();  // ... and so have everybody's; everyone is done with tile-1
     asm volatile("" ::: "memory");
-    issue((tile + kStages - 1) % kStages, id);  // tile + kStages-1 refills the slot of tile-1
-    lookup(tile + kStages, id);                  // ids for the next iteration's issue
+    issue((it + kStages - 1) % kStages, id);  // tile it + kStages-1 refills the slot of tile it-1
+    lookup(it + kStages, id);                  // ids for the next iteration's issue
 
     if (ts + kPrefillKV > L) {
       // Last tile of the request: slots past kv_len may hold anything.  The wave that fetched a V
@@ -541,22 +544,23 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
       for (int e = 1; e < 15; e += 2) tmax = max3(tmax, s[1][e], s[1][e + 1]);
       tmax = fmaxf(tmax, s[1][15]);
       tmax = xor32_max(tmax) * P.scale_log2;
-      // m is finite from the first tile on (key 0 is visible to every query); a row that sees
-      // nothing in this tile keeps its m
+      // a row that sees nothing in this tile keeps its m; a row that has seen nothing yet in this
+      // partition has m = -inf, l = 0 and all-zero accumulators
       if (__builtin_amdgcn_ballot_w64(tmax > m) != 0) {  // rescale only when some row's max grew
         const float m_new = fmaxf(m, tmax);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        const float alpha = m_new == PS_NEG_INF ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
         l *= alpha;
         m = m_new;
 #pragma unroll
         for (int n = 0; n < 4; ++n) acc[n] *= alpha;
       }
+      const float m_use = m == PS_NEG_INF ? 0.f : m;  // all scores of such a row are -inf: exp2 gives 0
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
         float psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          s[hf][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[hf][e], P.scale_log2, -m));
+          s[hf][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[hf][e], P.scale_log2, -m_use));
           psum += s[hf][e];
         }
         l += psum;
@@ -576,9 +580,10 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
 
   if (!active) return;
   const float ls = l + __shfl_xor(l, 32);
-  const float inv = 1.f / ls;
   const int row = q0 + j;
-  if (row < lq) {
+  if (row >= lq) return;
+  if (t.part < 0) {
+    const float inv = 1.f / ls;
     const size_t ob = ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
 #pragma unroll
     for (int n = 0; n < 4; ++n)
@@ -594,6 +599,19 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
           *(uint2*)((uint16_t*)P.out + ob + x) = w;
         }
       }
+  } else {  // one of several KV partitions of this row: unnormalised partial for the merge kernel
+    const int slot = t.part + (row - t.q0) * t.n_parts + t.k;
+    float* dst = P.partials + ((size_t)slot * P.Hq + head) * kPartStride;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        *(f32x4*)(dst + n * 32 + a * 8 + h2 * 4) =
+            (f32x4){acc[n][4 * a], acc[n][4 * a + 1], acc[n][4 * a + 2], acc[n][4 * a + 3]};
+    if (h2 == 0) {
+      dst[128] = m;
+      dst[129] = ls;
+    }
   }
 }
 
@@ -638,9 +656,9 @@ hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_merge(const StepParams& p, int n_merge, hipStream_t s) {
+hipError_t launch_merge(const StepParams& p, int first, int n_merge, hipStream_t s) {
   if (n_merge <= 0) return hipSuccess;
-  hipLaunchKernelGGL(merge_kernel, dim3(n_merge, p.Hq), dim3(128), 0, s, p);
+  hipLaunchKernelGGL(merge_kernel, dim3(n_merge, p.Hq), dim3(128), 0, s, p, first);
   return hipGetLastError();
 }
 

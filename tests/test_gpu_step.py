@@ -68,6 +68,19 @@ def test_split_k_partitions_and_merge(chunk):
     check_close(got, oracle_out(b, t, cache), False)
 
 
+@pytest.mark.parametrize("split", [1, 2, 3, -1])
+def test_prefill_kv_partitions(split):
+    """Prefill rows whose KV range is cut into partitions of `split` 64-token tiles and merged: same result
+    as unsplit (-1), for chunks with and without prefix, ragged ends, rows that see nothing in a partition."""
+    items = [(1, 40), (64, 64), (200, 200), (70, 70 + 333), (129, 129 + 1000), (5, 700), (33, 33 + 64), (1, 900)]
+    b, t = custom_batch(8, 2, items, seed=21)
+    got, cache = run_prefilled(b, t, prefill_split_tiles=split)
+    check_close(got, oracle_out(b, t, cache), False)
+    b, t = custom_batch(16, 2, items[:5], seed=22)          # G = 8: two head groups per workgroup tile
+    got, cache = run_prefilled(b, t, prefill_split_tiles=split)
+    check_close(got, oracle_out(b, t, cache), False)
+
+
 @pytest.mark.parametrize("idx,scale", [(2, 0.08), (4, 0.04), (5, 0.06)])
 def test_scaled_workloads(idx, scale):
     b = W.make_workload(idx, scale=scale)
