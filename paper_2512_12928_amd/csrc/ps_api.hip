@@ -77,7 +77,6 @@ struct ps_ctx {
   bool profiling = false;
   hipEvent_t prof_ev[6];
   bool prof_valid = false;
-  bool prof_phase[5];
   std::vector<ps::DecodeItem> ditems;
   std::vector<ps::MergeItem> mitems;
   std::vector<ps::PrefillTile> ptiles;

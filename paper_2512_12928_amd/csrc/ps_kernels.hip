@@ -28,16 +28,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
-__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
-  return __builtin_bit_cast(float, (uint32_t)b << 16);
-}
-
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-__device__ __forceinline__ bf16x8 join_bf16x4(uint2 lo, uint2 hi) {
-  uint4 v = {lo.x, lo.y, hi.x, hi.y};
-  return __builtin_bit_cast(bf16x8, v);
-}
 
 // Zero the 16-bit elements e (0..3) of v whose token index first+e is >= limit.
 __device__ __forceinline__ uint2 zero_from(uint2 v, int first, int limit) {
@@ -348,9 +339,15 @@ constexpr int kLoadsPerTile = 4;    // global->LDS loads each wave issues per ti
 // s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding)
 #define PS_VMCNT(n) (((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
-// One lane's 16 bytes at `gptr` -> LDS at lds_base + lane*16 (lds_base wave-uniform).
+// One lane's 16 bytes at `gptr` -> LDS at lds_base + lane*16 (lds_base wave-uniform).  The LDS
+// base travels in M0, which is saved and restored around the load.
 __device__ __forceinline__ void load_to_lds16(const void* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+  uint32_t saved;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+      : "=&s"(saved)
+      : "v"(gptr), "s"(lds_base)
+      : "memory");
 }
 
 // Four block-table entries through the scalar cache.  Written as asm because the compiler will
