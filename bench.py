@@ -20,7 +20,7 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of decode_kernel + merge_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by a plain 1 GiB copy; summary in profiles/attention_kernels_hbm_traffic_pmc.md), by workload index.
-MEASURED_DECODE_TRAFFIC = {2: 1.555e9 + 1.179e7, 4: 3.181e9 + 9.299e6}
+MEASURED_DECODE_TRAFFIC = {2: 1.488e9 + 1.2e7, 4: 3.032e9 + 5.3e6}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
