@@ -401,8 +401,9 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
         cut.push_back(t);
         continue;
       }
-      budget -= (int64_t)rows * np;
       const int len = (int)((t.reach + np - 1) / np);
+      np = (int)((t.reach + len - 1) / len);  // no empty partition: every one starts inside the reach
+      budget -= (int64_t)rows * np;
       for (int k = 0; k < np; ++k) {
         ps::PrefillTile q = t.t;
         q.tile_begin = k * len;

@@ -334,7 +334,8 @@ constexpr int kPrefillWaves = 8;
 constexpr int kPrefillRows = 32;    // query tokens per wave
 constexpr int kPrefillKV = 64;      // KV tokens per pipeline step
 constexpr int kStages = 4;
-constexpr int kLoadsPerTile = 4;    // global->LDS loads each wave issues per tile
+constexpr int kLoadsPerTile = 4;
+constexpr int kIdTiles = 512;       // block ids of up to this many KV tiles (32k tokens) are kept in LDS    // global->LDS loads each wave issues per tile
 
 // s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding)
 #define PS_VMCNT(n) (((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
@@ -379,6 +380,7 @@ struct PrefillStage {
 
 __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams P, int HW, int n_zsplit) {
   __shared__ PrefillStage sm[kStages];
+  __shared__ __attribute__((aligned(16))) int id_lds[kIdTiles * 4];
   // This kernel may share the chip with the HBM-bound decode kernel of the same step, whose many
   // waves mostly wait on memory: let the SIMD arbiter prefer these compute-bound waves.
   __builtin_amdgcn_s_setprio(3);
@@ -424,7 +426,8 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
   const int reach = (p + wg_last) / kPrefillKV + 1;  // KV tiles any query of the workgroup can see
   const int tile0 = t.tile_begin;                    // this partition: tiles [tile0, tile1)
   const int tile1 = t.tile_end < reach ? t.tile_end : reach;
-  const int ntiles = tile1 - tile0;                  // workgroup-uniform, >= 1
+  const int ntiles = tile1 - tile0;                  // workgroup-uniform; the host never makes it < 1
+  const int nt_ids = ntiles > 1 ? ntiles : 1;        // tiles whose block ids are looked up (never none)
   const int my_last = p + (q0 + kPrefillRows < lq ? q0 + kPrefillRows : lq) - 1;  // last visible key
   const int qpos = p + q0 + j;
 
@@ -432,20 +435,31 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
   const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
   const uint32_t sm_base = (uint32_t)(uintptr_t)(&sm[0]);  // LDS byte address of the ring
 
-  // Block ids of tile `tile` (clamped to the last tile; absent blocks repeat the last present one
-  // and are fully masked).
-  auto lookup = [&](int i, int (&id)[4]) {  // i-th tile of the partition
-    const int tile = tile0 + (i < ntiles ? i : ntiles - 1);
-    const int b0 = tile * (kPrefillKV / kBlockTokens);
-    const int last = nblk - 1;
-    load_ids(table + b0, table + (b0 + 1 < last ? b0 + 1 : last), table + (b0 + 2 < last ? b0 + 2 : last),
-             table + (b0 + 3 < last ? b0 + 3 : last), id);
+  // Block ids of the i-th tile of the partition (clamped to its last tile; absent blocks repeat the
+  // last present one and are fully masked).  For partitions of up to kIdTiles tiles the ids sit in
+  // LDS (filled below, before the ring starts): the read is issued one iteration before its use
+  // and costs no wait.  Longer partitions read them through the scalar cache and wait for it.
+  const bool ids_in_lds = nt_ids <= kIdTiles;
+  auto lookup = [&](int i, int4& idv) {
+    i = i < nt_ids ? i : nt_ids - 1;
+    if (ids_in_lds) {
+      idv = *(const int4*)&id_lds[i * 4];
+    } else {
+      const int b0 = (tile0 + i) * (kPrefillKV / kBlockTokens);
+      const int last = nblk - 1;
+      int id[4];
+      load_ids(table + b0, table + (b0 + 1 < last ? b0 + 1 : last), table + (b0 + 2 < last ? b0 + 2 : last),
+               table + (b0 + 3 < last ? b0 + 3 : last), id);
+      idv = make_int4(id[0], id[1], id[2], id[3]);
+    }
   };
   // Issues this wave's loads of one tile into ring slot `stage`: K fragment `wave` (dim chunk) and
   // V fragment `wave` (block wave/4, dims 32*(wave%4)..) of each half.  Every call issues exactly
   // kLoadsPerTile loads (past the end the last tile is fetched again): the vmcnt bookkeeping
   // below counts on it.
-  auto issue = [&](int stage, const int (&id)[4]) {
+  auto issue = [&](int stage, const int4& idv) {
+    const int id[4] = {__builtin_amdgcn_readfirstlane(idv.x), __builtin_amdgcn_readfirstlane(idv.y),
+                       __builtin_amdgcn_readfirstlane(idv.z), __builtin_amdgcn_readfirstlane(idv.w)};
     const uint32_t st = sm_base + (uint32_t)stage * (uint32_t)sizeof(PrefillStage);
     const int f = wave, u = f >> 2, n = f & 3;
 #pragma unroll
@@ -458,6 +472,15 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
     }
   };
 
+  if (ids_in_lds) {
+    const int last = nblk - 1;
+    for (int e = threadIdx.x; e < nt_ids * 4; e += kPrefillWaves * 64) {
+      const int bi = tile0 * (kPrefillKV / kBlockTokens) + e;
+      id_lds[e] = table[bi < last ? bi : last];
+    }
+    __syncthreads();
+  }
+
   // The Q loads above must be complete, and known to the compiler to be complete, before the ring
   // starts: otherwise its own vmcnt bookkeeping makes every MFMA in the loop wait for vmcnt(0),
   // which also waits for every tile in flight.
@@ -465,7 +488,7 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
   __builtin_amdgcn_s_waitcnt(PS_VMCNT(0));
   asm volatile("" ::: "memory");
 
-  int id[4];
+  int4 id;
 #pragma unroll
   for (int i = 0; i < kStages - 1; ++i) {
     lookup(i, id);
