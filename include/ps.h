@@ -67,11 +67,14 @@ typedef struct {
   int32_t decode_chunk;    /* KV tokens per split-K partition; 0 => library picks; else a
                               multiple of 32 in [32, 65536]                               */
   int32_t swap_workgroups; /* workgroups used by a swap kernel; 0 => library picks        */
-  int32_t serial_kernels;  /* 0 (default): the HBM-bound decode kernels and the MFMA-bound
-                              prefill kernel of one step run concurrently (the prefill kernel
-                              on a stream owned by the context, forked from and joined to the
-                              caller's stream with events); 1: every kernel on the caller's
-                              stream, one after another. Profiled steps are always serial.   */
+  int32_t own_streams;     /* 0 (default): every copy and kernel of a step is enqueued on the
+                              caller's stream. 1: the context creates two streams of its own
+                              (default priority): the batch description of step n+1 is uploaded
+                              while the kernels of step n run, and the MFMA-bound prefill kernel
+                              runs next to the HBM-bound decode kernels (fork/join with events).
+                              Measured gain 0-2 %; a process has few hardware queues, and streams
+                              that share one run one after another, so this is opt-in.
+                              Profiled steps always run every kernel on the caller's stream.   */
   int32_t prefill_split_tiles; /* 0 (default): the library splits the KV range of long prefill
                               rows over several workgroups (partials merged like decode's) when
                               the launch would otherwise be unbalanced; N > 0: always split into
@@ -99,7 +102,7 @@ typedef struct {
 const char* ps_last_error(void);
 
 /* Creates a context on the current HIP device. The context owns small pinned staging buffers,
- * events, two internal streams (default priority) and two device copies of the batch description
+ * events, with cfg.own_streams two streams, and two device copies of the batch description
  * (the arrays of ps_batch plus work lists, about 5 bytes per block-table entry; they grow, with
  * a hipMalloc inside ps_step, when a batch is larger than any before). PS_EINVAL on a bad cfg. */
 int ps_create(const ps_layer_cfg* cfg, ps_ctx** out);
@@ -125,10 +128,8 @@ int ps_workspace_bytes(const ps_ctx* ctx, int32_t max_req, int32_t max_tokens,
  *            are scratch and may be reused by the next call on the same stream (calls on
  *            different streams need different workspaces)
  *   hip_stream  hipStream_t (NULL = default stream); the step is ordered on it: it starts after
- *            the stream's earlier work and the stream's later work starts after it. Inside the
- *            step the batch description is uploaded on the context's copy stream (so the upload
- *            of one step overlaps the kernels of the previous one) and, unless
- *            cfg.serial_kernels, the prefill kernel runs on the context's second stream
+ *            the stream's earlier work and the stream's later work starts after it (with
+ *            cfg.own_streams parts of it run on the context's streams in between)
  *   wait_ticket 0, or a ticket from ps_swap_in/ps_swap_out: the stream waits for that copy
  *            to complete before any kernel of this step runs (Appendix B: compute
  *            synchronises on the reload's event only just before it needs the blocks)

@@ -171,7 +171,7 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
       (cfg->decode_chunk < kMinChunk || cfg->decode_chunk > 65536 || cfg->decode_chunk % 32 != 0))
     return fail(PS_EINVAL, "decode_chunk must be 0 or a multiple of 32 in [32, 65536]");
   if (cfg->swap_workgroups < 0 || cfg->swap_workgroups > 65536) return fail(PS_EINVAL, "bad swap_workgroups");
-  if (cfg->serial_kernels != 0 && cfg->serial_kernels != 1) return fail(PS_EINVAL, "serial_kernels must be 0 or 1");
+  if (cfg->own_streams != 0 && cfg->own_streams != 1) return fail(PS_EINVAL, "own_streams must be 0 or 1");
   if (cfg->prefill_split_tiles < -1 || cfg->prefill_split_tiles > 65536)
     return fail(PS_EINVAL, "prefill_split_tiles must be -1, 0 or a positive tile count");
   if (!(cfg->softmax_scale >= 0.f) || std::isinf(cfg->softmax_scale))
@@ -196,8 +196,10 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   for (int i = 0; i < kTicketRing && e == hipSuccess; ++i)
     e = hipEventCreateWithFlags(&c->ticket_ev[i], hipEventDisableTiming);
   for (int i = 0; i < 6 && e == hipSuccess; ++i) e = hipEventCreate(&c->prof_ev[i]);
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);  // default priority
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
+  if (cfg->own_streams) {
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);  // default priority
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
+  }
   for (int i = 0; i < 2 && e == hipSuccess; ++i) {
     e = hipEventCreateWithFlags(&c->meta[i].uploaded, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->meta[i].done, hipEventDisableTiming);
@@ -457,17 +459,23 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     mb.cap = cap;
     mb.used = false;
   }
-  if (mb.used) PS_HIP(hipStreamWaitEvent(c->copy, mb.done, 0));
-  PS_HIP(hipMemcpyAsync(mb.dev, h, ml.total, hipMemcpyHostToDevice, c->copy));
-  PS_HIP(hipEventRecord(slot.ev, c->copy));
-  slot.in_flight = true;
-  PS_HIP(hipEventRecord(mb.uploaded, c->copy));
-  mb.used = true;
-
-  if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
   const bool prof = c->profiling;
-  if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
-  PS_HIP(hipStreamWaitEvent(stream, mb.uploaded, 0));
+  if (c->copy) {  // own copy stream: the upload does not wait for the caller's earlier work
+    if (mb.used) PS_HIP(hipStreamWaitEvent(c->copy, mb.done, 0));
+    PS_HIP(hipMemcpyAsync(mb.dev, h, ml.total, hipMemcpyHostToDevice, c->copy));
+    PS_HIP(hipEventRecord(slot.ev, c->copy));
+    PS_HIP(hipEventRecord(mb.uploaded, c->copy));
+    if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
+    if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
+    PS_HIP(hipStreamWaitEvent(stream, mb.uploaded, 0));
+  } else {  // everything on the caller's stream (the two buffers still alternate)
+    if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
+    if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
+    PS_HIP(hipMemcpyAsync(mb.dev, h, ml.total, hipMemcpyHostToDevice, stream));
+    PS_HIP(hipEventRecord(slot.ev, stream));
+  }
+  slot.in_flight = true;
+  mb.used = true;
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[1], stream));
   char* w = mb.dev;
 
@@ -496,7 +504,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
   // Decode streams the cache at HBM speed and leaves the matrix pipes idle, prefill is the
   // opposite: with both kinds of work in the batch, run them side by side.
-  const bool fork = !prof && !c->cfg.serial_kernels && !c->ditems.empty() && !c->ptiles.empty();
+  const bool fork = !prof && c->side && !c->ditems.empty() && !c->ptiles.empty();
   if (fork) {
     PS_HIP(hipEventRecord(c->fork_ev, stream));
     PS_HIP(hipStreamWaitEvent(c->side, c->fork_ev, 0));
@@ -518,7 +526,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     PS_HIP(hipEventRecord(c->prof_ev[5], stream));
     c->prof_valid = true;
   }
-  PS_HIP(hipEventRecord(mb.done, stream));
+  if (c->copy) PS_HIP(hipEventRecord(mb.done, stream));
   return PS_OK;
 }
 

@@ -381,9 +381,6 @@ struct PrefillStage {
 __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams P, int HW, int n_zsplit) {
   __shared__ PrefillStage sm[kStages];
   __shared__ __attribute__((aligned(16))) int id_lds[kIdTiles * 4];
-  // This kernel may share the chip with the HBM-bound decode kernel of the same step, whose many
-  // waves mostly wait on memory: let the SIMD arbiter prefer these compute-bound waves.
-  __builtin_amdgcn_s_setprio(3);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 31;   // row of the K operand / query column of Q, P, O
@@ -557,6 +554,10 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void prefill_kernel(StepParams 
             if (tok > qpos) s[hf][e] = PS_NEG_INF;
           }
       }
+      // max3 is inline asm, so the compiler does not count the wait states the ISA requires between an
+      // MFMA and a VALU read of its result (11 for these 8-pass MFMAs); the 16 V-fragment reads above
+      // already separate them, the NOPs make it independent of instruction scheduling
+      asm volatile("s_nop 7\n\ts_nop 3" ::: "memory");
       float tmax = max3(s[0][0], s[0][1], s[1][0]);
 #pragma unroll
       for (int e = 2; e < 16; e += 2) tmax = max3(tmax, s[0][e], s[0][e + 1]);

@@ -68,6 +68,28 @@ def test_split_k_partitions_and_merge(chunk):
     check_close(got, oracle_out(b, t, cache), False)
 
 
+def test_own_streams_fork_join_matches():
+    """cfg.own_streams: upload on the context's copy stream, prefill next to decode on its second stream;
+    several steps back to back on a non-default stream, each equal to the oracle."""
+    b = W.make_workload(2, scale=0.08)
+    t = W.make_tensors(b)
+    cache = oracle_cache(b, t)
+    want = oracle_out(b, t, cache)
+    lay = Layer(b, own_streams=1, decode_chunk=64, prefill_split_tiles=1)
+    cache_dev, q = u16_to_dev(to_device_layout(cache.pool)), u16_to_dev(t.q)
+    st = torch.cuda.Stream()
+    outs = []
+    ws = lay.workspace(b)
+    for _ in range(4):
+        o = torch.full((b.n_tokens, b.shape.n_q_heads, 128), float("nan"), dtype=torch.float32, device=DEV)
+        B.ps_step(lay.ctx, b, q, None, None, cache_dev, o, ws, lay.ws_bytes, st)
+        outs.append(o)
+    st.synchronize()
+    for o in outs:
+        check_close(o.cpu().numpy().astype(np.float64), want, False)
+    lay.close()
+
+
 @pytest.mark.parametrize("split", [1, 2, 3, -1])
 def test_prefill_kv_partitions(split):
     """Prefill rows whose KV range is cut into partitions of `split` 64-token tiles and merged: same result
