@@ -56,7 +56,6 @@ struct ps_ctx {
   StageSlot step_slot[kStepSlots];
   int step_next = 0;
   StageSlot swap_slot[kSwapSlots];
-  int32_t* swap_ids_dev = nullptr;  // [kSwapSlots][2][kMaxSwap]
   int swap_next = 0;
   hipEvent_t ticket_ev[kTicketRing];
   uint64_t ticket_id[kTicketRing];
@@ -188,7 +187,6 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   for (auto& e : c->prof_ev) e = nullptr;
   for (auto& t : c->ticket_id) t = 0;
   hipError_t e = hipGetDevice(&c->device);
-  if (e == hipSuccess) e = hipMalloc((void**)&c->swap_ids_dev, (size_t)kSwapSlots * 2 * kMaxSwap * sizeof(int32_t));
   for (int i = 0; i < kStepSlots && e == hipSuccess; ++i)
     e = hipEventCreateWithFlags(&c->step_slot[i].ev, hipEventDisableTiming);
   for (int i = 0; i < kSwapSlots && e == hipSuccess; ++i)
@@ -239,7 +237,6 @@ void ps_destroy(ps_ctx* c) {
     if (mb.uploaded) (void)hipEventDestroy(mb.uploaded);
     if (mb.done) (void)hipEventDestroy(mb.done);
   }
-  if (c->swap_ids_dev) (void)hipFree(c->swap_ids_dev);
   delete c;
 }
 
@@ -560,6 +557,7 @@ static int swap_common(ps_ctx* c, bool out_dir, const int32_t* dev_ids, const in
   hipStream_t stream = (hipStream_t)side_stream;
 
   const int si = c->swap_next;
+  (void)si;
   c->swap_next = (c->swap_next + 1) % kSwapSlots;
   StageSlot& slot = c->swap_slot[si];
   int rc = acquire_slot(slot, (size_t)2 * kMaxSwap * sizeof(int32_t));
@@ -567,8 +565,10 @@ static int swap_common(ps_ctx* c, bool out_dir, const int32_t* dev_ids, const in
   int32_t* h = (int32_t*)slot.pinned;
   std::memcpy(h, dev_ids, (size_t)m * 4);
   std::memcpy(h + m, host_ids, (size_t)m * 4);
-  int32_t* d = c->swap_ids_dev + (size_t)si * 2 * kMaxSwap;
-  PS_HIP(hipMemcpyAsync(d, h, (size_t)2 * m * 4, hipMemcpyHostToDevice, stream));
+  // The kernel reads the ids straight from the pinned staging slot (one small read over the host
+  // link in its prologue).  A separate host-to-device copy of the ids in front of every kernel put
+  // a link round trip, queued behind the bulk traffic, between consecutive copy kernels.
+  int32_t* d = h;
   // measured next to a running attention step: 8 workgroups move more than 32 or 128 do
   const int wgs = c->cfg.swap_workgroups > 0 ? c->cfg.swap_workgroups : 8;
   if (out_dir)
