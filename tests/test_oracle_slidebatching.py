@@ -247,3 +247,94 @@ def test_eviction_takes_from_tail_and_spares_near_starved():
     sb.reqs[2].out_len = 1
     nxt = sb.form_batch(2000 * MS)
     assert len(nxt.swap_in) <= nxt.b_copy
+
+
+# ---------------------------------------------------------------- hand-worked cases for the block-management readings
+def test_offload_threshold_ladder_by_class():
+    """n_off halves per class (8, 4, 2 for classes 1, 2, 3): a 96-token prompt (6 full blocks) is offloaded at
+    once by class 3 and class 2, not yet by class 1."""
+    cfg = base_cfg()
+    assert [cfg.n_off(p) for p in (1, 2, 3, 4, 5)] == [8, 4, 2, 1, 1]
+    sb = S.SlideBatcher(cfg, list(range(64)), list(range(64)))
+    for rid, prio in ((0, 1), (1, 2), (2, 3)):
+        sb.add_request(rid, 0, prio, 96, 40)
+    res = sb.form_batch(0)
+    out_by_req = {rid: [d for d, _ in res.swap_out if d in sb.reqs[rid].dev_blocks[:6]] for rid in (0, 1, 2)}
+    assert len(out_by_req[0]) == 0 and len(out_by_req[1]) == 6 and len(out_by_req[2]) == 6
+    # 32 decode steps later class 1 has 8 full blocks and offloads them in one go
+    now = res.t_batch
+    total = 0
+    for _ in range(32):
+        r = sb.form_batch(now)
+        now += r.t_batch
+        total += sum(1 for d, _ in r.swap_out if d in sb.reqs[0].dev_blocks)
+    assert sb.reqs[0].computed == 128 and len(sb.reqs[0].host_slots) == 8 and total == 8
+
+
+def test_decode_token_is_atomic_and_may_overshoot_budget():
+    cfg = base_cfg(eta=3 * MS, t_c=2 * MS, ttft_slo=1 * MS, tpot_slo=1 * MS)   # every deadline already missed: t_budget = eta
+    sb = S.SlideBatcher(cfg, list(range(16384)), list(range(64)))
+    for rid in range(40):
+        sb.add_request(rid, 0, 1, 16, 400)
+    sb.form_batch(0)                                # prefill: 40 x 16 tokens
+    # each request now holds a 4000-token context so that a decode costs 141 us: 8 of them exceed the 1 ms left
+    for r in sb.reqs.values():
+        r.prompt_len, r.computed = 4000, 4000
+        r.dev_blocks = r.dev_blocks + [sb.dev_free.pop() for _ in range(250 - len(r.dev_blocks))]
+    res = sb.form_batch(10 * MS)
+    n = len(res.batch)
+    per = S.t_decode(cfg, 4001)
+    assert res.t_budget == cfg.eta and all(lq == 1 for _, lq, _ in res.batch)
+    assert cfg.t_c + (n - 1) * per < cfg.eta <= cfg.t_c + n * per       # stops right after crossing the budget
+    assert res.t_batch == cfg.t_c + n * per
+
+
+def test_partial_reload_rule_and_recompute():
+    """A victim with 8 host blocks when the copy budget works out to 0 (copying a block costs far more than
+    recomputing it): nothing is reloaded, the host copies are released and the request recomputes from token
+    0 -- allowed because the chunk finishes the request's outstanding tokens."""
+    cfg = base_cfg(t_block=10 * MS, eta=35 * MS, ttft_slo=1 * MS, tpot_slo=1 * MS, n_off_base=1)
+    sb = S.SlideBatcher(cfg, list(range(32)), list(range(32)))
+    sb.add_request(0, 0, 2, 128, 50)
+    r0 = sb.form_batch(0)
+    assert len(r0.swap_out) == 8 and len(sb.reqs[0].host_slots) == 8
+    victim = sb.reqs[0]
+    for b in victim.dev_blocks:                     # evict by hand: device blocks back to the pool
+        sb.dev_free.append(b)
+    victim.dev_blocks = []
+    victim.computed = 128
+    res = sb.form_batch(1000 * MS)
+    # case (1): T_fwd^min >= t_budget?  exec(decode, 129) + t_c = 2 ms + 3.4 us < 35 ms -> case 2; T_trans^max = 80 ms > T_fwd^min
+    # -> case 2(ii): largest B with B*10ms <= T_fwd + (8-B)*16*c_p = 2.0394 ms + (8-B)*28.8us -> B = 0
+    assert res.b_copy == 0 and res.swap_in == []
+    # with budget 0 the request recomputes everything: allowed, the chunk (129 tokens) completes it
+    assert res.batch == [(0, 129, 129)] and len(victim.dev_blocks) == 9
+    # the 8 stale host copies were released, and the 8 recomputed full blocks were offloaded afresh (n_off = 1)
+    assert len(res.swap_out) == 8 and len(victim.host_slots) == 8 and len(sb.host_free) == 32 - 8
+    assert [d for d, _ in res.swap_out] == victim.dev_blocks[:8]
+
+
+def test_partial_reload_is_refused_when_progress_is_too_small():
+    """Same victim, but only 100 us of latency budget: the chunk that fits (55 tokens) neither finishes the
+    request (129 outstanding) nor exceeds beta * (tokens left to recompute) = 2 * 8 * 16 -> the request is
+    skipped this round and keeps its host copies."""
+    roomy = base_cfg(t_block=10 * MS, eta=35 * MS, ttft_slo=1 * MS, tpot_slo=1 * MS, n_off_base=1)
+    tight = base_cfg(t_block=10 * MS, eta=2 * MS + 100 * US, t_c=2 * MS, ttft_slo=1 * MS, tpot_slo=1 * MS, n_off_base=1)
+    sb = S.SlideBatcher(roomy, list(range(32)), list(range(32)))
+    sb.add_request(0, 0, 2, 128, 50)
+    sb.form_batch(0)                                 # whole prompt, first token, 8 blocks offloaded
+    victim = sb.reqs[0]
+    assert victim.computed == 128 and victim.generated == 1 and len(victim.host_slots) == 8
+    for b in victim.dev_blocks:                      # evict by hand
+        sb.dev_free.append(b)
+    victim.dev_blocks = []
+    sb.cfg = tight
+    res = sb.form_batch(1000 * MS)
+    assert res.t_budget == tight.eta and res.b_copy == 0
+    assert S.max_chunk(tight, 129, 0, 100 * US) == 55      # a_p c^2 + c_p c <= 100 us
+    assert res.batch == [] and len(victim.host_slots) == 8 and victim.computed == 128 and res.t_batch == 0
+    # with beta = 1/4 the same 55 tokens are enough progress (55 * 4 > 1 * 128): admitted, host copies released
+    sb.cfg = base_cfg(t_block=10 * MS, eta=2 * MS + 100 * US, t_c=2 * MS, ttft_slo=1 * MS, tpot_slo=1 * MS,
+                      n_off_base=1, beta_num=1, beta_den=4)
+    res = sb.form_batch(1001 * MS)
+    assert res.batch == [(0, 55, 55)] and res.swap_in == [] and len(victim.dev_blocks) == 4
