@@ -347,7 +347,11 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   for (int r = 0; r < n_req; ++r) {
     const int qs = b->q_start[r], lq = b->q_start[r + 1] - qs, L = b->kv_len[r];
     if (k_new)
-      for (int lb = (L - lq) / ps::kBlockTokens; lb * ps::kBlockTokens < L; ++lb) c->aitems.push_back(ps::AppendItem{r, lb});
+      for (int lb = (L - lq) / ps::kBlockTokens; lb * ps::kBlockTokens < L; ++lb) {
+        const int b0 = lb * ps::kBlockTokens;
+        const int lo = std::max(L - lq, b0), hi = std::min(L, b0 + ps::kBlockTokens);  // new positions in this block
+        c->aitems.push_back(ps::AppendItem{b->block_ids[b->bt_start[r] + lb], qs + lo - (L - lq), lo - b0, hi - lo});
+      }
     if (lq == 1) {
       const int np = (L + CH - 1) / CH;
       if (np == 1) {
@@ -468,7 +472,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   } else {  // everything on the caller's stream (the two buffers still alternate)
     if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
     if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
-    PS_HIP(hipMemcpyAsync(mb.dev, h, ml.total, hipMemcpyHostToDevice, stream));
+    // a small kernel that reads the pinned slot over the host link: a third of the latency of a DMA copy
+    PS_HIP(ps::launch_upload(h, mb.dev, ml.total, stream));
     PS_HIP(hipEventRecord(slot.ev, stream));
   }
   slot.in_flight = true;

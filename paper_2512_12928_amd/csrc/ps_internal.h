@@ -31,10 +31,13 @@ struct MergeItem {
   int32_t pad;
 };
 
-// The new rows of one request that fall into one of its logical blocks.
+// The new rows of one request that fall into one of its blocks (all fields resolved on the host, so
+// that the kernel's loads depend on nothing but the item).
 struct AppendItem {
-  int32_t req;
-  int32_t lblock;  // logical block index of the request
+  int32_t block;  // physical block
+  int32_t row0;   // batch token index (row of k_new / v_new) of the first new row of the block
+  int32_t slot0;  // its slot in the block
+  int32_t n;      // number of new rows, 1..16
 };
 
 // One tile of consecutive query tokens of a prefill chunk, over one range of its KV tiles.
@@ -72,6 +75,8 @@ struct StepParams {
 };
 
 // Launchers (ps_kernels.hip). Each checks its own launch and returns the hipError_t.
+// dst (device) <- src (pinned host memory, read over the host link by the kernel), bytes a multiple of 16
+hipError_t launch_upload(const void* src_pinned, void* dst, size_t bytes, hipStream_t s);
 hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s);
 hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s);
 // merges items [first, first + n_merge) of the merge list

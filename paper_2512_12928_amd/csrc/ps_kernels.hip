@@ -16,6 +16,7 @@ namespace ps {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -46,40 +47,65 @@ __device__ __forceinline__ const uint16_t* v_slice(const uint16_t* cache, int bl
   return cache + ((size_t)(block * 2 + 1) * Hkv + g) * kSliceElems;
 }
 
+// ------------------------------------------------------------------------------------ upload
+// Device copy of the step's batch description: dst <- src, n16 units of 16 bytes.  src is pinned
+// host memory read over the host link; every lane has its loads in flight before the first store.
+__global__ __launch_bounds__(256) void upload_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int n16) {
+  const int stride = gridDim.x * 256;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n16; i += 4 * stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * stride < n16) v[u] = src[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (i + u * stride < n16) dst[i + u * stride] = v[u];
+  }
+}
+
 // ------------------------------------------------------------------------------------ append
 // Writes this step's new K/V rows into the paged cache.  grid (n_items, Hkv), 128 threads: a
-// workgroup owns the new rows of one request that fall into one logical block, thread x moves
-// dim x.  K goes to [dim/8][token][8].  V is dim-major inside a block: when the chunk covers the
-// whole block, thread x gathers its dim from the 16 rows and writes one full 32-byte run;
-// otherwise (a decode token, the ragged ends of a chunk) it writes 2-byte elements at stride 16.
+// workgroup owns the new rows of one request that fall into one block.  K goes to
+// [dim/8][token][8]: a thread moves 16-byte groups (token, 8 dims).  V is dim-major inside a
+// block: thread x owns dim x; when the chunk covers the whole block it gathers its dim from the
+// 16 rows and writes one full 32-byte run, otherwise (a decode token, the ragged ends of a chunk)
+// it writes 2-byte elements.  All loads of a thread are issued before its first store.
 __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
   const AppendItem it = P.aitems[blockIdx.x];
   const int g = blockIdx.y, x = threadIdx.x;
-  const int r = it.req;
-  const int qs = P.q_start[r];
-  const int L = P.kv_len[r];
-  const int p = L - (P.q_start[r + 1] - qs);
-  const int b0 = it.lblock * kBlockTokens;
-  const int lo = p > b0 ? p : b0;                                    // first new position in this block
-  const int hi = L < b0 + kBlockTokens ? L : b0 + kBlockTokens;      // one past the last
-  const int b = P.block_ids[P.bt_start[r] + it.lblock];
-  uint16_t* kd = const_cast<uint16_t*>(k_slice(P.cache, b, P.Hkv, g));
-  uint16_t* vd = const_cast<uint16_t*>(v_slice(P.cache, b, P.Hkv, g));
-  const size_t row0 = ((size_t)(qs + lo - p) * P.Hkv + g) * kHeadDim + x;  // batch token of position lo
+  uint16_t* kd = const_cast<uint16_t*>(k_slice(P.cache, it.block, P.Hkv, g));
+  uint16_t* vd = const_cast<uint16_t*>(v_slice(P.cache, it.block, P.Hkv, g));
   const size_t rstride = (size_t)P.Hkv * kHeadDim;
-  for (int t = lo; t < hi; ++t)
-    kd[(x >> 3) * (kBlockTokens * 8) + (t - b0) * 8 + (x & 7)] = P.k_new[row0 + (size_t)(t - lo) * rstride];
-  if (hi - lo == kBlockTokens) {
-    uint32_t w[8];
+  const uint16_t* ks = P.k_new + ((size_t)it.row0 * P.Hkv + g) * kHeadDim;
+  const uint16_t* vs = P.v_new + ((size_t)it.row0 * P.Hkv + g) * kHeadDim + x;
+  // rows past the item's last are replaced by its last row: the loads are unconditional (a
+  // branch around a load would make the compiler wait for every load before it)
+  const int last = it.n - 1;
+  u32x4 kv[2];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      w[i] = (uint32_t)P.v_new[row0 + (size_t)(2 * i) * rstride] |
-             ((uint32_t)P.v_new[row0 + (size_t)(2 * i + 1) * rstride] << 16);
+  for (int h = 0; h < 2; ++h) {
+    const int tt = (x + 128 * h) >> 4, grp = x & 15;
+    kv[h] = *(const u32x4*)(ks + (size_t)(tt < last ? tt : last) * rstride + grp * 8);
+  }
+  uint16_t vv[kBlockTokens];
+#pragma unroll
+  for (int tt = 0; tt < kBlockTokens; ++tt) vv[tt] = vs[(size_t)(tt < last ? tt : last) * rstride];
+  asm volatile("" : "+v"(kv[0]), "+v"(kv[1]));  // keeps the K loads up here, out of the branches below
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int tt = (x + 128 * h) >> 4, grp = x & 15;
+    if (tt < it.n) *(u32x4*)(kd + grp * (kBlockTokens * 8) + (it.slot0 + tt) * 8) = kv[h];
+  }
+  if (it.n == kBlockTokens) {
     uint4* dst = (uint4*)(vd + x * kBlockTokens);
-    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+    dst[0] = make_uint4(vv[0] | ((uint32_t)vv[1] << 16), vv[2] | ((uint32_t)vv[3] << 16), vv[4] | ((uint32_t)vv[5] << 16),
+                        vv[6] | ((uint32_t)vv[7] << 16));
+    dst[1] = make_uint4(vv[8] | ((uint32_t)vv[9] << 16), vv[10] | ((uint32_t)vv[11] << 16),
+                        vv[12] | ((uint32_t)vv[13] << 16), vv[14] | ((uint32_t)vv[15] << 16));
   } else {
-    for (int t = lo; t < hi; ++t) vd[x * kBlockTokens + (t - b0)] = P.v_new[row0 + (size_t)(t - lo) * rstride];
+#pragma unroll
+    for (int tt = 0; tt < kBlockTokens; ++tt)
+      if (tt < it.n) vd[x * kBlockTokens + it.slot0 + tt] = vv[tt];
   }
 }
 
@@ -98,7 +124,6 @@ __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
 // covers, per 8-dim group, all 16 slots of a block: runs of 256 bytes.  In the 32x32 result
 // layout lane (head j, k-group h2) holds, for MFMA step u, the 8 consecutive tokens
 // 16u + 8*h2 .. +7: its V operand is one 16-byte run of the dim-major V block.
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 load_stream16(const uint16_t* p) {
   return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4*)p));
@@ -284,26 +309,56 @@ __global__ __launch_bounds__(256, 3) void decode_kernel(StepParams P) {
   }
 }
 
-// Combines the split-K partials of one token (decode, or a prefill row whose KV range was split).  grid (n_merge, Hq), 128 threads (dims).
-__global__ __launch_bounds__(128) void merge_kernel(StepParams P, int first) {
+// Combines the split-K partials of one token (decode, or a prefill row whose KV range was split).
+// grid (n_merge, ceil(Hq/8)), 256 threads: 32 lanes per (token, head), 4 dims per lane.  The
+// partials of up to 8 partitions are loaded at once (nothing but the item is on their address
+// path); longer lists are folded in 8 at a time with a running maximum.
+__global__ __launch_bounds__(256) void merge_kernel(StepParams P, int first) {
   const MergeItem it = P.mitems[first + blockIdx.x];
-  const int head = blockIdx.y, x = threadIdx.x;
+  const int head = blockIdx.y * 8 + (threadIdx.x >> 5);
+  if (head >= P.Hq) return;
+  const int x = (threadIdx.x & 31) * 4;
   const float* base = P.partials + ((size_t)it.part0 * P.Hq + head) * kPartStride;
   const size_t stride = (size_t)P.Hq * kPartStride;
-  float mstar = PS_NEG_INF;
-  for (int k = 0; k < it.n_parts; ++k) mstar = fmaxf(mstar, base[k * stride + 128]);
-  float L = 0.f, o = 0.f;
-  for (int k = 0; k < it.n_parts; ++k) {
-    const float f = __builtin_amdgcn_exp2f(base[k * stride + 128] - mstar);
-    L += base[k * stride + 129] * f;
-    o += base[k * stride + x] * f;
+  float mstar = PS_NEG_INF, L = 0.f;
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < it.n_parts; k0 += 8) {
+    float mk[8], lk[8];
+    f32x4 ok[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int k = k0 + i < it.n_parts ? k0 + i : it.n_parts - 1;
+      const float* p = base + (size_t)k * stride;
+      mk[i] = p[128];
+      lk[i] = p[129];
+      ok[i] = *(const f32x4*)(p + x);
+    }
+    float m_new = mstar;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (k0 + i >= it.n_parts) mk[i] = PS_NEG_INF;  // a repeat of the last partition: weight 0
+      m_new = fmaxf(m_new, mk[i]);
+    }
+    // a partition whose row saw no key has m = -inf (and l = 0, o = 0): weight 0
+    const float f0 = mstar == PS_NEG_INF ? 0.f : __builtin_amdgcn_exp2f(mstar - m_new);
+    L *= f0;
+    o *= f0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float f = mk[i] == PS_NEG_INF ? 0.f : __builtin_amdgcn_exp2f(mk[i] - m_new);
+      L += lk[i] * f;
+      o += ok[i] * f;
+    }
+    mstar = m_new;
   }
   const size_t oi = ((size_t)it.tok * P.Hq + head) * kHeadDim + x;
-  const float r = o / L;
-  if (P.out_f32)
-    ((float*)P.out)[oi] = r;
-  else
-    ((uint16_t*)P.out)[oi] = (uint16_t)(pack_bf16x2(r, 0.f) & 0xFFFFu);
+  const float inv = 1.f / L;
+  if (P.out_f32) {
+    *(f32x4*)((float*)P.out + oi) = o * inv;
+  } else {
+    uint2 w = {pack_bf16x2(o[0] * inv, o[1] * inv), pack_bf16x2(o[2] * inv, o[3] * inv)};
+    *(uint2*)((uint16_t*)P.out + oi) = w;
+  }
 }
 
 // ------------------------------------------------------------------------------------ prefill
@@ -664,6 +719,14 @@ __global__ __launch_bounds__(256) void block_copy_kernel(const int32_t* __restri
 }
 
 // ------------------------------------------------------------------------------------ launchers
+hipError_t launch_upload(const void* src_pinned, void* dst, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  const int n16 = (int)(bytes / 16);
+  const int grid = std::min((n16 + 1023) / 1024, 64);  // 4 loads per lane in flight
+  hipLaunchKernelGGL(upload_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)src_pinned, (uint4*)dst, n16);
+  return hipGetLastError();
+}
+
 hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
   hipLaunchKernelGGL(append_kernel, dim3(n_items, p.Hkv), dim3(128), 0, s, p);
@@ -679,7 +742,7 @@ hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s) {
 
 hipError_t launch_merge(const StepParams& p, int first, int n_merge, hipStream_t s) {
   if (n_merge <= 0) return hipSuccess;
-  hipLaunchKernelGGL(merge_kernel, dim3(n_merge, p.Hq), dim3(128), 0, s, p, first);
+  hipLaunchKernelGGL(merge_kernel, dim3(n_merge, (p.Hq + 7) / 8), dim3(256), 0, s, p, first);
   return hipGetLastError();
 }
 
