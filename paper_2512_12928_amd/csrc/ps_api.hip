@@ -73,37 +73,142 @@ struct ps_ctx {
   hipStream_t copy = nullptr;
   hipStream_t side = nullptr;  // prefill kernel of a step, concurrent with its decode kernels
   hipEvent_t fork_ev = nullptr, join_ev = nullptr;
+  int n_cus = 256;
   bool profiling = false;
   hipEvent_t prof_ev[6];
   bool prof_valid = false;
   std::vector<ps::DecodeItem> ditems;
+  std::vector<int32_t> dslots;  // slot x owns ditems[dslots[x] .. dslots[x+1])
   std::vector<ps::MergeItem> mitems;
   std::vector<ps::PrefillTile> ptiles;
   std::vector<ps::AppendItem> aitems;
   std::vector<int32_t> seen;  // duplicate detection in swap lists
+  std::vector<int64_t> cover;  // scratch of the decode work-list check
 };
 
 namespace {
 
-int pick_decode_chunk(const ps_ctx* c, int64_t decode_kv_tokens) {
-  if (c->cfg.decode_chunk > 0) return c->cfg.decode_chunk;
-  // aim at ~1800 workgroups per launch (7 per CU over 256 CUs; measured sweep): long partitions
-  // keep the per-partition start-up and the partials traffic small, enough of them keep every CU
-  // fed.  Partitions are multiples of 128 tokens so the four waves of a workgroup get whole tiles.
-  int64_t ch = decode_kv_tokens * c->cfg.n_kv_heads / 1800;
-  ch = (ch + 127) / 128 * 128;
-  if (ch < 256) ch = 256;
-  if (ch > 4096) ch = 4096;
-  return (int)ch;
+constexpr int kMinSlotTiles = 16;  // a balanced decode slot holds at least this many 32-token tiles
+constexpr int kMinSegTiles = 4;    // a request is not cut closer than this to either of its ends
+
+// Decode work list.  Every decode request is cut into segments, and the segments are dealt to
+// slots; the decode kernel runs one workgroup per (slot, kv-head) which walks its slot's segments.
+//  - cfg.decode_chunk > 0: fixed partitions of that many tokens, one per slot, longest first.
+//  - otherwise: the requests' 32-token tiles, laid end to end in batch order, are cut into S slots
+//    of equal length, S chosen so that all workgroups of the launch are resident at once
+//    (cfg.decode_workgroups, default one per CU: measured best) and a slot is not shorter than kMinSlotTiles.
+//    A cut that would leave fewer than kMinSegTiles tiles of a request on one side moves to that
+//    end of the request.  At most S - 1 requests are cut, so there are at most n_req + S segments.
+// A request with several segments gets one partials slot per segment and a merge item.
+void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& reqs, int& n_parts) {
+  c->dslots.clear();
+  c->dslots.push_back(0);
+  auto close_slot = [&]() {
+    if ((int)c->ditems.size() > c->dslots.back()) c->dslots.push_back((int32_t)c->ditems.size());
+  };
+  auto item = [&](int r, int t0, int t1, int part) {
+    const int L = b->kv_len[r];
+    return ps::DecodeItem{b->bt_start[r], b->q_start[r], t0, t1, part, (L + ps::kBlockTokens - 1) / ps::kBlockTokens, {0, 0}};
+  };
+  if (c->cfg.decode_chunk > 0) {
+    const int CH = c->cfg.decode_chunk;
+    for (int r : reqs) {
+      const int L = b->kv_len[r], np = (L + CH - 1) / CH;
+      if (np == 1) {
+        c->ditems.push_back(item(r, 0, L, -1));
+      } else {
+        c->mitems.push_back(ps::MergeItem{b->q_start[r], n_parts, np, 0});
+        for (int k = 0; k < np; ++k) c->ditems.push_back(item(r, k * CH, std::min((k + 1) * CH, L), n_parts++));
+      }
+    }
+    // longest partitions first, so that the tail of the launch is made of short ones
+    std::stable_sort(c->ditems.begin(), c->ditems.end(),
+                     [](const ps::DecodeItem& a, const ps::DecodeItem& b2) { return a.t1 - a.t0 > b2.t1 - b2.t0; });
+    for (size_t i = 1; i <= c->ditems.size(); ++i) c->dslots.push_back((int32_t)i);
+    return;
+  }
+  int64_t T = 0;
+  for (int r : reqs) T += (b->kv_len[r] + ps::kTileTokens - 1) / ps::kTileTokens;
+  const int wgs = c->cfg.decode_workgroups > 0 ? c->cfg.decode_workgroups : c->n_cus;
+  const int64_t S = std::max<int64_t>(1, std::min<int64_t>(wgs / c->cfg.n_kv_heads, T / kMinSlotTiles));
+  auto boundary = [&](int64_t x) { return ((x + 1) * T + S - 1) / S; };  // nominal end of slot x, in tiles
+  int64_t off = 0, x = 0;
+  std::vector<std::pair<int, bool>> cuts;  // (tile index, slot ends here) inside one request
+  for (int r : reqs) {
+    const int L = b->kv_len[r];
+    const int n = (L + ps::kTileTokens - 1) / ps::kTileTokens;
+    while (x < S - 1 && boundary(x) <= off) {  // slot ends at or before the start of this request
+      close_slot();
+      ++x;
+    }
+    cuts.clear();
+    bool close_after = false;
+    int begin = 0;
+    while (x < S - 1 && boundary(x) < off + n) {
+      const int cpos = (int)(boundary(x) - off);  // in (0, n)
+      ++x;
+      if (cpos - begin < kMinSegTiles) {
+        if (begin == 0) close_slot();  // the slot ends in front of this request instead
+        continue;                      // (else: two cuts closer than a slot is long; drop the second)
+      }
+      if (n - cpos < kMinSegTiles) {   // the slot takes the rest of the request as well
+        close_after = true;
+        continue;
+      }
+      cuts.push_back({cpos, true});
+      begin = cpos;
+    }
+    if (cuts.empty()) {
+      c->ditems.push_back(item(r, 0, L, -1));
+    } else {
+      const int np = (int)cuts.size() + 1;
+      c->mitems.push_back(ps::MergeItem{b->q_start[r], n_parts, np, 0});
+      int t0 = 0;
+      for (auto& cu : cuts) {
+        c->ditems.push_back(item(r, t0, cu.first * ps::kTileTokens, n_parts++));
+        close_slot();
+        t0 = cu.first * ps::kTileTokens;
+      }
+      c->ditems.push_back(item(r, t0, L, n_parts++));
+    }
+    if (close_after) close_slot();
+    off += n;
+  }
+  close_slot();
+}
+
+// Host-side check of the decode work list before anything is launched from it: every slot a
+// non-empty range of items, every item inside its request, the segments of a request tiling
+// [0, kv_len) exactly.  A mistake here would otherwise become an out-of-bounds access on the GPU.
+bool decode_slots_ok(const ps_ctx* c, const ps_batch* b, const std::vector<int>& reqs, std::vector<int64_t>& cover) {
+  const size_t n = c->ditems.size();
+  if (c->dslots.empty() || c->dslots.front() != 0 || (size_t)c->dslots.back() != n) return false;
+  for (size_t i = 1; i < c->dslots.size(); ++i)
+    if (c->dslots[i] <= c->dslots[i - 1]) return false;
+  if (reqs.empty()) return n == 0 && c->dslots.size() == 1;
+  cover.assign((size_t)b->n_tokens, 0);
+  std::vector<int> req_of((size_t)b->n_tokens, -1);
+  for (int r : reqs) req_of[(size_t)b->q_start[r]] = r;
+  for (const ps::DecodeItem& it : c->ditems) {
+    if (it.tok < 0 || it.tok >= b->n_tokens || req_of[(size_t)it.tok] < 0) return false;
+    const int r = req_of[(size_t)it.tok], L = b->kv_len[r];
+    if (it.bt_off != b->bt_start[r] || it.nblk != (L + ps::kBlockTokens - 1) / ps::kBlockTokens) return false;
+    if (it.t0 < 0 || it.t0 >= it.t1 || it.t1 > L || it.t0 % ps::kTileTokens != 0) return false;
+    if (it.t1 != L && it.t1 % ps::kTileTokens != 0) return false;
+    cover[(size_t)it.tok] += it.t1 - it.t0;
+  }
+  for (int r : reqs)
+    if (cover[(size_t)b->q_start[r]] != b->kv_len[r]) return false;
+  return true;
 }
 
 // Bytes of the metadata block for given sizes (also the layout used by ps_step).
 struct MetaLayout {
-  size_t q_start, kv_len, bt_start, block_ids, aitems, ditems, mitems, ptiles, total;
+  size_t q_start, kv_len, bt_start, block_ids, aitems, ditems, dslots, mitems, ptiles, total;
 };
 
-MetaLayout meta_layout(int n_req, size_t n_aitems, int64_t n_table, size_t n_ditems, size_t n_mitems,
-                       size_t n_ptiles) {
+MetaLayout meta_layout(int n_req, size_t n_aitems, int64_t n_table, size_t n_ditems, size_t n_dslots,
+                       size_t n_mitems, size_t n_ptiles) {
   MetaLayout m;
   size_t o = 0;
   auto put = [&](size_t bytes) {
@@ -117,6 +222,7 @@ MetaLayout meta_layout(int n_req, size_t n_aitems, int64_t n_table, size_t n_dit
   m.block_ids = put((size_t)n_table * 4);
   m.aitems = put((size_t)n_aitems * sizeof(ps::AppendItem));
   m.ditems = put(n_ditems * sizeof(ps::DecodeItem));
+  m.dslots = put(n_dslots * 4);
   m.mitems = put(n_mitems * sizeof(ps::MergeItem));
   m.ptiles = put(n_ptiles * sizeof(ps::PrefillTile));
   m.total = o;
@@ -173,6 +279,8 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   if (cfg->own_streams != 0 && cfg->own_streams != 1) return fail(PS_EINVAL, "own_streams must be 0 or 1");
   if (cfg->prefill_split_tiles < -1 || cfg->prefill_split_tiles > 65536)
     return fail(PS_EINVAL, "prefill_split_tiles must be -1, 0 or a positive tile count");
+  if (cfg->decode_workgroups < 0 || cfg->decode_workgroups > 65536)
+    return fail(PS_EINVAL, "decode_workgroups must be in [0, 65536]");
   if (!(cfg->softmax_scale >= 0.f) || std::isinf(cfg->softmax_scale))
     return fail(PS_EINVAL, "softmax_scale must be finite and >= 0");
 
@@ -187,6 +295,8 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   for (auto& e : c->prof_ev) e = nullptr;
   for (auto& t : c->ticket_id) t = 0;
   hipError_t e = hipGetDevice(&c->device);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, c->device);
+  if (e == hipSuccess && c->n_cus < 1) c->n_cus = 1;
   for (int i = 0; i < kStepSlots && e == hipSuccess; ++i)
     e = hipEventCreateWithFlags(&c->step_slot[i].ev, hipEventDisableTiming);
   for (int i = 0; i < kSwapSlots && e == hipSuccess; ++i)
@@ -244,11 +354,12 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
                        size_t* out_bytes) {
   if (!c || !out_bytes) return fail(PS_EINVAL, "ps_workspace_bytes: NULL argument");
   if (max_req < 0 || max_tokens < 0 || max_table_entries < 0) return fail(PS_EINVAL, "negative size");
-  // worst case over chunk choices: every request is a decode split at the smallest chunk
-  const int min_chunk = c->cfg.decode_chunk > 0 ? c->cfg.decode_chunk : 256;
-  const size_t max_parts = (size_t)max_req + (size_t)(max_table_entries * ps::kBlockTokens / min_chunk);
-  const size_t max_tiles = (size_t)max_req + (size_t)max_tokens / 32;
-  (void)max_tiles;
+  // decode partials: one per segment.  Fixed partitions: every request a decode split at that size;
+  // balanced slots: at most one extra segment per slot, and a slot holds at least kMinSlotTiles
+  // tiles (a request of n table entries has at most (n + 1) / 2 tiles).
+  const size_t max_parts = (size_t)max_req + (c->cfg.decode_chunk > 0
+                                                 ? (size_t)(max_table_entries * ps::kBlockTokens / c->cfg.decode_chunk)
+                                                 : (size_t)((max_table_entries + max_req) / (2 * kMinSlotTiles)) + 1);
   // + up to two partial slots per batch token for prefill rows whose KV range is split
   *out_bytes = align_up((max_parts + 2 * (size_t)max_tokens) * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256) + 256;
   return PS_OK;
@@ -332,9 +443,9 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       return fail(PS_EINVAL, "block_ids[%lld] = %d outside [0, %d)", (long long)i, b->block_ids[i], M);
 
   // ---- work lists
-  const int CH = pick_decode_chunk(c, decode_kv);
   const int TT = ps::prefill_tile_tokens(c->G);
   c->ditems.clear();
+  c->dslots.assign(1, 0);
   c->mitems.clear();
   c->ptiles.clear();
   c->aitems.clear();
@@ -344,6 +455,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     ps::PrefillTile t;
   };
   std::vector<TileKey> tiles;
+  std::vector<int> decode_reqs;
   for (int r = 0; r < n_req; ++r) {
     const int qs = b->q_start[r], lq = b->q_start[r + 1] - qs, L = b->kv_len[r];
     if (k_new)
@@ -353,14 +465,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
         c->aitems.push_back(ps::AppendItem{b->block_ids[b->bt_start[r] + lb], qs + lo - (L - lq), lo - b0, hi - lo});
       }
     if (lq == 1) {
-      const int np = (L + CH - 1) / CH;
-      if (np == 1) {
-        c->ditems.push_back(ps::DecodeItem{r, qs, 0, L, -1, {0, 0, 0}});
-      } else {
-        c->mitems.push_back(ps::MergeItem{qs, n_parts, np, 0});
-        for (int k = 0; k < np; ++k)
-          c->ditems.push_back(ps::DecodeItem{r, qs, k * CH, std::min((k + 1) * CH, L), n_parts++, {0, 0, 0}});
-      }
+      decode_reqs.push_back(r);
     } else {
       const int p = L - lq;
       for (int q0 = 0; q0 < lq; q0 += TT) {
@@ -369,9 +474,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       }
     }
   }
-  // longest partitions first, so that the tail of the decode launch is made of short ones
-  std::stable_sort(c->ditems.begin(), c->ditems.end(),
-                   [](const ps::DecodeItem& a, const ps::DecodeItem& b2) { return a.t1 - a.t0 > b2.t1 - b2.t0; });
+  build_decode_slots(c, b, decode_reqs, n_parts);
+  if (!decode_slots_ok(c, b, decode_reqs, c->cover)) return fail(PS_ESTATE, "ps_step: inconsistent decode work list (library bug)");
 
   // Prefill: a query tile walks `reach` KV tiles.  When the longest walk is much longer than a CU's
   // fair share of all walks, the launch ends with a few workgroups running alone; then the long
@@ -425,7 +529,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
   for (auto& t : tiles) c->ptiles.push_back(t.t);
 
-  const MetaLayout ml = meta_layout(n_req, c->aitems.size(), n_table, c->ditems.size(), c->mitems.size(), c->ptiles.size());
+  const MetaLayout ml = meta_layout(n_req, c->aitems.size(), n_table, c->ditems.size(), c->dslots.size(),
+                                     c->mitems.size(), c->ptiles.size());
   const size_t part_bytes = align_up((size_t)n_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256);
   if (part_bytes > workspace_bytes)
     return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", part_bytes, workspace_bytes);
@@ -442,6 +547,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   std::memcpy(h + ml.block_ids, b->block_ids, (size_t)n_table * 4);
   if (!c->aitems.empty()) std::memcpy(h + ml.aitems, c->aitems.data(), c->aitems.size() * sizeof(ps::AppendItem));
   if (!c->ditems.empty()) std::memcpy(h + ml.ditems, c->ditems.data(), c->ditems.size() * sizeof(ps::DecodeItem));
+  if (!c->dslots.empty()) std::memcpy(h + ml.dslots, c->dslots.data(), c->dslots.size() * 4);
   if (!c->mitems.empty()) std::memcpy(h + ml.mitems, c->mitems.data(), c->mitems.size() * sizeof(ps::MergeItem));
   if (!c->ptiles.empty()) std::memcpy(h + ml.ptiles, c->ptiles.data(), c->ptiles.size() * sizeof(ps::PrefillTile));
 
@@ -488,6 +594,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   P.block_ids = (const int32_t*)(w + ml.block_ids);
   P.aitems = (const ps::AppendItem*)(w + ml.aitems);
   P.ditems = (const ps::DecodeItem*)(w + ml.ditems);
+  P.dslots = (const int32_t*)(w + ml.dslots);
   P.mitems = (const ps::MergeItem*)(w + ml.mitems);
   P.ptiles = (const ps::PrefillTile*)(w + ml.ptiles);
   P.partials = (float*)workspace;
@@ -514,7 +621,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     PS_HIP(ps::launch_merge(P, n_decode_merge, (int)c->mitems.size() - n_decode_merge, c->side));  // split prefill rows
     PS_HIP(hipEventRecord(c->join_ev, c->side));
   }
-  PS_HIP(ps::launch_decode(P, (int)c->ditems.size(), stream));
+  PS_HIP(ps::launch_decode(P, (int)c->dslots.size() - 1, stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[3], stream));
   PS_HIP(ps::launch_merge(P, 0, n_decode_merge, stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[4], stream));

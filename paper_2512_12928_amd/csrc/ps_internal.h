@@ -13,15 +13,17 @@ constexpr int kSliceElems = kBlockTokens * kHeadDim;  // one (block, K|V, kv-hea
 constexpr int kTileTokens = 32;                       // KV tokens per MFMA tile (two blocks)
 constexpr int kPartStride = 132;                      // fp32 per split-K partial: o[128], m, l, pad
 
-// One split-K partition of one decode token (all G query heads of one kv-head are handled by
-// the workgroup that blockIdx.y selects).
+// One split-K partition (segment) of one decode token: KV tokens [t0, t1) of its request, for all
+// G query heads of the kv-head that blockIdx.y selects.  A decode workgroup walks the segments
+// dslots[x] .. dslots[x+1] of its slot x one after the other.
 struct DecodeItem {
-  int32_t req;   // request index in the batch
-  int32_t tok;   // batch token index (row of q / out)
-  int32_t t0;    // first cached token of the partition (multiple of the chunk size)
-  int32_t t1;    // one past the last cached token (kv_len for the final partition)
-  int32_t part;  // slot in the partials buffer, or -1: single partition, write out directly
-  int32_t pad[3];
+  int32_t bt_off;  // first block-table entry of the request
+  int32_t tok;     // batch token index (row of q / out)
+  int32_t t0;      // first cached token of the segment (multiple of 32)
+  int32_t t1;      // one past the last cached token (kv_len for the final segment)
+  int32_t part;    // slot in the partials buffer, or -1: the only segment, write out directly
+  int32_t nblk;    // block-table entries of the request
+  int32_t pad[2];
 };
 
 struct MergeItem {
@@ -60,6 +62,7 @@ struct StepParams {
   const int32_t* block_ids;
   const AppendItem* aitems;
   const DecodeItem* ditems;
+  const int32_t* dslots;  // n_slots + 1 offsets into ditems
   const MergeItem* mitems;
   const PrefillTile* ptiles;
   float* partials;
@@ -78,7 +81,7 @@ struct StepParams {
 // dst (device) <- src (pinned host memory, read over the host link by the kernel), bytes a multiple of 16
 hipError_t launch_upload(const void* src_pinned, void* dst, size_t bytes, hipStream_t s);
 hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s);
-hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s);
+hipError_t launch_decode(const StepParams& p, int n_slots, hipStream_t s);
 // merges items [first, first + n_merge) of the merge list
 hipError_t launch_merge(const StepParams& p, int first, int n_merge, hipStream_t s);
 // tile_tokens: query tokens per workgroup tile as returned by prefill_tile_tokens(G).

@@ -110,14 +110,18 @@ __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
 }
 
 // ------------------------------------------------------------------------------------ decode
-// Split-K decode attention, HBM-bound.  grid (n_items, Hkv), 256 threads = 4 waves.
-// The workgroup owns KV tokens [t0, t1) of one request for one kv-head and all G query heads
-// of that head (padded to the 32 columns of a 32x32x16 MFMA: the matrix pipe has ten times the
-// throughput this kernel can feed it), so every K/V byte is read once.  Wave w streams the
-// 32-token tiles w, w+4, ...; per tile it issues 16 non-temporal 16-byte loads per lane (8 KiB K
+// Split-K decode attention, HBM-bound.  grid (n_slots, Hkv), 256 threads = 4 waves.
+// A workgroup walks the segments of its slot, one after the other; a segment is KV tokens
+// [t0, t1) of one request, handled for one kv-head and all G query heads of that head (padded to
+// the 32 columns of a 32x32x16 MFMA: the matrix pipe has ten times the throughput this kernel can
+// feed it), so every K/V byte is read once.  The host cuts the batch's decode tokens into slots
+// of equal length, as many as fit the chip at once, so that all workgroups end together: measured
+// on the same access pattern, a launch whose workgroups all run at once reads 6.7 TB/s, one
+// with a second, partly filled round of workgroups 5.7.  Wave w streams the 32-token tiles
+// w, w+4, ... of the segment; per tile it issues 16 non-temporal 16-byte loads per lane (8 KiB K
 // + 8 KiB V; the cache is read once, nothing is worth keeping in L2), 8 MFMAs for S^T and 8 for
 // O^T.  The four waves' running (m, l, O) states are combined through LDS; the result is either
-// the final output (single partition) or an unnormalised partial for the merge kernel.
+// the final output (the request's only segment) or an unnormalised partial for the merge kernel.
 //
 // Operand order (same as the prefill kernel): row i of the K operand is token pi(i) of the tile
 // (bits 2 and 3 of i swapped; rows 0..15 block A, 16..31 block B).  One K load instruction then
@@ -149,161 +153,167 @@ __device__ __forceinline__ float xor32_max(float x) {
 
 __global__ __launch_bounds__(256, 3) void decode_kernel(StepParams P) {
   extern __shared__ float smem[];  // [4][G][128] O, then [4][32] m, [4][32] l
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int j = lane & 31;   // row of the K operand / query-head column of Q, P, O
-  const int h2 = lane >> 5;  // k-group of the MFMA operands
-  const DecodeItem it = P.ditems[blockIdx.x];
-  const int g = blockIdx.y;
-  const int G = P.G, Hkv = P.Hkv;
-  const int* table = P.block_ids + P.bt_start[it.req];
-  const int nblk = (P.kv_len[it.req] + kBlockTokens - 1) >> 4;
-
   // Q^T operand: lane (head j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.  It is the same
   // for the four waves and is kept in LDS in operand order (one conflict-free 16-byte read per lane
   // and MFMA) rather than in 32 registers per lane: that is what lets three waves share a SIMD.
   __shared__ uint4 q_lds[8][64];
-  if (wave == 0) {
-    const uint16_t* qrow = P.q + ((size_t)it.tok * P.Hq + g * G + (j < G ? j : 0)) * kHeadDim;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      uint4 v = *(const uint4*)(qrow + (c * 2 + h2) * 8);
-      if (j >= G) v = make_uint4(0, 0, 0, 0);
-      q_lds[c][lane] = v;
-    }
-  }
-  __syncthreads();
-
-  float m = PS_NEG_INF, l = 0.f;
-  f32x16 acc[4];
-#pragma unroll
-  for (int n = 0; n < 4; ++n)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int j = lane & 31;   // row of the K operand / query-head column of Q, P, O
+  const int h2 = lane >> 5;  // k-group of the MFMA operands
+  const int g = blockIdx.y;
+  const int G = P.G, Hkv = P.Hkv;
+  float* sm_o = smem;                     // [4][G][128]
+  float* sm_m = smem + 4 * G * kHeadDim;  // [4][32]
+  float* sm_l = sm_m + 128;
 
   // per-lane element offsets inside a (block, head) slice
   const int k_off = h2 * (kBlockTokens * 8) + (8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3)) * 8;  // + c*2 groups
   const bool k_in_b = j >= 16;
   const int v_off = j * kBlockTokens + 8 * h2;  // + n*32 dims
 
-  const int ntiles = (it.t1 - it.t0 + kTileTokens - 1) / kTileTokens;
-  // block ids are fetched one tile ahead, so the table lookup is off the address path of the loads
-  int nextA = 0, nextB = 0;
-  if (wave < ntiles) {
-    const int bA = (it.t0 + wave * kTileTokens) >> 4;
-    nextA = table[bA];
-    nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;  // absent second block: masked below
-  }
-  for (int tile = wave; tile < ntiles; tile += 4) {
-    const int ts = it.t0 + tile * kTileTokens;
-    const int idA = nextA, idB = nextB;
-    if (tile + 4 < ntiles) {
-      const int bA = (ts + 4 * kTileTokens) >> 4;
+  // The workgroup walks the segments of its slot.  Barriers per segment: one after the Q operand is
+  // in LDS (every wave has then also left the previous segment's combine), one before the combine.
+  const int seg_end = P.dslots[blockIdx.x + 1];
+  for (int seg = P.dslots[blockIdx.x]; seg < seg_end; ++seg) {
+    const DecodeItem it = P.ditems[seg];
+    const int* table = P.block_ids + it.bt_off;
+    const int nblk = it.nblk;
+    const int ntiles = (it.t1 - it.t0 + kTileTokens - 1) / kTileTokens;
+
+    // block ids are fetched one tile ahead, so the table lookup is off the address path of the loads
+    int nextA = 0, nextB = 0;
+    if (wave < ntiles) {
+      const int bA = (it.t0 + wave * kTileTokens) >> 4;
       nextA = table[bA];
-      nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;
+      nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;  // absent second block: masked below
     }
-    const uint16_t* kp = k_slice(P.cache, k_in_b ? idB : idA, Hkv, g) + k_off;
-    const uint16_t* vA = v_slice(P.cache, idA, Hkv, g) + v_off;
-    const uint16_t* vB = v_slice(P.cache, idB, Hkv, g) + v_off;
+    if (wave == 0) {
+      const uint16_t* qrow = P.q + ((size_t)it.tok * P.Hq + g * G + (j < G ? j : 0)) * kHeadDim;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        uint4 v = *(const uint4*)(qrow + (c * 2 + h2) * 8);
+        if (j >= G) v = make_uint4(0, 0, 0, 0);
+        q_lds[c][lane] = v;
+      }
+    }
+    __syncthreads();
 
-    bf16x8 kf[8], vf[2][4];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) kf[c] = load_stream16(kp + c * 2 * (kBlockTokens * 8));
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      vf[0][n] = load_stream16(vA + n * 32 * kBlockTokens);
-      vf[1][n] = load_stream16(vB + n * 32 * kBlockTokens);
-    }
-
-    f32x16 s;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) s[e] = 0.f;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c], as_bf16x8(q_lds[c][lane]), s, 0, 0, 0);
-    // s[e]: token ts + 16*(e/8) + 8*h2 + e%8, head j
-    float tmax = PS_NEG_INF;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int tok = ts + 16 * (e >> 3) + 8 * h2 + (e & 7);
-      s[e] = tok < it.t1 ? s[e] * P.scale_log2 : PS_NEG_INF;
-      tmax = fmaxf(tmax, s[e]);
-    }
-    if (ts + kTileTokens > it.t1) {  // ragged tail: slots past kv_len may hold anything
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int n = 0; n < 4; ++n) vf[u][n] = zero_from8(vf[u][n], ts + 16 * u + 8 * h2, it.t1);
-    }
-    tmax = xor32_max(tmax);
-    const float m_new = fmaxf(m, tmax);  // finite: every tile holds at least one valid token
-    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-    float psum = 0.f;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      s[e] = __builtin_amdgcn_exp2f(s[e] - m_new);
-      psum += s[e];
-    }
-    l = l * alpha + psum;
-    m = m_new;
-#pragma unroll
-    for (int n = 0; n < 4; ++n) acc[n] *= alpha;
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      uint4 pv = {pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
-                  pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7])};
-      const bf16x8 pop = as_bf16x8(pv);
-#pragma unroll
-      for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u][n], pop, acc[n], 0, 0, 0);
-    }
-  }
-  l += __shfl_xor(l, 32);
-
-  // combine the four waves
-  float* sm_o = smem;                     // [4][G][128]
-  float* sm_m = smem + 4 * G * kHeadDim;  // [4][32]
-  float* sm_l = sm_m + 128;
-  if (j < G) {
+    float m = PS_NEG_INF, l = 0.f;
+    f32x16 acc[4];
 #pragma unroll
     for (int n = 0; n < 4; ++n)
 #pragma unroll
-      for (int a = 0; a < 4; ++a)  // acc[n][4a+b] is dim 32n + 8a + 4*h2 + b
-        *(f32x4*)(sm_o + ((wave * G + j) * kHeadDim) + n * 32 + a * 8 + h2 * 4) =
-            (f32x4){acc[n][4 * a], acc[n][4 * a + 1], acc[n][4 * a + 2], acc[n][4 * a + 3]};
-    if (h2 == 0) {
-      sm_m[wave * 32 + j] = m;
-      sm_l[wave * 32 + j] = l;
-    }
-  }
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 256) {
-    const int h = idx >> 7, x = idx & 127;
-    float mw[4], mstar = PS_NEG_INF;
+      for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+
+    for (int tile = wave; tile < ntiles; tile += 4) {
+      const int ts = it.t0 + tile * kTileTokens;
+      const int idA = nextA, idB = nextB;
+      if (tile + 4 < ntiles) {
+        const int bA = (ts + 4 * kTileTokens) >> 4;
+        nextA = table[bA];
+        nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;
+      }
+      const uint16_t* kp = k_slice(P.cache, k_in_b ? idB : idA, Hkv, g) + k_off;
+      const uint16_t* vA = v_slice(P.cache, idA, Hkv, g) + v_off;
+      const uint16_t* vB = v_slice(P.cache, idB, Hkv, g) + v_off;
+
+      bf16x8 kf[8], vf[2][4];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      mw[w] = sm_m[w * 32 + h];
-      mstar = fmaxf(mstar, mw[w]);
-    }
-    float L = 0.f, o = 0.f;
+      for (int c = 0; c < 8; ++c) kf[c] = load_stream16(kp + c * 2 * (kBlockTokens * 8));
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float f = __builtin_amdgcn_exp2f(mw[w] - mstar);  // idle wave: m = -inf -> 0
-      L += sm_l[w * 32 + h] * f;
-      o += sm_o[(w * G + h) * kHeadDim + x] * f;
+      for (int n = 0; n < 4; ++n) {
+        vf[0][n] = load_stream16(vA + n * 32 * kBlockTokens);
+        vf[1][n] = load_stream16(vB + n * 32 * kBlockTokens);
+      }
+
+      f32x16 s;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c], as_bf16x8(q_lds[c][lane]), s, 0, 0, 0);
+      // s[e]: token ts + 16*(e/8) + 8*h2 + e%8, head j
+      float tmax = PS_NEG_INF;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int tok = ts + 16 * (e >> 3) + 8 * h2 + (e & 7);
+        s[e] = tok < it.t1 ? s[e] * P.scale_log2 : PS_NEG_INF;
+        tmax = fmaxf(tmax, s[e]);
+      }
+      if (ts + kTileTokens > it.t1) {  // ragged tail: slots past kv_len may hold anything
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int n = 0; n < 4; ++n) vf[u][n] = zero_from8(vf[u][n], ts + 16 * u + 8 * h2, it.t1);
+      }
+      tmax = xor32_max(tmax);
+      const float m_new = fmaxf(m, tmax);  // finite: every tile holds at least one valid token
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        s[e] = __builtin_amdgcn_exp2f(s[e] - m_new);
+        psum += s[e];
+      }
+      l = l * alpha + psum;
+      m = m_new;
+#pragma unroll
+      for (int n = 0; n < 4; ++n) acc[n] *= alpha;
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        uint4 pv = {pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
+                    pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7])};
+        const bf16x8 pop = as_bf16x8(pv);
+#pragma unroll
+        for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u][n], pop, acc[n], 0, 0, 0);
+      }
     }
-    const int head = g * G + h;
-    if (it.part < 0) {
-      const size_t oi = ((size_t)it.tok * P.Hq + head) * kHeadDim + x;
-      const float r = o / L;
-      if (P.out_f32)
-        ((float*)P.out)[oi] = r;
-      else
-        ((uint16_t*)P.out)[oi] = (uint16_t)(pack_bf16x2(r, 0.f) & 0xFFFFu);
-    } else {
-      float* dst = P.partials + ((size_t)it.part * P.Hq + head) * kPartStride;
-      dst[x] = o;
-      if (x == 0) {
-        dst[128] = mstar;
-        dst[129] = L;
+    l += __shfl_xor(l, 32);
+
+    // combine the four waves
+    if (j < G) {
+#pragma unroll
+      for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int a = 0; a < 4; ++a)  // acc[n][4a+b] is dim 32n + 8a + 4*h2 + b
+          *(f32x4*)(sm_o + ((wave * G + j) * kHeadDim) + n * 32 + a * 8 + h2 * 4) =
+              (f32x4){acc[n][4 * a], acc[n][4 * a + 1], acc[n][4 * a + 2], acc[n][4 * a + 3]};
+      if (h2 == 0) {
+        sm_m[wave * 32 + j] = m;
+        sm_l[wave * 32 + j] = l;
+      }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 256) {
+      const int h = idx >> 7, x = idx & 127;
+      float mw[4], mstar = PS_NEG_INF;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        mw[w] = sm_m[w * 32 + h];
+        mstar = fmaxf(mstar, mw[w]);
+      }
+      float L = 0.f, o = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float f = __builtin_amdgcn_exp2f(mw[w] - mstar);  // idle wave: m = -inf -> 0
+        L += sm_l[w * 32 + h] * f;
+        o += sm_o[(w * G + h) * kHeadDim + x] * f;
+      }
+      const int head = g * G + h;
+      if (it.part < 0) {
+        const size_t oi = ((size_t)it.tok * P.Hq + head) * kHeadDim + x;
+        const float r = o / L;
+        if (P.out_f32)
+          ((float*)P.out)[oi] = r;
+        else
+          ((uint16_t*)P.out)[oi] = (uint16_t)(pack_bf16x2(r, 0.f) & 0xFFFFu);
+      } else {
+        float* dst = P.partials + ((size_t)it.part * P.Hq + head) * kPartStride;
+        dst[x] = o;
+        if (x == 0) {
+          dst[128] = mstar;
+          dst[129] = L;
+        }
       }
     }
   }
@@ -733,10 +743,10 @@ hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_decode(const StepParams& p, int n_items, hipStream_t s) {
-  if (n_items <= 0) return hipSuccess;
+hipError_t launch_decode(const StepParams& p, int n_slots, hipStream_t s) {
+  if (n_slots <= 0) return hipSuccess;
   const size_t smem = (size_t)(4 * p.G * kHeadDim + 256) * sizeof(float);
-  hipLaunchKernelGGL(decode_kernel, dim3(n_items, p.Hkv), dim3(256), smem, s, p);
+  hipLaunchKernelGGL(decode_kernel, dim3(n_slots, p.Hkv), dim3(256), smem, s, p);
   return hipGetLastError();
 }
 
