@@ -65,9 +65,9 @@ typedef struct {
   float softmax_scale;     /* 0 => 1/sqrt(head_dim)                                       */
   int32_t out_dtype;       /* PS_BF16 (default) or PS_F32                                 */
   int32_t decode_chunk;    /* 0 (default): the decode tokens of a batch are cut into equally
-                              long slots, one workgroup per slot and kv-head, all resident at
-                              once (see decode_workgroups); N > 0, a multiple of 32 in
-                              [32, 65536]: fixed split-K partitions of N KV tokens instead     */
+                              long slots, one wave per slot and kv-head, all resident at once
+                              (see decode_waves); N > 0, a multiple of 32 in [32, 65536]:
+                              fixed split-K partitions of N KV tokens, one wave each, instead  */
   int32_t swap_workgroups; /* workgroups used by a swap kernel; 0 => library picks        */
   int32_t own_streams;     /* 0 (default): every copy and kernel of a step is enqueued on the
                               caller's stream. 1: the context creates two streams of its own
@@ -81,8 +81,9 @@ typedef struct {
                               rows over several workgroups (partials merged like decode's) when
                               the launch would otherwise be unbalanced; N > 0: always split into
                               partitions of N 64-token KV tiles; -1: never split               */
-  int32_t decode_workgroups; /* workgroups of a decode launch when decode_chunk is 0; 0 (default)
-                              => one per compute unit of the device; else in [1, 65536]        */
+  int32_t decode_waves;    /* waves of a decode launch when decode_chunk is 0 (each walks one
+                              slot of one kv-head); 0 (default) => one per SIMD, i.e. four per
+                              compute unit of the device; else in [1, 65536]                   */
 } ps_layer_cfg;
 
 /* One mixed batch (the output of Alg. 1 as the attention layer sees it). HOST arrays. */

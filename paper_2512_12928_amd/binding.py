@@ -33,7 +33,7 @@ class ps_layer_cfg(C.Structure):
                 ("block_tokens", C.c_int32), ("n_device_blocks", C.c_int32), ("n_host_blocks", C.c_int32),
                 ("softmax_scale", C.c_float), ("out_dtype", C.c_int32), ("decode_chunk", C.c_int32),
                 ("swap_workgroups", C.c_int32), ("own_streams", C.c_int32), ("prefill_split_tiles", C.c_int32),
-                ("decode_workgroups", C.c_int32)]
+                ("decode_waves", C.c_int32)]
 
 
 class ps_batch(C.Structure):
@@ -146,10 +146,10 @@ def _i32p(a: np.ndarray):
 def ps_create(n_q_heads: int, n_kv_heads: int, n_device_blocks: int, n_host_blocks: int = 0,
               softmax_scale: float = 0.0, out_dtype: int = PS_BF16, decode_chunk: int = 0,
               swap_workgroups: int = 0, head_dim: int = 128, block_tokens: int = 16,
-              own_streams: int = 0, prefill_split_tiles: int = 0, decode_workgroups: int = 0) -> int:
+              own_streams: int = 0, prefill_split_tiles: int = 0, decode_waves: int = 0) -> int:
     cfg = ps_layer_cfg(n_q_heads, n_kv_heads, head_dim, block_tokens, n_device_blocks, n_host_blocks,
                        softmax_scale, out_dtype, decode_chunk, swap_workgroups, own_streams, prefill_split_tiles,
-                       decode_workgroups)
+                       decode_waves)
     h = C.c_void_p()
     _check(lib().ps_create(C.byref(cfg), C.byref(h)))
     return h.value

@@ -89,16 +89,14 @@ struct ps_ctx {
 namespace {
 
 constexpr int kMinSlotTiles = 16;  // a balanced decode slot holds at least this many 32-token tiles
-constexpr int kMinSegTiles = 4;    // a request is not cut closer than this to either of its ends
 
 // Decode work list.  Every decode request is cut into segments, and the segments are dealt to
-// slots; the decode kernel runs one workgroup per (slot, kv-head) which walks its slot's segments.
+// slots; the decode kernel runs one wave per (slot, kv-head) which walks its slot's segments.
 //  - cfg.decode_chunk > 0: fixed partitions of that many tokens, one per slot, longest first.
 //  - otherwise: the requests' 32-token tiles, laid end to end in batch order, are cut into S slots
-//    of equal length, S chosen so that all workgroups of the launch are resident at once
-//    (cfg.decode_workgroups, default one per CU: measured best) and a slot is not shorter than kMinSlotTiles.
-//    A cut that would leave fewer than kMinSegTiles tiles of a request on one side moves to that
-//    end of the request.  At most S - 1 requests are cut, so there are at most n_req + S segments.
+//    of equal length (to within a tile), S chosen so that all waves of the launch are resident at
+//    once (cfg.decode_waves, default one per SIMD: measured best) and a slot is not shorter than
+//    kMinSlotTiles.  At most S - 1 requests are cut, so there are at most n_req + S segments.
 // A request with several segments gets one partials slot per segment and a merge item.
 void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& reqs, int& n_parts) {
   c->dslots.clear();
@@ -129,11 +127,11 @@ void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& re
   }
   int64_t T = 0;
   for (int r : reqs) T += (b->kv_len[r] + ps::kTileTokens - 1) / ps::kTileTokens;
-  const int wgs = c->cfg.decode_workgroups > 0 ? c->cfg.decode_workgroups : c->n_cus;
-  const int64_t S = std::max<int64_t>(1, std::min<int64_t>(wgs / c->cfg.n_kv_heads, T / kMinSlotTiles));
+  const int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : 4 * c->n_cus;
+  const int64_t S = std::max<int64_t>(1, std::min<int64_t>(waves / c->cfg.n_kv_heads, T / kMinSlotTiles));
   auto boundary = [&](int64_t x) { return ((x + 1) * T + S - 1) / S; };  // nominal end of slot x, in tiles
   int64_t off = 0, x = 0;
-  std::vector<std::pair<int, bool>> cuts;  // (tile index, slot ends here) inside one request
+  std::vector<int> cuts;  // tile indices inside one request at which a slot ends
   for (int r : reqs) {
     const int L = b->kv_len[r];
     const int n = (L + ps::kTileTokens - 1) / ps::kTileTokens;
@@ -142,36 +140,19 @@ void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& re
       ++x;
     }
     cuts.clear();
-    bool close_after = false;
-    int begin = 0;
-    while (x < S - 1 && boundary(x) < off + n) {
-      const int cpos = (int)(boundary(x) - off);  // in (0, n)
-      ++x;
-      if (cpos - begin < kMinSegTiles) {
-        if (begin == 0) close_slot();  // the slot ends in front of this request instead
-        continue;                      // (else: two cuts closer than a slot is long; drop the second)
-      }
-      if (n - cpos < kMinSegTiles) {   // the slot takes the rest of the request as well
-        close_after = true;
-        continue;
-      }
-      cuts.push_back({cpos, true});
-      begin = cpos;
-    }
+    while (x < S - 1 && boundary(x) < off + n) cuts.push_back((int)(boundary(x++) - off));  // in (0, n), increasing
     if (cuts.empty()) {
       c->ditems.push_back(item(r, 0, L, -1));
     } else {
-      const int np = (int)cuts.size() + 1;
-      c->mitems.push_back(ps::MergeItem{b->q_start[r], n_parts, np, 0});
+      c->mitems.push_back(ps::MergeItem{b->q_start[r], n_parts, (int)cuts.size() + 1, 0});
       int t0 = 0;
-      for (auto& cu : cuts) {
-        c->ditems.push_back(item(r, t0, cu.first * ps::kTileTokens, n_parts++));
+      for (int cu : cuts) {
+        c->ditems.push_back(item(r, t0, cu * ps::kTileTokens, n_parts++));
         close_slot();
-        t0 = cu.first * ps::kTileTokens;
+        t0 = cu * ps::kTileTokens;
       }
       c->ditems.push_back(item(r, t0, L, n_parts++));
     }
-    if (close_after) close_slot();
     off += n;
   }
   close_slot();
@@ -279,8 +260,8 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   if (cfg->own_streams != 0 && cfg->own_streams != 1) return fail(PS_EINVAL, "own_streams must be 0 or 1");
   if (cfg->prefill_split_tiles < -1 || cfg->prefill_split_tiles > 65536)
     return fail(PS_EINVAL, "prefill_split_tiles must be -1, 0 or a positive tile count");
-  if (cfg->decode_workgroups < 0 || cfg->decode_workgroups > 65536)
-    return fail(PS_EINVAL, "decode_workgroups must be in [0, 65536]");
+  if (cfg->decode_waves < 0 || cfg->decode_waves > 65536)
+    return fail(PS_EINVAL, "decode_waves must be in [0, 65536]");
   if (!(cfg->softmax_scale >= 0.f) || std::isinf(cfg->softmax_scale))
     return fail(PS_EINVAL, "softmax_scale must be finite and >= 0");
 

@@ -10,6 +10,8 @@
 // and the per-row rescale factors of the online softmax are per-lane scalars.  Inside a block K
 // is stored [dim/8][token][8 dims] and V [dim][token], so every A-operand lane is one 16-byte
 // load and the lanes of one load instruction cover runs of 256 bytes or more.
+#include <type_traits>
+
 #include "ps_internal.h"
 
 namespace ps {
@@ -110,18 +112,21 @@ __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
 }
 
 // ------------------------------------------------------------------------------------ decode
-// Split-K decode attention, HBM-bound.  grid (n_slots, Hkv), 256 threads = 4 waves.
-// A workgroup walks the segments of its slot, one after the other; a segment is KV tokens
-// [t0, t1) of one request, handled for one kv-head and all G query heads of that head (padded to
-// the 32 columns of a 32x32x16 MFMA: the matrix pipe has ten times the throughput this kernel can
-// feed it), so every K/V byte is read once.  The host cuts the batch's decode tokens into slots
-// of equal length, as many as fit the chip at once, so that all workgroups end together: measured
-// on the same access pattern, a launch whose workgroups all run at once reads 6.7 TB/s, one
-// with a second, partly filled round of workgroups 5.7.  Wave w streams the 32-token tiles
-// w, w+4, ... of the segment; per tile it issues 16 non-temporal 16-byte loads per lane (8 KiB K
-// + 8 KiB V; the cache is read once, nothing is worth keeping in L2), 8 MFMAs for S^T and 8 for
-// O^T.  The four waves' running (m, l, O) states are combined through LDS; the result is either
-// the final output (the request's only segment) or an unnormalised partial for the merge kernel.
+// Split-K decode attention, HBM-bound.  grid (ceil(n_slots / 4), Hkv), 256 threads: four waves
+// that work independently (one slot each; a workgroup only pins them to the four SIMDs of one
+// CU), no barriers, no cross-wave combine.  A wave walks the segments of its slot one after the
+// other; a segment is KV tokens [t0, t1) of one request, handled for one kv-head and all G query
+// heads of that head (padded to the 32 columns of a 32x32x16 MFMA: the matrix pipe has ten times
+// the throughput this kernel can feed it), so every K/V byte is read once.  The host cuts the
+// batch's decode tokens into slots of equal length, as many as the chip runs at once, so that
+// all waves end together: measured on the same access pattern, a launch whose workgroups all
+// run at once reads 6.7 TB/s, one with a second, partly filled round 5.7.  Per 32-token tile
+// the wave issues 16 non-temporal 16-byte loads per lane (8 KiB K + 8 KiB V; the cache is read
+// once, nothing is worth keeping in L2), 8 MFMAs for S^T and 8 for O^T.  At the end of a
+// segment the lanes write their accumulators straight out: the final output (the request's
+// only segment) or an unnormalised partial for the merge kernel.  The next segment's
+// description, first block ids and Q are requested before that, so a segment boundary costs
+// about one tile step.
 //
 // Operand order (same as the prefill kernel): row i of the K operand is token pi(i) of the tile
 // (bits 2 and 3 of i swapped; rows 0..15 block A, 16..31 block B).  One K load instruction then
@@ -151,53 +156,65 @@ __device__ __forceinline__ float xor32_max(float x) {
   return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
 }
 
-__global__ __launch_bounds__(256, 3) void decode_kernel(StepParams P) {
-  extern __shared__ float smem[];  // [4][G][128] O, then [4][32] m, [4][32] l
-  // Q^T operand: lane (head j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.  It is the same
-  // for the four waves and is kept in LDS in operand order (one conflict-free 16-byte read per lane
-  // and MFMA) rather than in 32 registers per lane: that is what lets three waves share a SIMD.
-  __shared__ uint4 q_lds[8][64];
+// The work lists and the block tables come as separate restrict-qualified parameters: only then
+// does the compiler know that the kernel's own stores cannot change them, and fetches them through
+// the scalar cache instead of with vector loads it waits for on the spot.
+__global__ __launch_bounds__(256, 2) void decode_kernel(StepParams P, const DecodeItem* __restrict__ ditems,
+                                                     const int32_t* __restrict__ dslots,
+                                                     const int32_t* __restrict__ block_ids, int n_slots) {
+  // Q^T operand: lane (head j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.  Kept in LDS
+  // rather than in 32 registers (every lane reads back exactly what it wrote: no barrier); two
+  // copies, so that the next segment's Q can be stored while this one is still in use.
+  __shared__ uint4 q_all[4][2][8][64];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int slot = blockIdx.x * 4 + wave;  // the four waves of a workgroup work independently
+  if (slot >= n_slots) return;
+  uint4 (*q_lds)[8][64] = q_all[wave];
   const int j = lane & 31;   // row of the K operand / query-head column of Q, P, O
   const int h2 = lane >> 5;  // k-group of the MFMA operands
   const int g = blockIdx.y;
   const int G = P.G, Hkv = P.Hkv;
-  float* sm_o = smem;                     // [4][G][128]
-  float* sm_m = smem + 4 * G * kHeadDim;  // [4][32]
-  float* sm_l = sm_m + 128;
 
   // per-lane element offsets inside a (block, head) slice
   const int k_off = h2 * (kBlockTokens * 8) + (8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3)) * 8;  // + c*2 groups
   const bool k_in_b = j >= 16;
   const int v_off = j * kBlockTokens + 8 * h2;  // + n*32 dims
+  const int qhead = g * G + (j < G ? j : 0);
+  const uint32_t qmask = j < G ? 0xFFFFFFFFu : 0u;  // columns G..31 of the MFMA tile are zero
 
-  // The workgroup walks the segments of its slot.  Barriers per segment: one after the Q operand is
-  // in LDS (every wave has then also left the previous segment's combine), one before the combine.
-  const int seg_end = P.dslots[blockIdx.x + 1];
-  for (int seg = P.dslots[blockIdx.x]; seg < seg_end; ++seg) {
-    const DecodeItem it = P.ditems[seg];
-    const int* table = P.block_ids + it.bt_off;
-    const int nblk = it.nblk;
-    const int ntiles = (it.t1 - it.t0 + kTileTokens - 1) / kTileTokens;
-
-    // block ids are fetched one tile ahead, so the table lookup is off the address path of the loads
-    int nextA = 0, nextB = 0;
-    if (wave < ntiles) {
-      const int bA = (it.t0 + wave * kTileTokens) >> 4;
-      nextA = table[bA];
-      nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;  // absent second block: masked below
-    }
-    if (wave == 0) {
-      const uint16_t* qrow = P.q + ((size_t)it.tok * P.Hq + g * G + (j < G ? j : 0)) * kHeadDim;
+  // No branches around loads anywhere below: at a branch the compiler waits for every load in flight.
+  auto fetch_q = [&](int tok, u32x4 (&v)[8]) {
+    const uint16_t* qrow = P.q + ((size_t)tok * P.Hq + qhead) * kHeadDim;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        uint4 v = *(const uint4*)(qrow + (c * 2 + h2) * 8);
-        if (j >= G) v = make_uint4(0, 0, 0, 0);
-        q_lds[c][lane] = v;
-      }
-    }
-    __syncthreads();
+    for (int c = 0; c < 8; ++c) v[c] = *(const u32x4*)(qrow + (c * 2 + h2) * 8);
+  };
+  auto store_q = [&](const u32x4 (&v)[8], int buf) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+      q_lds[buf][c][lane] = make_uint4(v[c][0] & qmask, v[c][1] & qmask, v[c][2] & qmask, v[c][3] & qmask);
+  };
+  // block ids of the 32-token tile that starts at token ts (an absent second block repeats the
+  // first and is masked by the token test)
+  auto tile_ids = [&](const DecodeItem& d, int ts, int& a, int& b2) {
+    const int32_t* table = block_ids + d.bt_off;
+    const int bA = ts >> 4;
+    a = table[bA];
+    b2 = table[bA + 1 < d.nblk ? bA + 1 : bA];
+  };
+
+  const int seg_end = dslots[slot + 1];
+  int seg = dslots[slot];
+  DecodeItem it = ditems[seg];
+  int nextA, nextB;
+  tile_ids(it, it.t0, nextA, nextB);
+  {
+    u32x4 q0[8];
+    fetch_q(it.tok, q0);
+    store_q(q0, 0);
+  }
+  for (int buf = 0; seg < seg_end; ++seg, buf ^= 1) {
+    const DecodeItem itn = ditems[seg + 1 < seg_end ? seg + 1 : seg];  // the last one repeats itself
 
     float m = PS_NEG_INF, l = 0.f;
     f32x16 acc[4];
@@ -206,14 +223,19 @@ __global__ __launch_bounds__(256, 3) void decode_kernel(StepParams P) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
 
-    for (int tile = wave; tile < ntiles; tile += 4) {
-      const int ts = it.t0 + tile * kTileTokens;
+    // One 32-token tile.  In the last tile of the segment (LAST) the next segment's Q is requested
+    // ahead of the tile's own loads and stored to LDS behind its arithmetic, and the ids fetched one
+    // tile ahead are those of the next segment's first tile: a segment boundary costs no extra
+    // memory round trip.
+    auto tile = [&](int ts, auto last_tag) {
+      constexpr bool LAST = decltype(last_tag)::value;
+      u32x4 qn[8];
+      if (LAST) fetch_q(itn.tok, qn);
       const int idA = nextA, idB = nextB;
-      if (tile + 4 < ntiles) {
-        const int bA = (ts + 4 * kTileTokens) >> 4;
-        nextA = table[bA];
-        nextB = (bA + 1 < nblk) ? table[bA + 1] : nextA;
-      }
+      if (LAST)
+        tile_ids(itn, itn.t0, nextA, nextB);
+      else
+        tile_ids(it, ts + kTileTokens, nextA, nextB);
       const uint16_t* kp = k_slice(P.cache, k_in_b ? idB : idA, Hkv, g) + k_off;
       const uint16_t* vA = v_slice(P.cache, idA, Hkv, g) + v_off;
       const uint16_t* vB = v_slice(P.cache, idB, Hkv, g) + v_off;
@@ -226,21 +248,24 @@ __global__ __launch_bounds__(256, 3) void decode_kernel(StepParams P) {
         vf[0][n] = load_stream16(vA + n * 32 * kBlockTokens);
         vf[1][n] = load_stream16(vB + n * 32 * kBlockTokens);
       }
+      // all 16 loads are in flight before anything waits for the first (left alone, the scheduler
+      // holds the V loads back until the K registers are free again: two round trips per tile)
+      __builtin_amdgcn_sched_barrier(0);
 
       f32x16 s;
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c], as_bf16x8(q_lds[c][lane]), s, 0, 0, 0);
+      for (int c = 0; c < 8; ++c) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c], as_bf16x8(q_lds[buf][c][lane]), s, 0, 0, 0);
       // s[e]: token ts + 16*(e/8) + 8*h2 + e%8, head j
       float tmax = PS_NEG_INF;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int tok = ts + 16 * (e >> 3) + 8 * h2 + (e & 7);
-        s[e] = tok < it.t1 ? s[e] * P.scale_log2 : PS_NEG_INF;
+        s[e] = (!LAST || tok < it.t1) ? s[e] * P.scale_log2 : PS_NEG_INF;  // only the last tile is ragged
         tmax = fmaxf(tmax, s[e]);
       }
-      if (ts + kTileTokens > it.t1) {  // ragged tail: slots past kv_len may hold anything
+      if (LAST) {  // slots past the segment's end may hold anything
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -267,55 +292,48 @@ __global__ __launch_bounds__(256, 3) void decode_kernel(StepParams P) {
 #pragma unroll
         for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u][n], pop, acc[n], 0, 0, 0);
       }
-    }
+      if (LAST) store_q(qn, buf ^ 1);
+    };
+    int ts = it.t0;
+    for (; ts + kTileTokens < it.t1; ts += kTileTokens) tile(ts, std::false_type{});
+    tile(ts, std::true_type{});
     l += __shfl_xor(l, 32);
 
-    // combine the four waves
+    // acc[n][4a+b] is dim 32n + 8a + 4*h2 + b of head j
     if (j < G) {
-#pragma unroll
-      for (int n = 0; n < 4; ++n)
-#pragma unroll
-        for (int a = 0; a < 4; ++a)  // acc[n][4a+b] is dim 32n + 8a + 4*h2 + b
-          *(f32x4*)(sm_o + ((wave * G + j) * kHeadDim) + n * 32 + a * 8 + h2 * 4) =
-              (f32x4){acc[n][4 * a], acc[n][4 * a + 1], acc[n][4 * a + 2], acc[n][4 * a + 3]};
-      if (h2 == 0) {
-        sm_m[wave * 32 + j] = m;
-        sm_l[wave * 32 + j] = l;
-      }
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 256) {
-      const int h = idx >> 7, x = idx & 127;
-      float mw[4], mstar = PS_NEG_INF;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        mw[w] = sm_m[w * 32 + h];
-        mstar = fmaxf(mstar, mw[w]);
-      }
-      float L = 0.f, o = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float f = __builtin_amdgcn_exp2f(mw[w] - mstar);  // idle wave: m = -inf -> 0
-        L += sm_l[w * 32 + h] * f;
-        o += sm_o[(w * G + h) * kHeadDim + x] * f;
-      }
-      const int head = g * G + h;
+      const int head = g * G + j;
       if (it.part < 0) {
-        const size_t oi = ((size_t)it.tok * P.Hq + head) * kHeadDim + x;
-        const float r = o / L;
-        if (P.out_f32)
-          ((float*)P.out)[oi] = r;
-        else
-          ((uint16_t*)P.out)[oi] = (uint16_t)(pack_bf16x2(r, 0.f) & 0xFFFFu);
-      } else {
+        const float inv = 1.f / l;
+        const size_t ob = ((size_t)it.tok * P.Hq + head) * kHeadDim;
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+          for (int a = 0; a < 4; ++a) {
+            const int x = n * 32 + a * 8 + h2 * 4;
+            const float o0 = acc[n][4 * a + 0] * inv, o1 = acc[n][4 * a + 1] * inv;
+            const float o2 = acc[n][4 * a + 2] * inv, o3 = acc[n][4 * a + 3] * inv;
+            if (P.out_f32) {
+              *(f32x4*)((float*)P.out + ob + x) = (f32x4){o0, o1, o2, o3};
+            } else {
+              uint2 w = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
+              *(uint2*)((uint16_t*)P.out + ob + x) = w;
+            }
+          }
+      } else {  // unnormalised partial for the merge kernel
         float* dst = P.partials + ((size_t)it.part * P.Hq + head) * kPartStride;
-        dst[x] = o;
-        if (x == 0) {
-          dst[128] = mstar;
-          dst[129] = L;
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+          for (int a = 0; a < 4; ++a)
+            *(f32x4*)(dst + n * 32 + a * 8 + h2 * 4) =
+                (f32x4){acc[n][4 * a], acc[n][4 * a + 1], acc[n][4 * a + 2], acc[n][4 * a + 3]};
+        if (h2 == 0) {
+          dst[128] = m;
+          dst[129] = l;
         }
       }
     }
+    it = itn;
   }
 }
 
@@ -745,8 +763,8 @@ hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s) {
 
 hipError_t launch_decode(const StepParams& p, int n_slots, hipStream_t s) {
   if (n_slots <= 0) return hipSuccess;
-  const size_t smem = (size_t)(4 * p.G * kHeadDim + 256) * sizeof(float);
-  hipLaunchKernelGGL(decode_kernel, dim3(n_slots, p.Hkv), dim3(256), smem, s, p);
+  hipLaunchKernelGGL(decode_kernel, dim3((n_slots + 3) / 4, p.Hkv), dim3(256), 0, s, p, p.ditems, p.dslots, p.block_ids,
+                     n_slots);
   return hipGetLastError();
 }
 
