@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <new>
 #include <string>
 #include <vector>
@@ -458,23 +459,54 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   build_decode_slots(c, b, decode_reqs, n_parts);
   if (!decode_slots_ok(c, b, decode_reqs, c->cover)) return fail(PS_ESTATE, "ps_step: inconsistent decode work list (library bug)");
 
-  // Prefill: a query tile walks `reach` KV tiles.  When the longest walk is much longer than a CU's
-  // fair share of all walks, the launch ends with a few workgroups running alone; then the long
-  // walks are cut into partitions whose partial results the merge kernel combines.
+  // Prefill: a query tile walks `reach` KV tiles.  In a small launch the longest walks decide when
+  // it ends; they can be cut into partitions whose partial results the merge kernel combines.
   const int n_decode_merge = (int)c->mitems.size();
   {
     const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
-    int64_t total = 0, longest = 0;
-    for (auto& t : tiles) {
-      total += t.reach;
-      longest = std::max(longest, t.reach);
-    }
-    const int64_t share = (total * wg_per_tile + 255) / 256;  // KV tiles per CU if spread evenly
-    int64_t split = 0;                                        // partition length in KV tiles; 0 = none
-    if (c->cfg.prefill_split_tiles > 0)
+    int64_t longest = 0;
+    for (auto& t : tiles) longest = std::max(longest, t.reach);
+    int64_t split = 0;  // partition length in KV tiles; 0 = none
+    if (c->cfg.prefill_split_tiles > 0) {
       split = c->cfg.prefill_split_tiles;
-    else if (c->cfg.prefill_split_tiles == 0 && longest * 4 > share * 5 + 16)
-      split = std::max<int64_t>(8, share);
+    } else if (c->cfg.prefill_split_tiles == 0 && !tiles.empty()) {
+      // Candidates: the longest walk cut into k = 1..8 equal parts.  Each is priced in units of one
+      // KV tile step of a workgroup (measured on workload-sized launches): the time the launch
+      // ends when workgroups are handed, longest first, to whichever CU is free next, plus the merge
+      // (a kernel launch worth 4 steps, and 0.0047 steps per partial row of 32 heads).  Launches of
+      // more than 1024 workgroups balance well enough without a cut and are not priced.
+      std::vector<int64_t> sizes, bins;
+      double best = 0;
+      for (int k = 1; k <= 8; ++k) {
+        const int64_t cand = (longest + k - 1) / k;
+        if (k > 1 && cand < 8) break;
+        sizes.clear();
+        int64_t rows = 0;
+        for (auto& t : tiles) {
+          int np = k == 1 ? 1 : (int)std::min<int64_t>((t.reach + cand - 1) / cand, 8);
+          const int64_t len = (t.reach + np - 1) / np;
+          np = (int)((t.reach + len - 1) / len);
+          for (int q = 0; q < np; ++q) sizes.push_back(std::min<int64_t>((int64_t)(q + 1) * len, t.reach) - q * len);
+          if (np > 1) rows += (int64_t)std::min(TT, b->q_start[t.t.req + 1] - b->q_start[t.t.req] - t.t.q0) * np;
+        }
+        if (sizes.size() * (size_t)wg_per_tile > 1024) break;
+        std::sort(sizes.begin(), sizes.end(), std::greater<int64_t>());
+        bins.assign((size_t)c->n_cus, 0);  // min-heap of CU finish times
+        auto later = std::greater<int64_t>();
+        for (int64_t sz : sizes)
+          for (int w = 0; w < wg_per_tile; ++w) {
+            std::pop_heap(bins.begin(), bins.end(), later);
+            bins.back() += sz;
+            std::push_heap(bins.begin(), bins.end(), later);
+          }
+        const int64_t makespan = *std::max_element(bins.begin(), bins.end());
+        const double cost = (double)makespan + (rows > 0 ? 4.0 : 0.0) + 0.0047 * (c->cfg.n_q_heads / 32.0) * (double)rows;
+        if (k == 1 || cost < best) {
+          best = cost;
+          split = k == 1 ? 0 : cand;
+        }
+      }
+    }
     // partial slots: budget of two per batch token, and whatever the caller's workspace holds
     const size_t slot_bytes = (size_t)c->cfg.n_q_heads * ps::kPartStride * sizeof(float);
     int64_t budget = std::min<int64_t>(2 * (int64_t)b->n_tokens, (int64_t)(workspace_bytes / slot_bytes) - n_parts);
