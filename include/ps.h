@@ -99,7 +99,10 @@ typedef struct {
   const uint8_t* prio;      /* [n_req] priority class, may be NULL; carried, not used      */
 } ps_batch;
 
-/* GPU time of the phases of the last profiled ps_step, in milliseconds (0 if not run). */
+/* GPU time of the phases of the last profiled ps_step, in milliseconds (0 if not run), in the
+ * order they run: upload (only with own_streams: the wait for the copy stream; otherwise the
+ * upload shares the append's launch and is counted there), append, decode, prefill, merge (one
+ * launch for the split-K partials of decode tokens and of prefill rows). */
 typedef struct {
   float upload_ms, append_ms, decode_ms, merge_ms, prefill_ms, total_ms;
 } ps_step_times;

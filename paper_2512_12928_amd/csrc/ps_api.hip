@@ -359,7 +359,7 @@ int ps_get_step_times(ps_ctx* c, ps_step_times* out) {
   std::memset(out, 0, sizeof *out);
   if (!c->prof_valid) return fail(PS_ESTATE, "no profiled step");
   PS_HIP(hipEventSynchronize(c->prof_ev[5]));
-  float* dst[5] = {&out->upload_ms, &out->append_ms, &out->decode_ms, &out->merge_ms, &out->prefill_ms};
+  float* dst[5] = {&out->upload_ms, &out->append_ms, &out->decode_ms, &out->prefill_ms, &out->merge_ms};
   for (int i = 0; i < 5; ++i) PS_HIP(hipEventElapsedTime(dst[i], c->prof_ev[i], c->prof_ev[i + 1]));
   PS_HIP(hipEventElapsedTime(&out->total_ms, c->prof_ev[0], c->prof_ev[5]));
   return PS_OK;
@@ -461,7 +461,6 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
 
   // Prefill: a query tile walks `reach` KV tiles.  In a small launch the longest walks decide when
   // it ends; they can be cut into partitions whose partial results the merge kernel combines.
-  const int n_decode_merge = (int)c->mitems.size();
   {
     const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
     int64_t longest = 0;
@@ -591,9 +590,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   } else {  // everything on the caller's stream (the two buffers still alternate)
     if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
     if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
-    // a small kernel that reads the pinned slot over the host link: a third of the latency of a DMA copy
-    PS_HIP(ps::launch_upload(h, mb.dev, ml.total, stream));
-    PS_HIP(hipEventRecord(slot.ev, stream));
+    // the upload is part of the prologue kernel launched below
   }
   slot.in_flight = true;
   mb.used = true;
@@ -605,7 +602,6 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   P.kv_len = (const int32_t*)(w + ml.kv_len);
   P.bt_start = (const int32_t*)(w + ml.bt_start);
   P.block_ids = (const int32_t*)(w + ml.block_ids);
-  P.aitems = (const ps::AppendItem*)(w + ml.aitems);
   P.ditems = (const ps::DecodeItem*)(w + ml.ditems);
   P.dslots = (const int32_t*)(w + ml.dslots);
   P.mitems = (const ps::MergeItem*)(w + ml.mitems);
@@ -622,28 +618,31 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   P.out_f32 = c->cfg.out_dtype == PS_F32;
   P.scale_log2 = c->scale_log2;
 
-  if (k_new) PS_HIP(ps::launch_append(P, (int)c->aitems.size(), stream));
+  // Prologue: one launch.  It appends the new K/V rows and, unless the context's copy stream has
+  // already brought the batch description over, uploads it with a kernel that reads the pinned slot
+  // over the host link (a third of the latency of a DMA copy).
+  PS_HIP(ps::launch_prologue(P, h, mb.dev, c->copy ? 0 : ml.total, (const ps::AppendItem*)(h + ml.aitems),
+                             k_new ? (int)c->aitems.size() : 0, stream));
+  if (!c->copy || k_new) PS_HIP(hipEventRecord(slot.ev, stream));  // last reader of the pinned slot
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
   // Decode streams the cache at HBM speed and leaves the matrix pipes idle, prefill is the
-  // opposite: with both kinds of work in the batch, run them side by side.
+  // opposite: with own streams and both kinds of work in the batch, run them side by side.
+  // One merge launch at the end combines the partials of both.
   const bool fork = !prof && c->side && !c->ditems.empty() && !c->ptiles.empty();
   if (fork) {
     PS_HIP(hipEventRecord(c->fork_ev, stream));
     PS_HIP(hipStreamWaitEvent(c->side, c->fork_ev, 0));
     PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), c->side));
-    PS_HIP(ps::launch_merge(P, n_decode_merge, (int)c->mitems.size() - n_decode_merge, c->side));  // split prefill rows
     PS_HIP(hipEventRecord(c->join_ev, c->side));
   }
   PS_HIP(ps::launch_decode(P, (int)c->dslots.size() - 1, stream));
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[3], stream));
-  PS_HIP(ps::launch_merge(P, 0, n_decode_merge, stream));
-  if (prof) PS_HIP(hipEventRecord(c->prof_ev[4], stream));
-  if (fork) {
+  if (fork)
     PS_HIP(hipStreamWaitEvent(stream, c->join_ev, 0));
-  } else {
+  else
     PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), stream));
-    PS_HIP(ps::launch_merge(P, n_decode_merge, (int)c->mitems.size() - n_decode_merge, stream));
-  }
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev[4], stream));
+  PS_HIP(ps::launch_merge(P, 0, (int)c->mitems.size(), stream));
   if (prof) {
     PS_HIP(hipEventRecord(c->prof_ev[5], stream));
     c->prof_valid = true;

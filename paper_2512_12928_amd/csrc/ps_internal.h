@@ -60,7 +60,6 @@ struct StepParams {
   const int32_t* kv_len;
   const int32_t* bt_start;
   const int32_t* block_ids;
-  const AppendItem* aitems;
   const DecodeItem* ditems;
   const int32_t* dslots;  // n_slots + 1 offsets into ditems
   const MergeItem* mitems;
@@ -78,9 +77,11 @@ struct StepParams {
 };
 
 // Launchers (ps_kernels.hip). Each checks its own launch and returns the hipError_t.
-// dst (device) <- src (pinned host memory, read over the host link by the kernel), bytes a multiple of 16
-hipError_t launch_upload(const void* src_pinned, void* dst, size_t bytes, hipStream_t s);
-hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s);
+// Uploads the batch description, dst (device) <- src_pinned (pinned host memory, read over the host
+// link by the kernel; bytes a multiple of 16), and in the same launch appends the step's new K/V
+// rows (n_items append items, read from aitems_pinned, which lies in the same pinned block).
+hipError_t launch_prologue(const StepParams& p, const void* src_pinned, void* dst, size_t bytes,
+                           const AppendItem* aitems_pinned, int n_items, hipStream_t s);
 hipError_t launch_decode(const StepParams& p, int n_slots, hipStream_t s);
 // merges items [first, first + n_merge) of the merge list
 hipError_t launch_merge(const StepParams& p, int first, int n_merge, hipStream_t s);

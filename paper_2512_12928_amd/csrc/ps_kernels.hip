@@ -49,32 +49,39 @@ __device__ __forceinline__ const uint16_t* v_slice(const uint16_t* cache, int bl
   return cache + ((size_t)(block * 2 + 1) * Hkv + g) * kSliceElems;
 }
 
-// ------------------------------------------------------------------------------------ upload
-// Device copy of the step's batch description: dst <- src, n16 units of 16 bytes.  src is pinned
-// host memory read over the host link; every lane has its loads in flight before the first store.
-__global__ __launch_bounds__(256) void upload_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int n16) {
-  const int stride = gridDim.x * 256;
-  for (int i = blockIdx.x * 256 + threadIdx.x; i < n16; i += 4 * stride) {
-    uint4 v[4];
+// ------------------------------------------------------------------------------------ prologue
+// One launch, 256 threads per workgroup, two kinds of workgroup:
+//  - the first n_up copy the step's batch description to the device: dst <- src, n16 units of
+//    16 bytes.  src is pinned host memory read over the host link; every lane has its loads in
+//    flight before the first store.
+//  - the rest write this step's new K/V rows into the paged cache, two (item, kv-head) pairs per
+//    workgroup (128 threads each).  An item is the new rows of one request that fall into one
+//    block; the items are read from the pinned copy (the device copy is being written by the
+//    other workgroups of this launch).  K goes to [dim/8][token][8]: a thread moves 16-byte groups
+//    (token, 8 dims).  V is dim-major inside a block: thread x owns dim x; when the chunk covers
+//    the whole block it gathers its dim from the 16 rows and writes one full 32-byte run,
+//    otherwise (a decode token, the ragged ends of a chunk) it writes 2-byte elements.  All loads
+//    of a thread are issued before its first store.
+__global__ __launch_bounds__(256) void prologue_kernel(StepParams P, const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                       int n16, int n_up, const AppendItem* __restrict__ aitems_pinned,
+                                                       int n_pairs) {
+  if ((int)blockIdx.x < n_up) {
+    const int stride = n_up * 256;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n16; i += 4 * stride) {
+      uint4 v[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (i + u * stride < n16) v[u] = src[i + u * stride];
+      for (int u = 0; u < 4; ++u)
+        if (i + u * stride < n16) v[u] = src[i + u * stride];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (i + u * stride < n16) dst[i + u * stride] = v[u];
+      for (int u = 0; u < 4; ++u)
+        if (i + u * stride < n16) dst[i + u * stride] = v[u];
+    }
+    return;
   }
-}
-
-// ------------------------------------------------------------------------------------ append
-// Writes this step's new K/V rows into the paged cache.  grid (n_items, Hkv), 128 threads: a
-// workgroup owns the new rows of one request that fall into one block.  K goes to
-// [dim/8][token][8]: a thread moves 16-byte groups (token, 8 dims).  V is dim-major inside a
-// block: thread x owns dim x; when the chunk covers the whole block it gathers its dim from the
-// 16 rows and writes one full 32-byte run, otherwise (a decode token, the ragged ends of a chunk)
-// it writes 2-byte elements.  All loads of a thread are issued before its first store.
-__global__ __launch_bounds__(128) void append_kernel(StepParams P) {
-  const AppendItem it = P.aitems[blockIdx.x];
-  const int g = blockIdx.y, x = threadIdx.x;
+  const int pair = ((int)blockIdx.x - n_up) * 2 + (threadIdx.x >> 7);  // item * Hkv + kv-head
+  if (pair >= n_pairs) return;
+  const AppendItem it = aitems_pinned[pair / P.Hkv];
+  const int g = pair % P.Hkv, x = threadIdx.x & 127;
   uint16_t* kd = const_cast<uint16_t*>(k_slice(P.cache, it.block, P.Hkv, g));
   uint16_t* vd = const_cast<uint16_t*>(v_slice(P.cache, it.block, P.Hkv, g));
   const size_t rstride = (size_t)P.Hkv * kHeadDim;
@@ -99,11 +106,11 @@ __global__ __launch_bounds__(128) void append_kernel(StepParams P) {
     if (tt < it.n) *(u32x4*)(kd + grp * (kBlockTokens * 8) + (it.slot0 + tt) * 8) = kv[h];
   }
   if (it.n == kBlockTokens) {
-    uint4* dst = (uint4*)(vd + x * kBlockTokens);
-    dst[0] = make_uint4(vv[0] | ((uint32_t)vv[1] << 16), vv[2] | ((uint32_t)vv[3] << 16), vv[4] | ((uint32_t)vv[5] << 16),
-                        vv[6] | ((uint32_t)vv[7] << 16));
-    dst[1] = make_uint4(vv[8] | ((uint32_t)vv[9] << 16), vv[10] | ((uint32_t)vv[11] << 16),
-                        vv[12] | ((uint32_t)vv[13] << 16), vv[14] | ((uint32_t)vv[15] << 16));
+    uint4* dst2 = (uint4*)(vd + x * kBlockTokens);
+    dst2[0] = make_uint4(vv[0] | ((uint32_t)vv[1] << 16), vv[2] | ((uint32_t)vv[3] << 16), vv[4] | ((uint32_t)vv[5] << 16),
+                         vv[6] | ((uint32_t)vv[7] << 16));
+    dst2[1] = make_uint4(vv[8] | ((uint32_t)vv[9] << 16), vv[10] | ((uint32_t)vv[11] << 16),
+                         vv[12] | ((uint32_t)vv[13] << 16), vv[14] | ((uint32_t)vv[15] << 16));
   } else {
 #pragma unroll
     for (int tt = 0; tt < kBlockTokens; ++tt)
@@ -747,17 +754,15 @@ __global__ __launch_bounds__(256) void block_copy_kernel(const int32_t* __restri
 }
 
 // ------------------------------------------------------------------------------------ launchers
-hipError_t launch_upload(const void* src_pinned, void* dst, size_t bytes, hipStream_t s) {
-  if (bytes == 0) return hipSuccess;
+hipError_t launch_prologue(const StepParams& p, const void* src_pinned, void* dst, size_t bytes,
+                           const AppendItem* aitems_pinned, int n_items, hipStream_t s) {
   const int n16 = (int)(bytes / 16);
-  const int grid = std::min((n16 + 1023) / 1024, 64);  // 4 loads per lane in flight
-  hipLaunchKernelGGL(upload_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)src_pinned, (uint4*)dst, n16);
-  return hipGetLastError();
-}
-
-hipError_t launch_append(const StepParams& p, int n_items, hipStream_t s) {
-  if (n_items <= 0) return hipSuccess;
-  hipLaunchKernelGGL(append_kernel, dim3(n_items, p.Hkv), dim3(128), 0, s, p);
+  const int n_up = std::min((n16 + 1023) / 1024, 64);  // 4 loads per lane in flight
+  const int n_pairs = n_items * p.Hkv;
+  const int grid = n_up + (n_pairs + 1) / 2;
+  if (grid <= 0) return hipSuccess;
+  hipLaunchKernelGGL(prologue_kernel, dim3(grid), dim3(256), 0, s, p, (const uint4*)src_pinned, (uint4*)dst, n16, n_up,
+                     aitems_pinned, n_pairs);
   return hipGetLastError();
 }
 
