@@ -69,14 +69,12 @@ typedef struct {
                               (see decode_waves); N > 0, a multiple of 32 in [32, 65536]:
                               fixed split-K partitions of N KV tokens, one wave each, instead  */
   int32_t swap_workgroups; /* workgroups used by a swap kernel; 0 => library picks        */
-  int32_t own_streams;     /* 0 (default): every copy and kernel of a step is enqueued on the
-                              caller's stream. 1: the context creates two streams of its own
-                              (default priority): the batch description of step n+1 is uploaded
-                              while the kernels of step n run, and the MFMA-bound prefill kernel
-                              runs next to the HBM-bound decode kernels (fork/join with events).
-                              Measured gain 0-2 %; a process has few hardware queues, and streams
-                              that share one run one after another, so this is opt-in.
-                              Profiled steps always run every kernel on the caller's stream.   */
+  int32_t own_streams;     /* 0 (default): everything a step does is enqueued on the caller's
+                              stream. 1: the context creates a copy stream of its own (default
+                              priority) on which the batch description of step n+1 is uploaded
+                              while the kernels of step n run. A process has few hardware
+                              queues, and streams that share one run one after another, so
+                              this is opt-in.                                                  */
   int32_t prefill_split_tiles; /* 0 (default): the library splits the KV range of long prefill
                               rows over several workgroups (partials merged like decode's) when
                               the launch would otherwise be unbalanced; N > 0: always split into
@@ -99,18 +97,20 @@ typedef struct {
   const uint8_t* prio;      /* [n_req] priority class, may be NULL; carried, not used      */
 } ps_batch;
 
-/* GPU time of the phases of the last profiled ps_step, in milliseconds (0 if not run), in the
- * order they run: upload (only with own_streams: the wait for the copy stream; otherwise the
- * upload shares the append's launch and is counted there), append, decode, prefill, merge (one
- * launch for the split-K partials of decode tokens and of prefill rows). */
+/* GPU time of the phases of the last profiled ps_step, in milliseconds, in the order they run:
+ * upload (only with own_streams: the wait for the copy stream; otherwise the upload shares the
+ * append's launch and is counted there), append, attention (one launch for the decode and the
+ * prefill work of the batch), merge (the split-K partials of decode tokens and prefill rows).
+ * decode_ms and prefill_ms are filled in profiling mode 2 only, where the two kinds of work are
+ * launched one after the other (each with the whole chip) and attention_ms is their sum. */
 typedef struct {
-  float upload_ms, append_ms, decode_ms, merge_ms, prefill_ms, total_ms;
+  float upload_ms, append_ms, decode_ms, merge_ms, prefill_ms, total_ms, attention_ms;
 } ps_step_times;
 
 const char* ps_last_error(void);
 
 /* Creates a context on the current HIP device. The context owns small pinned staging buffers,
- * events, with cfg.own_streams two streams, and two device copies of the batch description
+ * events, with cfg.own_streams a copy stream, and two device copies of the batch description
  * (the arrays of ps_batch plus work lists, about 5 bytes per block-table entry; they grow, with
  * a hipMalloc inside ps_step, when a batch is larger than any before). PS_EINVAL on a bad cfg. */
 int ps_create(const ps_layer_cfg* cfg, ps_ctx** out);
@@ -149,8 +149,10 @@ int ps_step(ps_ctx* ctx, const ps_batch* batch, const void* q, const void* k_new
             const void* v_new, void* kv_cache, void* out, void* workspace,
             size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket);
 
-/* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds). */
-int ps_set_profiling(ps_ctx* ctx, int enabled);
+/* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds).
+ * mode 0: off; 1: the phases as they run; 2: the decode and the prefill work of the attention
+ * phase in launches of their own, one after the other. PS_EINVAL for any other mode. */
+int ps_set_profiling(ps_ctx* ctx, int mode);
 /* Blocks until the last profiled step has finished, then fills *out. */
 int ps_get_step_times(ps_ctx* ctx, ps_step_times* out);
 

@@ -43,7 +43,8 @@ class ps_batch(C.Structure):
 
 
 class ps_step_times(C.Structure):
-    _fields_ = [(n, C.c_float) for n in ("upload_ms", "append_ms", "decode_ms", "merge_ms", "prefill_ms", "total_ms")]
+    _fields_ = [(n, C.c_float) for n in ("upload_ms", "append_ms", "decode_ms", "merge_ms", "prefill_ms", "total_ms",
+                                             "attention_ms")]
 
 
 class ps_sched_cfg(C.Structure):
@@ -189,8 +190,8 @@ def ps_step(ctx: int, batch, q, k_new, v_new, kv_cache, out, workspace, workspac
     del keep
 
 
-def ps_set_profiling(ctx: int, enabled: bool) -> None:
-    _check(lib().ps_set_profiling(ctx, int(enabled)))
+def ps_set_profiling(ctx: int, mode) -> None:
+    _check(lib().ps_set_profiling(ctx, int(mode)))
 
 
 def ps_get_step_times(ctx: int) -> dict:

@@ -72,12 +72,11 @@ struct ps_ctx {
   } meta[2];
   int meta_next = 0;
   hipStream_t copy = nullptr;
-  hipStream_t side = nullptr;  // prefill kernel of a step, concurrent with its decode kernels
-  hipEvent_t fork_ev = nullptr, join_ev = nullptr;
   int n_cus = 256;
-  bool profiling = false;
+  int profiling = 0;  // 0 off, 1 phases as they run, 2 decode and prefill roles in launches of their own
   hipEvent_t prof_ev[6];
   bool prof_valid = false;
+  int prof_mode = 0;
   std::vector<ps::DecodeItem> ditems;
   std::vector<int32_t> dslots;  // slot x owns ditems[dslots[x] .. dslots[x+1])
   std::vector<ps::MergeItem> mitems;
@@ -99,7 +98,7 @@ constexpr int kMinSlotTiles = 16;  // a balanced decode slot holds at least this
 //    once (cfg.decode_waves, default one per SIMD: measured best) and a slot is not shorter than
 //    kMinSlotTiles.  At most S - 1 requests are cut, so there are at most n_req + S segments.
 // A request with several segments gets one partials slot per segment and a merge item.
-void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& reqs, int& n_parts) {
+void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& reqs, int& n_parts, int waves) {
   c->dslots.clear();
   c->dslots.push_back(0);
   auto close_slot = [&]() {
@@ -128,7 +127,6 @@ void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& re
   }
   int64_t T = 0;
   for (int r : reqs) T += (b->kv_len[r] + ps::kTileTokens - 1) / ps::kTileTokens;
-  const int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : 4 * c->n_cus;
   const int64_t S = std::max<int64_t>(1, std::min<int64_t>(waves / c->cfg.n_kv_heads, T / kMinSlotTiles));
   auto boundary = [&](int64_t x) { return ((x + 1) * T + S - 1) / S; };  // nominal end of slot x, in tiles
   int64_t off = 0, x = 0;
@@ -287,15 +285,12 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
     e = hipEventCreateWithFlags(&c->ticket_ev[i], hipEventDisableTiming);
   for (int i = 0; i < 6 && e == hipSuccess; ++i) e = hipEventCreate(&c->prof_ev[i]);
   if (cfg->own_streams) {
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);  // default priority
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
   }
   for (int i = 0; i < 2 && e == hipSuccess; ++i) {
     e = hipEventCreateWithFlags(&c->meta[i].uploaded, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->meta[i].done, hipEventDisableTiming);
   }
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
   if (e != hipSuccess) {
     int rc = fail(PS_EHIP, "ps_create: %s", hipGetErrorString(e));
     ps_destroy(c);
@@ -320,9 +315,6 @@ void ps_destroy(ps_ctx* c) {
     if (e) (void)hipEventDestroy(e);
   for (auto& e : c->prof_ev)
     if (e) (void)hipEventDestroy(e);
-  if (c->fork_ev) (void)hipEventDestroy(c->fork_ev);
-  if (c->join_ev) (void)hipEventDestroy(c->join_ev);
-  if (c->side) (void)hipStreamDestroy(c->side);
   if (c->copy) (void)hipStreamDestroy(c->copy);
   for (auto& mb : c->meta) {
     if (mb.dev) (void)hipFree(mb.dev);
@@ -349,7 +341,8 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
 
 int ps_set_profiling(ps_ctx* c, int enabled) {
   if (!c) return fail(PS_EINVAL, "NULL ctx");
-  c->profiling = enabled != 0;
+  if (enabled < 0 || enabled > 2) return fail(PS_EINVAL, "ps_set_profiling: mode must be 0, 1 or 2");
+  c->profiling = enabled;
   c->prof_valid = false;
   return PS_OK;
 }
@@ -359,8 +352,17 @@ int ps_get_step_times(ps_ctx* c, ps_step_times* out) {
   std::memset(out, 0, sizeof *out);
   if (!c->prof_valid) return fail(PS_ESTATE, "no profiled step");
   PS_HIP(hipEventSynchronize(c->prof_ev[5]));
-  float* dst[5] = {&out->upload_ms, &out->append_ms, &out->decode_ms, &out->prefill_ms, &out->merge_ms};
-  for (int i = 0; i < 5; ++i) PS_HIP(hipEventElapsedTime(dst[i], c->prof_ev[i], c->prof_ev[i + 1]));
+  float att = 0.f, pre = 0.f;
+  PS_HIP(hipEventElapsedTime(&out->upload_ms, c->prof_ev[0], c->prof_ev[1]));
+  PS_HIP(hipEventElapsedTime(&out->append_ms, c->prof_ev[1], c->prof_ev[2]));
+  PS_HIP(hipEventElapsedTime(&att, c->prof_ev[2], c->prof_ev[3]));
+  PS_HIP(hipEventElapsedTime(&pre, c->prof_ev[3], c->prof_ev[4]));
+  PS_HIP(hipEventElapsedTime(&out->merge_ms, c->prof_ev[4], c->prof_ev[5]));
+  if (c->prof_mode == 2) {
+    out->decode_ms = att;
+    out->prefill_ms = pre;
+  }
+  out->attention_ms = att + pre;
   PS_HIP(hipEventElapsedTime(&out->total_ms, c->prof_ev[0], c->prof_ev[5]));
   return PS_OK;
 }
@@ -438,6 +440,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   };
   std::vector<TileKey> tiles;
   std::vector<int> decode_reqs;
+  double prefill_steps = 0;  // price of the batch's prefill work on the whole chip, in KV tile steps
   for (int r = 0; r < n_req; ++r) {
     const int qs = b->q_start[r], lq = b->q_start[r + 1] - qs, L = b->kv_len[r];
     if (k_new)
@@ -456,9 +459,6 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       }
     }
   }
-  build_decode_slots(c, b, decode_reqs, n_parts);
-  if (!decode_slots_ok(c, b, decode_reqs, c->cover)) return fail(PS_ESTATE, "ps_step: inconsistent decode work list (library bug)");
-
   // Prefill: a query tile walks `reach` KV tiles.  In a small launch the longest walks decide when
   // it ends; they can be cut into partitions whose partial results the merge kernel combines.
   {
@@ -466,6 +466,11 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     int64_t longest = 0;
     for (auto& t : tiles) longest = std::max(longest, t.reach);
     int64_t split = 0;  // partition length in KV tiles; 0 = none
+    {  // default price of the prefill work, in KV tile steps per CU: an even spread
+      int64_t total = 0;
+      for (auto& t : tiles) total += t.reach;
+      prefill_steps = (double)total * wg_per_tile / c->n_cus;
+    }
     if (c->cfg.prefill_split_tiles > 0) {
       split = c->cfg.prefill_split_tiles;
     } else if (c->cfg.prefill_split_tiles == 0 && !tiles.empty()) {
@@ -505,6 +510,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
           split = k == 1 ? 0 : cand;
         }
       }
+      if (best > 0) prefill_steps = best;
     }
     // partial slots: budget of two per batch token, and whatever the caller's workspace holds
     const size_t slot_bytes = (size_t)c->cfg.n_q_heads * ps::kPartStride * sizeof(float);
@@ -537,6 +543,24 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     }
     tiles.swap(cut);
   }
+  // Decode slots.  With prefill work in the same launch the decode workgroups get the share of the
+  // CUs that makes both kinds of work end together (each priced at its full-chip speed: 6.3 TB/s
+  // for the cache stream, 1.92 us per KV tile step of a prefill workgroup; the decode share is cut
+  // by 5 %: prefill workgroups inherit CUs that decode leaves early, never the other way round).
+  {
+    int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
+    if (c->cfg.decode_waves == 0 && c->profiling != 2 && !decode_reqs.empty() && !tiles.empty()) {
+      const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / 6.3e6;  // us
+      const double t_p = prefill_steps * 1.92;
+      int cus = (int)(0.95 * c->n_cus * t_d / (t_d + t_p));
+      cus = std::max(std::min(8, c->n_cus), std::min(cus, c->n_cus - 8));
+      waves = ps::decode_waves_per_wg() * cus;
+    }
+    build_decode_slots(c, b, decode_reqs, n_parts, waves);
+    if (!decode_slots_ok(c, b, decode_reqs, c->cover))
+      return fail(PS_ESTATE, "ps_step: inconsistent decode work list (library bug)");
+  }
+
   // heaviest partitions first, so the tail of the launch is made of short ones
   std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
   for (auto& t : tiles) c->ptiles.push_back(t.t);
@@ -578,7 +602,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     mb.cap = cap;
     mb.used = false;
   }
-  const bool prof = c->profiling;
+  const int prof = c->profiling;
   if (c->copy) {  // own copy stream: the upload does not wait for the caller's earlier work
     if (mb.used) PS_HIP(hipStreamWaitEvent(c->copy, mb.done, 0));
     PS_HIP(hipMemcpyAsync(mb.dev, h, ml.total, hipMemcpyHostToDevice, c->copy));
@@ -625,27 +649,27 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
                              k_new ? (int)c->aitems.size() : 0, stream));
   if (!c->copy || k_new) PS_HIP(hipEventRecord(slot.ev, stream));  // last reader of the pinned slot
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
-  // Decode streams the cache at HBM speed and leaves the matrix pipes idle, prefill is the
-  // opposite: with own streams and both kinds of work in the batch, run them side by side.
-  // One merge launch at the end combines the partials of both.
-  const bool fork = !prof && c->side && !c->ditems.empty() && !c->ptiles.empty();
-  if (fork) {
-    PS_HIP(hipEventRecord(c->fork_ev, stream));
-    PS_HIP(hipStreamWaitEvent(c->side, c->fork_ev, 0));
-    PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), c->side));
-    PS_HIP(hipEventRecord(c->join_ev, c->side));
+  // Attention: one launch for the decode slots and the prefill tiles (decode streams the cache at
+  // HBM speed and leaves the matrix pipes idle, prefill is the opposite: they run side by side on
+  // disjoint CUs).  Profiling mode 2 gives each its own launch instead.
+  const int n_slots = (int)c->dslots.size() - 1;
+  if (prof == 2) {
+    PS_HIP(ps::launch_attention(P, n_slots, 0, stream));
+    PS_HIP(hipEventRecord(c->prof_ev[3], stream));
+    PS_HIP(ps::launch_attention(P, 0, (int)c->ptiles.size(), stream));
+    PS_HIP(hipEventRecord(c->prof_ev[4], stream));
+  } else {
+    PS_HIP(ps::launch_attention(P, n_slots, (int)c->ptiles.size(), stream));
+    if (prof) {
+      PS_HIP(hipEventRecord(c->prof_ev[3], stream));
+      PS_HIP(hipEventRecord(c->prof_ev[4], stream));
+    }
   }
-  PS_HIP(ps::launch_decode(P, (int)c->dslots.size() - 1, stream));
-  if (prof) PS_HIP(hipEventRecord(c->prof_ev[3], stream));
-  if (fork)
-    PS_HIP(hipStreamWaitEvent(stream, c->join_ev, 0));
-  else
-    PS_HIP(ps::launch_prefill(P, (int)c->ptiles.size(), stream));
-  if (prof) PS_HIP(hipEventRecord(c->prof_ev[4], stream));
   PS_HIP(ps::launch_merge(P, 0, (int)c->mitems.size(), stream));
   if (prof) {
     PS_HIP(hipEventRecord(c->prof_ev[5], stream));
     c->prof_valid = true;
+    c->prof_mode = prof;
   }
   if (c->copy) PS_HIP(hipEventRecord(mb.done, stream));
   return PS_OK;

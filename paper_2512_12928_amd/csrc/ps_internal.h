@@ -82,11 +82,12 @@ struct StepParams {
 // rows (n_items append items, read from aitems_pinned, which lies in the same pinned block).
 hipError_t launch_prologue(const StepParams& p, const void* src_pinned, void* dst, size_t bytes,
                            const AppendItem* aitems_pinned, int n_items, hipStream_t s);
-hipError_t launch_decode(const StepParams& p, int n_slots, hipStream_t s);
 // merges items [first, first + n_merge) of the merge list
 hipError_t launch_merge(const StepParams& p, int first, int n_merge, hipStream_t s);
+// One launch for the decode slots and the prefill tiles of the batch (either may be 0).
+hipError_t launch_attention(const StepParams& p, int n_slots, int n_tiles, hipStream_t s);
+int decode_waves_per_wg();
 // tile_tokens: query tokens per workgroup tile as returned by prefill_tile_tokens(G).
-hipError_t launch_prefill(const StepParams& p, int n_tiles, hipStream_t s);
 int prefill_tile_tokens(int G);
 int prefill_heads_per_wg(int G);
 hipError_t launch_block_copy(const int32_t* src_ids, const int32_t* dst_ids, int n, const void* src_pool,

@@ -221,12 +221,26 @@ def test_empty_batch_and_validation_errors():
 
 
 def test_profiling_times_are_reported():
+    """Mode 1 times the phases as they run (one attention launch); mode 2 gives the decode and the
+    prefill work launches of their own.  Both leave the results unchanged."""
     b = W.make_workload(2, scale=0.08)
     t = W.make_tensors(b)
     cache = oracle_cache(b, t)
     lay = Layer(b)
-    B.ps_set_profiling(lay.ctx, True)
-    lay.step(b, u16_to_dev(t.q), u16_to_dev(to_device_layout(cache.pool)))
+    ref = lay.step(b, u16_to_dev(t.q), u16_to_dev(to_device_layout(cache.pool))).clone()
+    B.ps_set_profiling(lay.ctx, 1)
+    got = lay.step(b, u16_to_dev(t.q), u16_to_dev(to_device_layout(cache.pool)))
     tm = B.ps_get_step_times(lay.ctx)
-    assert tm["total_ms"] > 0 and tm["decode_ms"] > 0 and tm["prefill_ms"] > 0
+    assert tm["total_ms"] > 0 and tm["attention_ms"] > 0 and tm["decode_ms"] == 0 and tm["prefill_ms"] == 0
+    assert torch.equal(got, ref)
+    B.ps_set_profiling(lay.ctx, 2)
+    got = lay.step(b, u16_to_dev(t.q), u16_to_dev(to_device_layout(cache.pool)))
+    tm = B.ps_get_step_times(lay.ctx)
+    assert tm["decode_ms"] > 0 and tm["prefill_ms"] > 0
+    assert abs(tm["attention_ms"] - tm["decode_ms"] - tm["prefill_ms"]) < 1e-3
+    # the decode slots are cut differently in mode 2 (whole chip), so only closeness is asserted
+    assert (got.float() - ref.float()).abs().max().item() < 2e-2
+    with pytest.raises(B.PsError) as e:
+        B.ps_set_profiling(lay.ctx, 3)
+    assert e.value.code == B.PS_EINVAL
     lay.close()
