@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the engine-step hot path on one MI355X.
 
-A step is one pass of the hot path over one synthetic mixed batch: host batch description ->
-device, KV append, split-K decode attention + merge, prefill-chunk attention (ps_step).  The
+A step is one pass of the hot path over one synthetic mixed batch (ps_step): host batch
+description -> device and KV append (one launch), split-K decode attention and prefill-chunk
+attention side by side (one launch), merge of the split-K partials (one launch).  The
 headline workload is the Qwen3-8B-shaped layer (256 decode requests + 2048 prefill tokens in 4
 chunks).  Prints ONE JSON line; see the design doc for the fields.
 """
@@ -18,9 +19,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of decode_kernel + merge_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (scaled by a plain 1 GiB copy; summary in profiles/attention_kernels_hbm_traffic_pmc.md), by workload index.
-MEASURED_DECODE_TRAFFIC = {2: 1.488e9 + 1.2e7, 4: 3.032e9 + 5.3e6}
+# HBM bytes per launch of attention_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+# plain 1 GiB copy; summary in profiles/attention_kernel_hbm_traffic_pmc.md), by workload index.
+MEASURED_ATTENTION_TRAFFIC = {2: 1.607e9, 4: 3.401e9}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
@@ -57,13 +58,19 @@ def main() -> int:
         return W.device_inputs(batch, seed, dev)
 
     def algorithmic(batch):
+        """Bytes the attention launch has to move at least (decode: every cached K/V byte once, q, out,
+        table; prefill: the K/V of every chunk's context once, q, out, table) and the prefill FLOPs."""
         s = batch.shape
-        dec = batch.decode_reqs
-        kv_bytes = int(batch.kv_len[dec].astype(np.int64).sum()) * s.n_kv_heads * s.head_dim * 2 * 2
-        qo_bytes = len(dec) * 2 * s.n_q_heads * s.head_dim * 2
-        tab_bytes = int(sum(4 * -(-int(batch.kv_len[r]) // s.block_tokens) for r in dec))
+        tok_bytes = s.n_kv_heads * s.head_dim * 2 * 2
+        row_bytes = 2 * s.n_q_heads * s.head_dim * 2          # one q row in, one out row out
+
+        def part(reqs):
+            kv = int(batch.kv_len[reqs].astype(np.int64).sum()) * tok_bytes
+            rows = int(sum(batch.l_q(int(r)) for r in reqs)) * row_bytes
+            tab = int(sum(4 * -(-int(batch.kv_len[r]) // s.block_tokens) for r in reqs))
+            return kv + rows + tab
         flops = 4 * s.head_dim * s.n_q_heads * batch.causal_pairs()
-        return kv_bytes + qo_bytes + tab_bytes, flops
+        return part(batch.decode_reqs), part(batch.prefill_reqs), flops
 
     def run(batch, steps, warmup, decode_chunk=0, profile_steps=20):
         s = batch.shape
@@ -83,28 +90,38 @@ def main() -> int:
             B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        # per-kernel durations: HIP events recorded by the library on the launch stream
-        B.ps_set_profiling(ctx, True)
-        acc = {}
-        for _ in range(profile_steps):
-            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
-            for k, v in B.ps_get_step_times(ctx).items():
-                acc[k] = acc.get(k, 0.0) + v / profile_steps
-        B.ps_set_profiling(ctx, False)
-        res = dict(ms_per_step=dt / steps * 1e3, phases_ms=acc, ctx=ctx, pool=pool, q=q, out=out, kn=kn, vn=vn)
+        # per-launch durations: HIP events recorded by the library on the launch stream.  Mode 1: the
+        # phases as they run; mode 2: the decode and the prefill work in launches of their own
+        phases = {}
+        for mode in (1, 2):
+            B.ps_set_profiling(ctx, mode)
+            acc = {}
+            for _ in range(profile_steps):
+                B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+                for k, v in B.ps_get_step_times(ctx).items():
+                    acc[k] = acc.get(k, 0.0) + v / profile_steps
+            phases[mode] = acc
+        B.ps_set_profiling(ctx, 0)
+        res = dict(ms_per_step=dt / steps * 1e3, phases_ms=phases, ctx=ctx, pool=pool, q=q, out=out, kn=kn, vn=vn)
         return res
 
     def rooflines(batch, res):
-        bytes_dec, flops_pre = algorithmic(batch)
-        ph = res["phases_ms"]
-        dec_s = (ph["decode_ms"] + ph["merge_ms"]) * 1e-3
-        pre_s = ph["prefill_ms"] * 1e-3
+        bytes_dec, bytes_pre, flops_pre = algorithmic(batch)
+        run_, alone = res["phases_ms"][1], res["phases_ms"][2]
+        att_s = run_["attention_ms"] * 1e-3
+        dec_s, pre_s = alone["decode_ms"] * 1e-3, alone["prefill_ms"] * 1e-3
+        att_gbs = (bytes_dec + bytes_pre) / att_s / 1e9 if att_s > 0 else 0.0
+        att_tf = flops_pre / att_s / 1e12 if att_s > 0 else 0.0
         dec_gbs = bytes_dec / dec_s / 1e9 if dec_s > 0 else 0.0
         pre_tf = flops_pre / pre_s / 1e12 if pre_s > 0 else 0.0
-        return dict(decode_GBps=dec_gbs, decode_frac=dec_gbs / HBM_PEAK_GBS, prefill_TFLOPs=pre_tf,
-                    prefill_frac=pre_tf / MFMA_BF16_PEAK_TFLOPS, decode_bytes=bytes_dec, prefill_flops=flops_pre,
-                    decode_ms=ph["decode_ms"], merge_ms=ph["merge_ms"], prefill_ms=ph["prefill_ms"],
-                    append_ms=ph["append_ms"], upload_ms=ph["upload_ms"])
+        return dict(attention_ms=run_["attention_ms"], attention_GBps=att_gbs, attention_hbm_frac=att_gbs / HBM_PEAK_GBS,
+                    attention_TFLOPs=att_tf, attention_mfma_frac=att_tf / MFMA_BF16_PEAK_TFLOPS,
+                    attention_bytes=bytes_dec + bytes_pre, prefill_flops=flops_pre,
+                    append_ms=run_["append_ms"], merge_ms=run_["merge_ms"],
+                    # the two kinds of work in launches of their own, each with the whole chip
+                    decode_alone_ms=alone["decode_ms"], decode_alone_GBps=dec_gbs, decode_alone_frac=dec_gbs / HBM_PEAK_GBS,
+                    prefill_alone_ms=alone["prefill_ms"], prefill_alone_TFLOPs=pre_tf,
+                    prefill_alone_frac=pre_tf / MFMA_BF16_PEAK_TFLOPS)
 
     if args.pmc_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -193,13 +210,14 @@ def main() -> int:
         extra["swap"] = swap_bench(B, W, torch, np, dev)
         extra["sched"] = sched_bench(B, W, np, res["ms_per_step"])
 
-    dominant_decode = rl["decode_ms"] + rl["merge_ms"] >= rl["prefill_ms"]
-    if dominant_decode:
-        roof = dict(bound="hbm", kernel="decode_kernel(+merge)", achieved=rl["decode_GBps"], peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=rl["decode_frac"], traffic=MEASURED_DECODE_TRAFFIC.get(args.workload))
+    # the dominant kernel is the attention launch; it is priced against the roof of whichever kind of
+    # work would take longer on its own
+    if rl["decode_alone_ms"] >= rl["prefill_alone_ms"]:
+        roof = dict(bound="hbm", kernel="attention_kernel", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=rl["attention_hbm_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get(args.workload))
     else:
-        roof = dict(bound="mfma", kernel="prefill_kernel", achieved=rl["prefill_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
-                    unit="TFLOP/s", frac=rl["prefill_frac"], traffic=None)
+        roof = dict(bound="mfma", kernel="attention_kernel", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=rl["attention_mfma_frac"], traffic=None)
     line = {
         "metric": "mixed-batch paged-attn tokens/s per layer", "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],

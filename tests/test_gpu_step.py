@@ -68,9 +68,9 @@ def test_split_k_partitions_and_merge(chunk):
     check_close(got, oracle_out(b, t, cache), False)
 
 
-def test_own_streams_fork_join_matches():
-    """cfg.own_streams: upload on the context's copy stream, prefill next to decode on its second stream;
-    several steps back to back on a non-default stream, each equal to the oracle."""
+def test_own_copy_stream_matches():
+    """cfg.own_streams: the batch description is uploaded on the context's copy stream; several steps
+    back to back on a non-default stream, each equal to the oracle."""
     b = W.make_workload(2, scale=0.08)
     t = W.make_tensors(b)
     cache = oracle_cache(b, t)
