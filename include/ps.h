@@ -149,6 +149,20 @@ int ps_step(ps_ctx* ctx, const ps_batch* batch, const void* q, const void* k_new
             const void* v_new, void* kv_cache, void* out, void* workspace,
             size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket);
 
+/* Host only, no device needed: the decode work list ps_step builds for the decode requests (l_q == 1)
+ * of `batch` when `waves` decode waves are available (ps_step itself uses four per compute unit for
+ * a decode-only batch and a share of that next to prefill work). The list: the requests'
+ * 32-token KV tiles, laid end to end in batch order, are cut into n_slots = min(waves / n_kv_heads,
+ * tiles / 16) slots of equal length (to within one tile); each (slot, kv-head) is walked by one wave.
+ * With cfg.decode_chunk > 0: fixed partitions of that many tokens, one per slot, longest first.
+ *   cfg     only n_kv_heads, n_device_blocks and decode_chunk are read
+ *   seg     HOST int32 [seg_cap][5], out: per segment, in launch order: request index, first token,
+ *           one past the last token, slot index, partials index (-1: the request's only segment)
+ *   n_seg, n_slots  out
+ * PS_EINVAL as for ps_step's batch checks; PS_ENOMEM if seg_cap is too small (*n_seg is set). */
+int ps_plan_decode(const ps_layer_cfg* cfg, const ps_batch* batch, int32_t waves, int32_t* seg,
+                   int32_t seg_cap, int32_t* n_seg, int32_t* n_slots);
+
 /* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds).
  * mode 0: off; 1: the phases as they run; 2: the decode and the prefill work of the attention
  * phase in launches of their own, one after the other. PS_EINVAL for any other mode. */

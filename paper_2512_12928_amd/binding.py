@@ -23,7 +23,7 @@ PS_BF16, PS_F32 = 0, 1
 
 EXPORTS = [
     "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_set_profiling",
-    "ps_get_step_times", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
+    "ps_get_step_times", "ps_plan_decode", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
     "ps_sched_create", "ps_sched_destroy", "ps_sched_add_request", "ps_form_batch", "ps_sched_counts",
 ]
 
@@ -188,6 +188,27 @@ def ps_step(ctx: int, batch, q, k_new, v_new, kv_cache, out, workspace, workspac
     _check(lib().ps_step(ctx, C.byref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_cache), _ptr(out),
                          _ptr(workspace), workspace_bytes, _stream(stream), wait_ticket))
     del keep
+
+
+def ps_plan_decode(n_kv_heads: int, n_device_blocks: int, batch, waves: int, decode_chunk: int = 0):
+    """Host only.  batch: as for ps_step.  Returns (segments int32 [n_seg, 5] = request, t0, t1, slot,
+    part; n_slots)."""
+    cfg = ps_layer_cfg()
+    cfg.n_kv_heads, cfg.n_device_blocks, cfg.decode_chunk = n_kv_heads, n_device_blocks, decode_chunk
+    keep = None
+    if isinstance(batch, tuple):
+        batch, keep = batch
+    elif not isinstance(batch, ps_batch):
+        batch, keep = make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, getattr(batch, "prio", None))
+    n_seg, n_slots = C.c_int32(), C.c_int32()
+    rc = lib().ps_plan_decode(C.byref(cfg), C.byref(batch), waves, None, 0, C.byref(n_seg), C.byref(n_slots))
+    if rc not in (PS_OK, PS_ENOMEM):
+        _check(rc)
+    seg = np.zeros((max(n_seg.value, 1), 5), dtype=np.int32)
+    _check(lib().ps_plan_decode(C.byref(cfg), C.byref(batch), waves, _i32p(seg), n_seg.value, C.byref(n_seg),
+                                C.byref(n_slots)))
+    del keep
+    return seg[:n_seg.value].copy(), n_slots.value
 
 
 def ps_set_profiling(ctx: int, mode) -> None:

@@ -48,6 +48,13 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
+// The decode work list of a step (and the merge items of the step: decode's first, prefill's appended).
+struct DecodePlan {
+  std::vector<ps::DecodeItem> ditems;
+  std::vector<int32_t> dslots;  // slot x owns ditems[dslots[x] .. dslots[x+1])
+  std::vector<ps::MergeItem> mitems;
+};
+
 struct ps_ctx {
   ps_layer_cfg cfg;
   int device = 0;
@@ -77,9 +84,7 @@ struct ps_ctx {
   hipEvent_t prof_ev[6];
   bool prof_valid = false;
   int prof_mode = 0;
-  std::vector<ps::DecodeItem> ditems;
-  std::vector<int32_t> dslots;  // slot x owns ditems[dslots[x] .. dslots[x+1])
-  std::vector<ps::MergeItem> mitems;
+  DecodePlan plan;
   std::vector<ps::PrefillTile> ptiles;
   std::vector<ps::AppendItem> aitems;
   std::vector<int32_t> seen;  // duplicate detection in swap lists
@@ -87,6 +92,32 @@ struct ps_ctx {
 };
 
 namespace {
+
+// The checks on a batch description that need no device: PS_EINVAL with a message, or PS_OK and the
+// number of cached tokens the decode requests read.  Arrays must be non-NULL and n_req > 0.
+int check_batch(const ps_batch* b, int M, int64_t* decode_kv_out) {
+  const int n_req = b->n_req;
+  if (b->q_start[0] != 0 || b->bt_start[0] != 0) return fail(PS_EINVAL, "q_start[0] and bt_start[0] must be 0");
+  int64_t decode_kv = 0;
+  for (int r = 0; r < n_req; ++r) {
+    const int64_t lq = (int64_t)b->q_start[r + 1] - b->q_start[r];
+    const int64_t L = b->kv_len[r];
+    if (lq < 1) return fail(PS_EINVAL, "request %d: l_q = %lld < 1", r, (long long)lq);
+    if (L < lq) return fail(PS_EINVAL, "request %d: l_q = %lld exceeds kv_len = %lld", r, (long long)lq, (long long)L);
+    const int64_t nb = (int64_t)b->bt_start[r + 1] - b->bt_start[r];
+    if (nb != (L + ps::kBlockTokens - 1) / ps::kBlockTokens)
+      return fail(PS_EINVAL, "request %d: block table has %lld entries, kv_len %lld needs %lld", r, (long long)nb,
+                  (long long)L, (long long)((L + ps::kBlockTokens - 1) / ps::kBlockTokens));
+    if (lq == 1) decode_kv += L;
+  }
+  if (b->q_start[n_req] != b->n_tokens) return fail(PS_EINVAL, "q_start[n_req] != n_tokens");
+  const int64_t n_table = b->bt_start[n_req];
+  for (int64_t i = 0; i < n_table; ++i)
+    if ((uint32_t)b->block_ids[i] >= (uint32_t)M)
+      return fail(PS_EINVAL, "block_ids[%lld] = %d outside [0, %d)", (long long)i, b->block_ids[i], M);
+  *decode_kv_out = decode_kv;
+  return PS_OK;
+}
 
 constexpr int kMinSlotTiles = 16;  // a balanced decode slot holds at least this many 32-token tiles
 
@@ -98,7 +129,9 @@ constexpr int kMinSlotTiles = 16;  // a balanced decode slot holds at least this
 //    once (cfg.decode_waves, default one per SIMD: measured best) and a slot is not shorter than
 //    kMinSlotTiles.  At most S - 1 requests are cut, so there are at most n_req + S segments.
 // A request with several segments gets one partials slot per segment and a merge item.
-void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& reqs, int& n_parts, int waves) {
+void build_decode_slots(DecodePlan* c, int n_kv_heads, int decode_chunk, const ps_batch* b, const std::vector<int>& reqs,
+                        int& n_parts, int waves) {
+  c->ditems.clear();
   c->dslots.clear();
   c->dslots.push_back(0);
   auto close_slot = [&]() {
@@ -108,8 +141,8 @@ void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& re
     const int L = b->kv_len[r];
     return ps::DecodeItem{b->bt_start[r], b->q_start[r], t0, t1, part, (L + ps::kBlockTokens - 1) / ps::kBlockTokens, {0, 0}};
   };
-  if (c->cfg.decode_chunk > 0) {
-    const int CH = c->cfg.decode_chunk;
+  if (decode_chunk > 0) {
+    const int CH = decode_chunk;
     for (int r : reqs) {
       const int L = b->kv_len[r], np = (L + CH - 1) / CH;
       if (np == 1) {
@@ -127,7 +160,7 @@ void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& re
   }
   int64_t T = 0;
   for (int r : reqs) T += (b->kv_len[r] + ps::kTileTokens - 1) / ps::kTileTokens;
-  const int64_t S = std::max<int64_t>(1, std::min<int64_t>(waves / c->cfg.n_kv_heads, T / kMinSlotTiles));
+  const int64_t S = std::max<int64_t>(1, std::min<int64_t>(waves / n_kv_heads, T / kMinSlotTiles));
   auto boundary = [&](int64_t x) { return ((x + 1) * T + S - 1) / S; };  // nominal end of slot x, in tiles
   int64_t off = 0, x = 0;
   std::vector<int> cuts;  // tile indices inside one request at which a slot ends
@@ -160,7 +193,7 @@ void build_decode_slots(ps_ctx* c, const ps_batch* b, const std::vector<int>& re
 // Host-side check of the decode work list before anything is launched from it: every slot a
 // non-empty range of items, every item inside its request, the segments of a request tiling
 // [0, kv_len) exactly.  A mistake here would otherwise become an out-of-bounds access on the GPU.
-bool decode_slots_ok(const ps_ctx* c, const ps_batch* b, const std::vector<int>& reqs, std::vector<int64_t>& cover) {
+bool decode_slots_ok(const DecodePlan* c, const ps_batch* b, const std::vector<int>& reqs, std::vector<int64_t>& cover) {
   const size_t n = c->ditems.size();
   if (c->dslots.empty() || c->dslots.front() != 0 || (size_t)c->dslots.back() != n) return false;
   for (size_t i = 1; i < c->dslots.size(); ++i)
@@ -339,6 +372,46 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
   return PS_OK;
 }
 
+int ps_plan_decode(const ps_layer_cfg* cfg, const ps_batch* b, int32_t waves, int32_t* seg, int32_t seg_cap,
+                   int32_t* n_seg, int32_t* n_slots) {
+  if (!cfg || !b || !n_seg || !n_slots || (!seg && seg_cap > 0)) return fail(PS_EINVAL, "ps_plan_decode: NULL argument");
+  if (cfg->n_kv_heads < 1 || cfg->n_device_blocks < 1 || waves < 1 || seg_cap < 0)
+    return fail(PS_EINVAL, "ps_plan_decode: bad n_kv_heads / n_device_blocks / waves / seg_cap");
+  if (cfg->decode_chunk != 0 && (cfg->decode_chunk < kMinChunk || cfg->decode_chunk > 65536 || cfg->decode_chunk % 32 != 0))
+    return fail(PS_EINVAL, "decode_chunk must be 0 or a multiple of 32 in [32, 65536]");
+  *n_seg = *n_slots = 0;
+  if (b->n_req < 0 || b->n_tokens < 0) return fail(PS_EINVAL, "negative n_req / n_tokens");
+  if (b->n_req == 0) return b->n_tokens == 0 ? PS_OK : fail(PS_EINVAL, "n_tokens != 0 with n_req == 0");
+  if (!b->q_start || !b->kv_len || !b->bt_start || !b->block_ids) return fail(PS_EINVAL, "ps_plan_decode: NULL batch array");
+  int64_t decode_kv = 0;
+  int rc = check_batch(b, cfg->n_device_blocks, &decode_kv);
+  if (rc != PS_OK) return rc;
+  std::vector<int> reqs;
+  for (int r = 0; r < b->n_req; ++r)
+    if (b->q_start[r + 1] - b->q_start[r] == 1) reqs.push_back(r);
+  DecodePlan plan;
+  int n_parts = 0;
+  std::vector<int64_t> cover;
+  build_decode_slots(&plan, cfg->n_kv_heads, cfg->decode_chunk, b, reqs, n_parts, waves);
+  if (!decode_slots_ok(&plan, b, reqs, cover)) return fail(PS_ESTATE, "ps_plan_decode: inconsistent decode work list (library bug)");
+  *n_seg = (int32_t)plan.ditems.size();
+  *n_slots = (int32_t)plan.dslots.size() - 1;
+  if (*n_seg > seg_cap) return fail(PS_ENOMEM, "ps_plan_decode: %d segments, room for %d", *n_seg, seg_cap);
+  std::vector<int> req_of((size_t)b->n_tokens, -1);
+  for (int r : reqs) req_of[(size_t)b->q_start[r]] = r;
+  for (int x = 0; x + 1 < (int)plan.dslots.size(); ++x)
+    for (int i = plan.dslots[x]; i < plan.dslots[x + 1]; ++i) {
+      const ps::DecodeItem& it = plan.ditems[(size_t)i];
+      int32_t* o = seg + (size_t)i * 5;
+      o[0] = req_of[(size_t)it.tok];
+      o[1] = it.t0;
+      o[2] = it.t1;
+      o[3] = x;
+      o[4] = it.part;
+    }
+  return PS_OK;
+}
+
 int ps_set_profiling(ps_ctx* c, int enabled) {
   if (!c) return fail(PS_EINVAL, "NULL ctx");
   if (enabled < 0 || enabled > 2) return fail(PS_EINVAL, "ps_set_profiling: mode must be 0, 1 or 2");
@@ -406,31 +479,18 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
 
   // ---- validation, O(batch description)
   const int n_req = b->n_req;
-  const int M = c->cfg.n_device_blocks;
-  if (b->q_start[0] != 0 || b->bt_start[0] != 0) return fail(PS_EINVAL, "q_start[0] and bt_start[0] must be 0");
   int64_t decode_kv = 0;
-  for (int r = 0; r < n_req; ++r) {
-    const int64_t lq = (int64_t)b->q_start[r + 1] - b->q_start[r];
-    const int64_t L = b->kv_len[r];
-    if (lq < 1) return fail(PS_EINVAL, "request %d: l_q = %lld < 1", r, (long long)lq);
-    if (L < lq) return fail(PS_EINVAL, "request %d: l_q = %lld exceeds kv_len = %lld", r, (long long)lq, (long long)L);
-    const int64_t nb = (int64_t)b->bt_start[r + 1] - b->bt_start[r];
-    if (nb != (L + ps::kBlockTokens - 1) / ps::kBlockTokens)
-      return fail(PS_EINVAL, "request %d: block table has %lld entries, kv_len %lld needs %lld", r, (long long)nb,
-                  (long long)L, (long long)((L + ps::kBlockTokens - 1) / ps::kBlockTokens));
-    if (lq == 1) decode_kv += L;
+  {
+    int rc = check_batch(b, c->cfg.n_device_blocks, &decode_kv);
+    if (rc != PS_OK) return rc;
   }
-  if (b->q_start[n_req] != b->n_tokens) return fail(PS_EINVAL, "q_start[n_req] != n_tokens");
   const int64_t n_table = b->bt_start[n_req];
-  for (int64_t i = 0; i < n_table; ++i)
-    if ((uint32_t)b->block_ids[i] >= (uint32_t)M)
-      return fail(PS_EINVAL, "block_ids[%lld] = %d outside [0, %d)", (long long)i, b->block_ids[i], M);
 
   // ---- work lists
   const int TT = ps::prefill_tile_tokens(c->G);
-  c->ditems.clear();
-  c->dslots.assign(1, 0);
-  c->mitems.clear();
+  c->plan.ditems.clear();
+  c->plan.dslots.assign(1, 0);
+  c->plan.mitems.clear();
   c->ptiles.clear();
   c->aitems.clear();
   int n_parts = 0;
@@ -538,7 +598,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
         q.k = k;
         cut.push_back(TileKey{q.tile_end - q.tile_begin, q});
       }
-      for (int row = 0; row < rows; ++row) c->mitems.push_back(ps::MergeItem{qs + t.t.q0 + row, n_parts + row * np, np, 0});
+      for (int row = 0; row < rows; ++row) c->plan.mitems.push_back(ps::MergeItem{qs + t.t.q0 + row, n_parts + row * np, np, 0});
       n_parts += rows * np;
     }
     tiles.swap(cut);
@@ -556,8 +616,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       cus = std::max(std::min(8, c->n_cus), std::min(cus, c->n_cus - 8));
       waves = ps::decode_waves_per_wg() * cus;
     }
-    build_decode_slots(c, b, decode_reqs, n_parts, waves);
-    if (!decode_slots_ok(c, b, decode_reqs, c->cover))
+    build_decode_slots(&c->plan, c->cfg.n_kv_heads, c->cfg.decode_chunk, b, decode_reqs, n_parts, waves);
+    if (!decode_slots_ok(&c->plan, b, decode_reqs, c->cover))
       return fail(PS_ESTATE, "ps_step: inconsistent decode work list (library bug)");
   }
 
@@ -565,8 +625,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
   for (auto& t : tiles) c->ptiles.push_back(t.t);
 
-  const MetaLayout ml = meta_layout(n_req, c->aitems.size(), n_table, c->ditems.size(), c->dslots.size(),
-                                     c->mitems.size(), c->ptiles.size());
+  const MetaLayout ml = meta_layout(n_req, c->aitems.size(), n_table, c->plan.ditems.size(), c->plan.dslots.size(),
+                                     c->plan.mitems.size(), c->ptiles.size());
   const size_t part_bytes = align_up((size_t)n_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256);
   if (part_bytes > workspace_bytes)
     return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", part_bytes, workspace_bytes);
@@ -582,9 +642,9 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   std::memcpy(h + ml.bt_start, b->bt_start, (size_t)(n_req + 1) * 4);
   std::memcpy(h + ml.block_ids, b->block_ids, (size_t)n_table * 4);
   if (!c->aitems.empty()) std::memcpy(h + ml.aitems, c->aitems.data(), c->aitems.size() * sizeof(ps::AppendItem));
-  if (!c->ditems.empty()) std::memcpy(h + ml.ditems, c->ditems.data(), c->ditems.size() * sizeof(ps::DecodeItem));
-  if (!c->dslots.empty()) std::memcpy(h + ml.dslots, c->dslots.data(), c->dslots.size() * 4);
-  if (!c->mitems.empty()) std::memcpy(h + ml.mitems, c->mitems.data(), c->mitems.size() * sizeof(ps::MergeItem));
+  if (!c->plan.ditems.empty()) std::memcpy(h + ml.ditems, c->plan.ditems.data(), c->plan.ditems.size() * sizeof(ps::DecodeItem));
+  if (!c->plan.dslots.empty()) std::memcpy(h + ml.dslots, c->plan.dslots.data(), c->plan.dslots.size() * 4);
+  if (!c->plan.mitems.empty()) std::memcpy(h + ml.mitems, c->plan.mitems.data(), c->plan.mitems.size() * sizeof(ps::MergeItem));
   if (!c->ptiles.empty()) std::memcpy(h + ml.ptiles, c->ptiles.data(), c->ptiles.size() * sizeof(ps::PrefillTile));
 
   // upload on the copy stream into the buffer that step n-2 used, once that step is done with it
@@ -652,7 +712,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   // Attention: one launch for the decode slots and the prefill tiles (decode streams the cache at
   // HBM speed and leaves the matrix pipes idle, prefill is the opposite: they run side by side on
   // disjoint CUs).  Profiling mode 2 gives each its own launch instead.
-  const int n_slots = (int)c->dslots.size() - 1;
+  const int n_slots = (int)c->plan.dslots.size() - 1;
   if (prof == 2) {
     PS_HIP(ps::launch_attention(P, n_slots, 0, stream));
     PS_HIP(hipEventRecord(c->prof_ev[3], stream));
@@ -665,7 +725,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       PS_HIP(hipEventRecord(c->prof_ev[4], stream));
     }
   }
-  PS_HIP(ps::launch_merge(P, 0, (int)c->mitems.size(), stream));
+  PS_HIP(ps::launch_merge(P, 0, (int)c->plan.mitems.size(), stream));
   if (prof) {
     PS_HIP(hipEventRecord(c->prof_ev[5], stream));
     c->prof_valid = true;
