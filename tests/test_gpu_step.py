@@ -68,6 +68,31 @@ def test_split_k_partitions_and_merge(chunk):
     check_close(got, oracle_out(b, t, cache), False)
 
 
+@pytest.mark.parametrize("waves", [8, 64, 1024, 4096])
+def test_balanced_decode_slots(waves):
+    """Decode-only batch, balanced slots: one wave walking every request (8 waves = one slot), a long
+    request cut into more than 8 partials (the merge kernel's second round), requests of one token."""
+    lens = [1, 3, 16, 17, 31, 32, 33, 64, 100, 257, 700, 1, 48, 9000, 2, 511, 1025]
+    b, t = custom_batch(16, 8, [(1, L) for L in lens], seed=99)
+    got, cache = run_prefilled(b, t, decode_waves=waves)
+    check_close(got, oracle_out(b, t, cache), False)
+    seg, n_slots = B.ps_plan_decode(8, b.n_device_blocks, b, waves)
+    assert n_slots == max(1, min(waves // 8, 380 // 16))
+    if waves >= 1024:
+        assert max(np.bincount(seg[:, 0])) > 8     # the 9000-token request has more than 8 segments
+
+
+def test_mixed_batch_decode_share_extremes():
+    """Mixed batches whose decode share of the chip clamps at either end: a sliver of decode work next
+    to a long prefill chunk, and a sliver of prefill next to heavy decode."""
+    b, t = custom_batch(8, 2, [(1, 40), (300, 2100), (1, 7)], seed=5)
+    got, cache = run_prefilled(b, t)
+    check_close(got, oracle_out(b, t, cache), False)
+    b, t = custom_batch(8, 2, [(1, 6000), (2, 2), (1, 5000), (1, 4000)], seed=6)
+    got, cache = run_prefilled(b, t)
+    check_close(got, oracle_out(b, t, cache), False)
+
+
 def test_own_copy_stream_matches():
     """cfg.own_streams: the batch description is uploaded on the context's copy stream; several steps
     back to back on a non-default stream, each equal to the oracle."""
