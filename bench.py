@@ -208,6 +208,7 @@ def main() -> int:
             del rr
             torch.cuda.empty_cache()
         extra["swap"] = swap_bench(B, W, torch, np, dev)
+        extra["reload_pipeline"] = reload_pipeline_bench(B, W, torch, np, dev)
         extra["sched"] = sched_bench(B, W, np, res["ms_per_step"])
 
     # the dominant kernel is the attention launch; it is priced against the roof of whichever kind of
@@ -328,6 +329,92 @@ def swap_bench(B, W, torch, np, dev):
     res["overlap_both_frac_of_bidir_link"] = res["overlap_both_each_way_GBps"] / res["link_bidir_each_way_GBps"]
     res["overlap_out_frac_of_link"] = res["overlap_out_GBps"] / res["link_d2h_GBps"]
     res["overlap_in_frac_of_link"] = res["overlap_in_GBps"] / res["link_h2d_GBps"]
+    B.ps_destroy(ctx)
+    return res
+
+
+def reload_pipeline_bench(B, W, torch, np, dev, n_layers=8):
+    """Pipelined reload across layers (Sec. 4.3, Appendix B) on workload 3: the blocks of the batch's longest
+    requests (512 blocks, 32 MiB per layer) are in pinned host memory when the forward pass over n_layers
+    attention layers starts.  Three ways to run the pass: reload layer by layer and wait (synchronous), reload
+    everything, then compute (full reload first), and the paper's pipeline: layer i+1's blocks are copied on a
+    side stream while layer i computes, each layer waiting only for its own ticket; the last also under a copy
+    budget sized so that a layer's copy takes no longer than its attention."""
+    import time as _t
+    batch = W.make_workload(3)
+    s = batch.shape
+    bb = s.block_bytes
+    order = np.argsort(-batch.kv_len[batch.decode_reqs])
+    ids = []
+    for r in batch.decode_reqs[order]:
+        ids.extend(batch.table(int(r)).tolist())
+        if len(ids) >= 512:
+            break
+    dev_ids = np.array(ids[:512], dtype=np.int32)
+    slots = np.random.default_rng(5).permutation(512).astype(np.int32)
+    g = torch.Generator(device=dev)
+    g.manual_seed(35)
+    pools = [torch.empty((batch.n_device_blocks, bb // 2), dtype=torch.bfloat16, device=dev).normal_(generator=g)
+             for _ in range(n_layers)]
+    hosts = []
+    for ell in range(n_layers):
+        h = torch.empty((512, bb), dtype=torch.uint8).pin_memory()
+        h.copy_(pools[ell].view(torch.uint8).view(batch.n_device_blocks, bb)[torch.from_numpy(dev_ids.astype(np.int64)).to(dev)][
+            torch.from_numpy(np.argsort(slots).astype(np.int64)).to(dev)].cpu())
+        hosts.append(h)
+    q = torch.randn((batch.n_tokens, s.n_q_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, 512)
+    nbytes = B.ps_workspace_bytes(ctx, batch.n_req, batch.n_tokens, len(batch.block_ids))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
+    compute, side = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def one_pass(mode, budget=-1):
+        if mode == "compute_only":
+            for ell in range(n_layers):
+                B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute)
+        elif mode == "synchronous":
+            for ell in range(n_layers):
+                _, tk = B.ps_swap_in(ctx, slots, dev_ids, budget, hosts[ell], pools[ell], side)
+                B.ps_ticket_wait(ctx, tk)
+                B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute)
+        elif mode == "full_reload_first":
+            tks = [B.ps_swap_in(ctx, slots, dev_ids, budget, hosts[ell], pools[ell], side)[1] for ell in range(n_layers)]
+            B.ps_ticket_wait(ctx, tks[-1])
+            for ell in range(n_layers):
+                B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute)
+        else:  # pipelined
+            tk = B.ps_swap_in(ctx, slots, dev_ids, budget, hosts[0], pools[0], side)[1]
+            for ell in range(n_layers):
+                nxt = B.ps_swap_in(ctx, slots, dev_ids, budget, hosts[ell + 1], pools[ell + 1], side)[1] if ell + 1 < n_layers else 0
+                B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute, tk)
+                tk = nxt
+
+    def timed(mode, budget=-1, reps=10):
+        one_pass(mode, budget)
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(3):
+            t0 = _t.perf_counter()
+            for _ in range(reps):
+                one_pass(mode, budget)
+            torch.cuda.synchronize()
+            ts.append((_t.perf_counter() - t0) / reps * 1e3)
+        return sorted(ts)[1]
+
+    res = dict(n_layers=n_layers, blocks_per_layer=512, MiB_per_layer=512 * bb / 2 ** 20)
+    res["compute_only_ms"] = timed("compute_only")
+    res["synchronous_ms"] = timed("synchronous")
+    res["full_reload_first_ms"] = timed("full_reload_first")
+    res["pipelined_ms"] = timed("pipelined")
+    # copy budget B_copy such that one layer's copy fits under one layer's attention (measured rates)
+    layer_ms = res["compute_only_ms"] / n_layers
+    copy_ms_per_block = (res["full_reload_first_ms"] - res["compute_only_ms"]) / n_layers / 512
+    fit = max(1, min(512, int(layer_ms / copy_ms_per_block)))
+    res["budget_blocks_that_fit"] = fit
+    res["pipelined_budgeted_ms"] = timed("pipelined", fit)
+    res["pipelined_budgeted_overhead_vs_compute_only"] = res["pipelined_budgeted_ms"] / res["compute_only_ms"] - 1.0
     B.ps_destroy(ctx)
     return res
 

@@ -1,0 +1,103 @@
+"""Pipelined reload across layers (Sec. 4.3, Appendix B): the blocks of preempted requests sit in a
+pinned host pool per layer; while layer i computes, layer i+1's blocks are copied back on a side
+stream, and each layer's attention waits, on the compute stream, only for its own copy's ticket.
+Every layer's output must equal the oracle's on that layer's K/V, whatever the order in which copies
+and kernels actually ran, and the copy budget must cut the reload list where the oracle says."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as A
+from oracle import blockcopy as C
+from paper_2512_12928_amd import binding as B
+from paper_2512_12928_amd import workloads as W
+from paper_2512_12928_amd.kvlayout import to_device_layout
+from gpu_harness import DEV, check_close, oracle_cache, u16_to_dev
+
+pytestmark = pytest.mark.gpu
+
+N_LAYERS = 4
+
+
+def build_layers(b, victims):
+    """Per layer: tensors, the oracle's expected output, a device pool in which the victims' blocks hold
+    NaN (they were evicted), and a pinned host pool that holds those blocks in shuffled slots."""
+    s = b.shape
+    vic_tab = np.concatenate([b.table(r) for r in victims]).astype(np.int32)
+    rng = np.random.default_rng(11)
+    Mh = len(vic_tab) + 5
+    layers = []
+    for ell in range(N_LAYERS):
+        t = W.make_tensors(b, seed=b.seed + 1000 * (ell + 1))
+        cache = oracle_cache(b, t)
+        want = A.paged_attention(t.q, cache, b.q_start, b.kv_len, b.bt_start, b.block_ids)
+        flat = to_device_layout(cache.pool)                      # [M, block elems] uint16
+        slots = rng.permutation(Mh)[:len(vic_tab)].astype(np.int32)
+        host_np = np.zeros((Mh, s.block_bytes), dtype=np.uint8)
+        host_np[slots] = flat[vic_tab].view(np.uint8).reshape(len(vic_tab), -1)
+        flat = flat.copy()
+        flat[vic_tab] = W.BF16_NAN                               # the device copies are gone
+        layers.append(dict(q=u16_to_dev(t.q), want=want, pool=u16_to_dev(flat), host=torch.from_numpy(host_np).pin_memory(),
+                           host_np=host_np, slots=slots))
+    return layers, vic_tab, Mh
+
+
+@pytest.mark.parametrize("mode", ["pipelined", "all_up_front"])
+def test_pipelined_reload_across_layers(mode):
+    b = W.make_workload(2, scale=0.08)
+    s = b.shape
+    victims = [int(r) for r in np.argsort(-b.kv_len)[:3]]        # the three longest requests were preempted
+    layers, vic_tab, Mh = build_layers(b, victims)
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, b.n_device_blocks, Mh, out_dtype=B.PS_F32)
+    nbytes = B.ps_workspace_bytes(ctx, b.n_req, b.n_tokens, len(b.block_ids))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    compute, side = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = [torch.full((b.n_tokens, s.n_q_heads, 128), float("nan"), dtype=torch.float32, device=DEV) for _ in layers]
+    torch.cuda.synchronize()
+
+    def reload(ell):
+        L = layers[ell]
+        n, tk = B.ps_swap_in(ctx, L["slots"], vic_tab, -1, L["host"], L["pool"], side)
+        assert n == len(vic_tab)
+        return tk
+
+    if mode == "pipelined":
+        tk = reload(0)
+        for ell, L in enumerate(layers):
+            nxt = reload(ell + 1) if ell + 1 < N_LAYERS else 0   # layer ell+1 loads while layer ell computes
+            B.ps_step(ctx, b, L["q"], None, None, L["pool"], outs[ell], ws, nbytes, compute, tk)
+            tk = nxt
+    else:
+        tks = [reload(ell) for ell in range(N_LAYERS)]
+        for ell, L in enumerate(layers):
+            B.ps_step(ctx, b, L["q"], None, None, L["pool"], outs[ell], ws, nbytes, compute, tks[ell])
+    torch.cuda.synchronize()
+    for ell, L in enumerate(layers):
+        check_close(outs[ell].cpu().numpy().astype(np.float64), L["want"], False)
+        assert np.array_equal(L["host"].numpy(), L["host_np"])   # a reload does not change the host pool
+    B.ps_destroy(ctx)
+
+
+def test_reload_budget_cuts_the_list_where_the_oracle_does():
+    """Under a copy budget the first B blocks of the list arrive and nothing else changes (Sec. 4.3:
+    the rest is recomputed by the caller); checked against the copy oracle on every layer."""
+    b = W.make_workload(2, scale=0.08)
+    s = b.shape
+    victims = [int(r) for r in np.argsort(-b.kv_len)[:2]]
+    layers, vic_tab, Mh = build_layers(b, victims)
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, b.n_device_blocks, Mh)
+    side = torch.cuda.Stream()
+    for ell, L in enumerate(layers):
+        budget = [0, 1, len(vic_tab) - 1, len(vic_tab) + 7][ell]
+        before = L["pool"].cpu().numpy().view(np.uint8).reshape(b.n_device_blocks, -1).copy()
+        n, tk = B.ps_swap_in(ctx, L["slots"], vic_tab, budget, L["host"], L["pool"], side)
+        if tk:
+            B.ps_ticket_wait(ctx, tk)
+        torch.cuda.synchronize()
+        m = C.n_moved(len(vic_tab), budget)
+        assert n == m
+        want = before.copy()
+        for k in range(m):
+            want[vic_tab[k]] = L["host_np"][L["slots"][k]]
+        assert np.array_equal(L["pool"].cpu().numpy().view(np.uint8).reshape(b.n_device_blocks, -1), want)
+    B.ps_destroy(ctx)
