@@ -1,0 +1,135 @@
+"""Batch latency estimator of Sec. 4.1 (Eqs. 4-7), fitted to measured ps_step times on this machine.
+
+    T(B) = sum over prefill requests (a_p l_q^2 + b_p l_q l_kv + c_p l_q)
+         + sum over decode requests  (a_d l_kv + b_d)  +  t_c
+
+is linear in (a_p, b_p, c_p, a_d, b_d, t_c), so the "training on offline profiling batches" the paper
+describes is a least-squares problem on six batch features.  `python -m paper_2512_12928_amd.estimator`
+draws seeded profiling batches, times ps_step on each (GPU needed), fits on one half and reports the mean
+absolute percentage error on the other (the paper reports about 4.5 % for its whole-model estimator; here
+only the attention layer is timed).  l_kv follows the scheduler's convention: cached prefix before this pass
+for a prefill request, context including this token for a decode request.
+"""
+from __future__ import annotations
+
+import json
+import sys
+import time
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+from . import workloads as W
+
+PARAMS = ("a_p", "b_p", "c_p", "a_d", "b_d", "t_c")
+
+
+def features(q_start: Sequence[int], kv_len: Sequence[int]) -> np.ndarray:
+    """The six sums that multiply (a_p, b_p, c_p, a_d, b_d, t_c) in Eq. 7."""
+    lq = np.diff(np.asarray(q_start, dtype=np.int64))
+    kv = np.asarray(kv_len, dtype=np.int64)
+    pre, dec = lq > 1, lq == 1
+    prefix = kv[pre] - lq[pre]
+    return np.array([float((lq[pre] ** 2).sum()), float((lq[pre] * prefix).sum()), float(lq[pre].sum()),
+                     float(kv[dec].sum()), float(dec.sum()), 1.0])
+
+
+def fit(X: np.ndarray, y: np.ndarray) -> np.ndarray:
+    """Least squares on relative error (each batch weighted by 1 / its time, the quantity MAPE measures),
+    columns scaled for conditioning."""
+    X = np.asarray(X, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    Xw = X / y[:, None]
+    scale = np.abs(Xw).max(axis=0)
+    scale[scale == 0] = 1.0
+    coef, *_ = np.linalg.lstsq(Xw / scale, np.ones_like(y), rcond=None)
+    return coef / scale
+
+
+def predict(coef: np.ndarray, X: np.ndarray) -> np.ndarray:
+    return np.asarray(X, dtype=np.float64) @ np.asarray(coef, dtype=np.float64)
+
+
+def mape(coef: np.ndarray, X: np.ndarray, y: np.ndarray) -> float:
+    y = np.asarray(y, dtype=np.float64)
+    return float(np.mean(np.abs(predict(coef, X) - y) / y))
+
+
+def profiling_batches(n: int, seed: int, shape: W.LayerShape, max_blocks: int) -> List[W.MixedBatch]:
+    """Seeded synthetic profiling batches: 0-512 decode requests with lognormal contexts, 0-4 prefill chunks
+    of 64-2048 tokens over prefixes of 0-8192 tokens, in random order; never empty."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        n_dec = int(rng.choice([0, 8, 32, 64, 128, 256, 384, 512]))
+        n_pre = int(rng.integers(0, 5))
+        if n_dec + n_pre == 0:
+            continue
+        mean = float(rng.choice([300, 800, 1500, 3000]))
+        items: List[Tuple[int, int]] = []
+        for _ in range(n_dec):
+            L = int(np.clip(rng.lognormal(np.log(mean) - 0.32, 0.8), 16, 16384))
+            items.append((1, L))
+        for _ in range(n_pre):
+            lq = int(rng.choice([64, 128, 256, 512, 1024, 2048]))
+            items.append((lq, lq + int(rng.choice([0, 256, 1024, 2048, 4096, 8192]))))
+        order = rng.permutation(len(items))
+        items = [items[i] for i in order]
+        need = sum(-(-L // shape.block_tokens) for _, L in items)
+        if need > max_blocks:
+            continue
+        out.append(W.build_batch(shape, items, [1] * len(items), rng, n_device_blocks=max_blocks, seed=seed))
+    return out
+
+
+def measure(batches: Sequence[W.MixedBatch], shape: W.LayerShape, n_blocks: int, steps: int = 20) -> np.ndarray:
+    """Wall time per ps_step in microseconds for each batch (inputs resident, cache already filled)."""
+    import torch
+    from . import binding as B
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+    pool = torch.empty((n_blocks, shape.block_bytes // 2), dtype=torch.bfloat16, device=dev).normal_(generator=g)
+    max_tok = max(b.n_tokens for b in batches)
+    q = torch.randn((max_tok, shape.n_q_heads, shape.head_dim), generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    ctx = B.ps_create(shape.n_q_heads, shape.n_kv_heads, n_blocks, 0)
+    nbytes = B.ps_workspace_bytes(ctx, max(b.n_req for b in batches), max_tok, max(len(b.block_ids) for b in batches))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    res = np.zeros(len(batches))
+    for i, b in enumerate(batches):
+        cb = B.make_batch(b.q_start, b.kv_len, b.bt_start, b.block_ids, b.prio)
+        for _ in range(3):
+            B.ps_step(ctx, cb, q, None, None, pool, out, ws, nbytes, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.ps_step(ctx, cb, q, None, None, pool, out, ws, nbytes, stream)
+        torch.cuda.synchronize()
+        res[i] = (time.perf_counter() - t0) / steps * 1e6
+    B.ps_destroy(ctx)
+    return res
+
+
+def main(argv=None) -> int:
+    n = int(argv[0]) if argv else 240
+    shape = W.LayerShape(32, 8)
+    n_blocks = 60_000
+    batches = profiling_batches(n, 2512_12928, shape, n_blocks)
+    y = measure(batches, shape, n_blocks)
+    X = np.stack([features(b.q_start, b.kv_len) for b in batches])
+    half = n // 2
+    coef = fit(X[:half], y[:half])
+    kinds = np.array([("mixed" if (x[2] > 0 and x[4] > 0) else ("prefill" if x[2] > 0 else "decode")) for x in X[half:]])
+    res = dict(n_train=half, n_eval=n - half, unit="us per ps_step (one attention layer, 32q/8kv)",
+               params={k: float(v) for k, v in zip(PARAMS, coef)},
+               mape_train=mape(coef, X[:half], y[:half]), mape_eval=mape(coef, X[half:], y[half:]),
+               mape_eval_by_kind={k: mape(coef, X[half:][kinds == k], y[half:][kinds == k]) for k in np.unique(kinds)},
+               step_us_range=[float(y.min()), float(y.max())])
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv[1:]))

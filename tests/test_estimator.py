@@ -1,0 +1,41 @@
+"""Latency-estimator fit (Sec. 4.1, Eqs. 4-7): the six batch features are pinned to the oracle's own
+T_pd(B), and the least-squares fit to planted coefficients."""
+import numpy as np
+
+from oracle import slidebatching as S
+from paper_2512_12928_amd import estimator as E
+from paper_2512_12928_amd import workloads as W
+from test_sched_parity import cfg_pair
+
+
+def test_features_reproduce_the_oracle_estimate():
+    oc, _ = cfg_pair()
+    coef = np.array([oc.a_p, oc.b_p, oc.c_p, oc.a_d, oc.b_d, oc.t_c], dtype=np.float64)
+    for b in E.profiling_batches(25, 3, W.LayerShape(8, 2), 40_000):
+        pre = [(b.l_q(int(r)), int(b.kv_len[r]) - b.l_q(int(r))) for r in b.prefill_reqs]
+        dec = [int(b.kv_len[r]) for r in b.decode_reqs]
+        want = S.t_batch_estimate(oc, pre, dec)
+        got = float(E.features(b.q_start, b.kv_len) @ coef)
+        assert abs(got - want) <= 1e-9 * want
+
+
+def test_fit_recovers_planted_coefficients():
+    batches = E.profiling_batches(80, 5, W.LayerShape(32, 8), 60_000)
+    X = np.stack([E.features(b.q_start, b.kv_len) for b in batches])
+    planted = np.array([3e-5, 4e-5, 2e-3, 6e-4, 0.05, 25.0])       # microseconds
+    y = X @ planted
+    coef = E.fit(X, y)
+    assert np.allclose(coef, planted, rtol=1e-6)
+    assert E.mape(coef, X, y) < 1e-9
+    # 5 % multiplicative noise: the error of the fit stays of that order
+    rng = np.random.default_rng(1)
+    yn = y * (1 + 0.05 * rng.standard_normal(len(y)))
+    assert E.mape(E.fit(X[:40], yn[:40]), X[40:], yn[40:]) < 0.08
+
+
+def test_profiling_batches_are_valid_and_seeded():
+    a = E.profiling_batches(10, 9, W.LayerShape(32, 8), 60_000)
+    b = E.profiling_batches(10, 9, W.LayerShape(32, 8), 60_000)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.kv_len, y.kv_len) and np.array_equal(x.block_ids, y.block_ids)
+        assert x.n_req >= 1 and len(set(x.block_ids.tolist())) == len(x.block_ids)
