@@ -93,6 +93,34 @@ def test_mixed_batch_decode_share_extremes():
     check_close(got, oracle_out(b, t, cache), False)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_mixed_batches(seed):
+    """Seeded random mixed batches (head shapes, request counts, lengths, chunk sizes and prefixes drawn at
+    random; odd seeds go through the append path) against the oracle, pool checked bit for bit after an append."""
+    rng = np.random.default_rng(4000 + seed)
+    Hq, Hkv = [(8, 2), (32, 8), (16, 1), (64, 8)][seed % 4]
+    items = [(1, int(rng.integers(1, 3000))) for _ in range(int(rng.integers(0, 40)))]
+    for _ in range(int(rng.integers(0 if items else 1, 4))):
+        lq = int(rng.integers(2, 300))
+        items.append((lq, lq + int(rng.integers(0, 1500))))
+    items = [items[i] for i in rng.permutation(len(items))]
+    b, t = custom_batch(Hq, Hkv, items, seed=4000 + seed)
+    full = oracle_cache(b, t)
+    want = oracle_out(b, t, full)
+    if seed % 2 == 0:
+        got, _ = run_prefilled(b, t)
+        check_close(got, want, False)
+    else:
+        pre = oracle_cache(b, t, upto_prefix=True)
+        cache_dev = u16_to_dev(to_device_layout(pre.pool))
+        k_new, v_new = t.new_rows(b)
+        lay = Layer(b)
+        out = lay.step(b, u16_to_dev(t.q), cache_dev, u16_to_dev(k_new), u16_to_dev(v_new))
+        lay.close()
+        check_close(out.cpu().numpy().astype(np.float64), want, False)
+        assert np.array_equal(from_device_layout(dev_to_u16(cache_dev), b.shape.n_kv_heads), full.pool)
+
+
 def test_own_copy_stream_matches():
     """cfg.own_streams: the batch description is uploaded on the context's copy stream; several steps
     back to back on a non-default stream, each equal to the oracle."""
