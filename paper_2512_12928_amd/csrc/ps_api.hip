@@ -526,6 +526,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     int64_t longest = 0;
     for (auto& t : tiles) longest = std::max(longest, t.reach);
     int64_t split = 0;  // partition length in KV tiles; 0 = none
+    bool priced = false;
     {  // default price of the prefill work, in KV tile steps per CU: an even spread
       int64_t total = 0;
       for (auto& t : tiles) total += t.reach;
@@ -570,7 +571,10 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
           split = k == 1 ? 0 : cand;
         }
       }
-      if (best > 0) prefill_steps = best;
+      if (best > 0) {
+        prefill_steps = best;
+        priced = true;
+      }
     }
     // partial slots: budget of two per batch token, and whatever the caller's workspace holds
     const size_t slot_bytes = (size_t)c->cfg.n_q_heads * ps::kPartStride * sizeof(float);
@@ -602,6 +606,16 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       n_parts += rows * np;
     }
     tiles.swap(cut);
+    if (!priced && !tiles.empty()) {  // forced partition length, or a launch too large to simulate: a bound instead
+      int64_t longest_part = 0, rows = 0;
+      for (auto& t : tiles) {
+        longest_part = std::max(longest_part, t.reach);
+        if (t.t.part >= 0 && t.t.k == 0)
+          rows += (int64_t)std::min(TT, b->q_start[t.t.req + 1] - b->q_start[t.t.req] - t.t.q0) * t.t.n_parts;
+      }
+      prefill_steps = std::max(prefill_steps, (double)longest_part) + (rows > 0 ? 4.0 : 0.0) +
+                      0.0047 * (c->cfg.n_q_heads / 32.0) * (double)rows;
+    }
   }
   // Decode slots.  With prefill work in the same launch the decode workgroups get the share of the
   // CUs that makes both kinds of work end together (each priced at its full-chip speed: 6.3 TB/s
