@@ -187,6 +187,16 @@ def test_ragged_and_degenerate_shapes():
     assert np.array_equal(got[0], np.repeat(v0, 4, axis=0))
 
 
+@pytest.mark.parametrize("split", [-1, 0])
+def test_very_long_contexts(split):
+    """A chunk over a 36 000-token prefix and a decode request of 70 000 tokens.  Unsplit, the chunk's KV
+    walk is one partition of more than 512 tiles, whose block ids do not fit the kernel's LDS table and are
+    read through the scalar cache instead; with the default split the partitions are short again."""
+    b, t = custom_batch(2, 1, [(40, 40 + 36_000), (1, 70_000), (1, 5)], seed=31)
+    got, cache = run_prefilled(b, t, prefill_split_tiles=split)
+    check_close(got, oracle_out(b, t, cache), False)
+
+
 def test_block_relabelling_is_bit_identical():
     b = W.make_workload(1)
     t = W.make_tensors(b)
