@@ -93,6 +93,117 @@ struct ps_ctx {
 
 namespace {
 
+// A prefill work item while the launch is being planned: `reach` = its length in 64-token KV tiles.
+struct TileKey {
+  int64_t reach;
+  ps::PrefillTile t;
+};
+
+// Prefill: a query tile walks `reach` KV tiles.  In a small launch the longest walks decide when
+// it ends; they can be cut into partitions whose partial results the merge kernel combines.
+// In:  tiles, one per query tile of every prefill chunk, with its full walk [0, reach).
+// Out: tiles replaced by the launch's work items (partitions of the walks, not yet ordered), merge
+//      items and partial slots for split rows appended; returns the price of the prefill work with the
+//      whole chip, in KV tile steps per CU.
+double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, int TT, size_t workspace_bytes, int& n_parts) {
+  double prefill_steps = 0;
+  const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
+  int64_t longest = 0;
+  for (auto& t : tiles) longest = std::max(longest, t.reach);
+  int64_t split = 0;  // partition length in KV tiles; 0 = none
+  bool priced = false;
+  {  // default price of the prefill work, in KV tile steps per CU: an even spread
+    int64_t total = 0;
+    for (auto& t : tiles) total += t.reach;
+    prefill_steps = (double)total * wg_per_tile / c->n_cus;
+  }
+  if (c->cfg.prefill_split_tiles > 0) {
+    split = c->cfg.prefill_split_tiles;
+  } else if (c->cfg.prefill_split_tiles == 0 && !tiles.empty()) {
+    // Candidates: the longest walk cut into k = 1..8 equal parts.  Each is priced in units of one
+    // KV tile step of a workgroup (measured on workload-sized launches): the time the launch
+    // ends when workgroups are handed, longest first, to whichever CU is free next, plus the merge
+    // (a kernel launch worth 4 steps, and 0.0047 steps per partial row of 32 heads).  Launches of
+    // more than 1024 workgroups balance well enough without a cut and are not priced.
+    std::vector<int64_t> sizes, bins;
+    double best = 0;
+    for (int k = 1; k <= 8; ++k) {
+      const int64_t cand = (longest + k - 1) / k;
+      if (k > 1 && cand < 8) break;
+      sizes.clear();
+      int64_t rows = 0;
+      for (auto& t : tiles) {
+        int np = k == 1 ? 1 : (int)std::min<int64_t>((t.reach + cand - 1) / cand, 8);
+        const int64_t len = (t.reach + np - 1) / np;
+        np = (int)((t.reach + len - 1) / len);
+        for (int q = 0; q < np; ++q) sizes.push_back(std::min<int64_t>((int64_t)(q + 1) * len, t.reach) - q * len);
+        if (np > 1) rows += (int64_t)std::min(TT, b->q_start[t.t.req + 1] - b->q_start[t.t.req] - t.t.q0) * np;
+      }
+      if (sizes.size() * (size_t)wg_per_tile > 1024) break;
+      std::sort(sizes.begin(), sizes.end(), std::greater<int64_t>());
+      bins.assign((size_t)c->n_cus, 0);  // min-heap of CU finish times
+      auto later = std::greater<int64_t>();
+      for (int64_t sz : sizes)
+        for (int w = 0; w < wg_per_tile; ++w) {
+          std::pop_heap(bins.begin(), bins.end(), later);
+          bins.back() += sz;
+          std::push_heap(bins.begin(), bins.end(), later);
+        }
+      const int64_t makespan = *std::max_element(bins.begin(), bins.end());
+      const double cost = (double)makespan + (rows > 0 ? 4.0 : 0.0) + 0.0047 * (c->cfg.n_q_heads / 32.0) * (double)rows;
+      if (k == 1 || cost < best) {
+        best = cost;
+        split = k == 1 ? 0 : cand;
+      }
+    }
+    if (best > 0) {
+      prefill_steps = best;
+      priced = true;
+    }
+  }
+  // partial slots: budget of two per batch token, and whatever the caller's workspace holds
+  const size_t slot_bytes = (size_t)c->cfg.n_q_heads * ps::kPartStride * sizeof(float);
+  int64_t budget = std::min<int64_t>(2 * (int64_t)b->n_tokens, (int64_t)(workspace_bytes / slot_bytes) - n_parts);
+  std::vector<TileKey> cut;
+  for (auto& t : tiles) {
+    const int qs = b->q_start[t.t.req], lq = b->q_start[t.t.req + 1] - qs;
+    const int rows = std::min(TT, lq - t.t.q0);
+    int np = split > 0 ? (int)std::min<int64_t>((t.reach + split - 1) / split, 8) : 1;
+    if (np > 1 && (int64_t)rows * np > budget) np = 1;
+    if (np == 1) {
+      t.t.tile_end = (int32_t)t.reach;
+      cut.push_back(t);
+      continue;
+    }
+    const int len = (int)((t.reach + np - 1) / np);
+    np = (int)((t.reach + len - 1) / len);  // no empty partition: every one starts inside the reach
+    budget -= (int64_t)rows * np;
+    for (int k = 0; k < np; ++k) {
+      ps::PrefillTile q = t.t;
+      q.tile_begin = k * len;
+      q.tile_end = (int32_t)std::min<int64_t>((int64_t)(k + 1) * len, t.reach);
+      q.part = n_parts;
+      q.n_parts = np;
+      q.k = k;
+      cut.push_back(TileKey{q.tile_end - q.tile_begin, q});
+    }
+    for (int row = 0; row < rows; ++row) c->plan.mitems.push_back(ps::MergeItem{qs + t.t.q0 + row, n_parts + row * np, np, 0});
+    n_parts += rows * np;
+  }
+  tiles.swap(cut);
+  if (!priced && !tiles.empty()) {  // forced partition length, or a launch too large to simulate: a bound instead
+    int64_t longest_part = 0, rows = 0;
+    for (auto& t : tiles) {
+      longest_part = std::max(longest_part, t.reach);
+      if (t.t.part >= 0 && t.t.k == 0)
+        rows += (int64_t)std::min(TT, b->q_start[t.t.req + 1] - b->q_start[t.t.req] - t.t.q0) * t.t.n_parts;
+    }
+    prefill_steps = std::max(prefill_steps, (double)longest_part) + (rows > 0 ? 4.0 : 0.0) +
+                    0.0047 * (c->cfg.n_q_heads / 32.0) * (double)rows;
+  }
+  return prefill_steps;
+}
+
 // The checks on a batch description that need no device: PS_EINVAL with a message, or PS_OK and the
 // number of cached tokens the decode requests read.  Arrays must be non-NULL and n_req > 0.
 int check_batch(const ps_batch* b, int M, int64_t* decode_kv_out) {
@@ -494,13 +605,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   c->ptiles.clear();
   c->aitems.clear();
   int n_parts = 0;
-  struct TileKey {
-    int64_t reach;
-    ps::PrefillTile t;
-  };
   std::vector<TileKey> tiles;
   std::vector<int> decode_reqs;
-  double prefill_steps = 0;  // price of the batch's prefill work on the whole chip, in KV tile steps
   for (int r = 0; r < n_req; ++r) {
     const int qs = b->q_start[r], lq = b->q_start[r + 1] - qs, L = b->kv_len[r];
     if (k_new)
@@ -519,104 +625,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
       }
     }
   }
-  // Prefill: a query tile walks `reach` KV tiles.  In a small launch the longest walks decide when
-  // it ends; they can be cut into partitions whose partial results the merge kernel combines.
-  {
-    const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
-    int64_t longest = 0;
-    for (auto& t : tiles) longest = std::max(longest, t.reach);
-    int64_t split = 0;  // partition length in KV tiles; 0 = none
-    bool priced = false;
-    {  // default price of the prefill work, in KV tile steps per CU: an even spread
-      int64_t total = 0;
-      for (auto& t : tiles) total += t.reach;
-      prefill_steps = (double)total * wg_per_tile / c->n_cus;
-    }
-    if (c->cfg.prefill_split_tiles > 0) {
-      split = c->cfg.prefill_split_tiles;
-    } else if (c->cfg.prefill_split_tiles == 0 && !tiles.empty()) {
-      // Candidates: the longest walk cut into k = 1..8 equal parts.  Each is priced in units of one
-      // KV tile step of a workgroup (measured on workload-sized launches): the time the launch
-      // ends when workgroups are handed, longest first, to whichever CU is free next, plus the merge
-      // (a kernel launch worth 4 steps, and 0.0047 steps per partial row of 32 heads).  Launches of
-      // more than 1024 workgroups balance well enough without a cut and are not priced.
-      std::vector<int64_t> sizes, bins;
-      double best = 0;
-      for (int k = 1; k <= 8; ++k) {
-        const int64_t cand = (longest + k - 1) / k;
-        if (k > 1 && cand < 8) break;
-        sizes.clear();
-        int64_t rows = 0;
-        for (auto& t : tiles) {
-          int np = k == 1 ? 1 : (int)std::min<int64_t>((t.reach + cand - 1) / cand, 8);
-          const int64_t len = (t.reach + np - 1) / np;
-          np = (int)((t.reach + len - 1) / len);
-          for (int q = 0; q < np; ++q) sizes.push_back(std::min<int64_t>((int64_t)(q + 1) * len, t.reach) - q * len);
-          if (np > 1) rows += (int64_t)std::min(TT, b->q_start[t.t.req + 1] - b->q_start[t.t.req] - t.t.q0) * np;
-        }
-        if (sizes.size() * (size_t)wg_per_tile > 1024) break;
-        std::sort(sizes.begin(), sizes.end(), std::greater<int64_t>());
-        bins.assign((size_t)c->n_cus, 0);  // min-heap of CU finish times
-        auto later = std::greater<int64_t>();
-        for (int64_t sz : sizes)
-          for (int w = 0; w < wg_per_tile; ++w) {
-            std::pop_heap(bins.begin(), bins.end(), later);
-            bins.back() += sz;
-            std::push_heap(bins.begin(), bins.end(), later);
-          }
-        const int64_t makespan = *std::max_element(bins.begin(), bins.end());
-        const double cost = (double)makespan + (rows > 0 ? 4.0 : 0.0) + 0.0047 * (c->cfg.n_q_heads / 32.0) * (double)rows;
-        if (k == 1 || cost < best) {
-          best = cost;
-          split = k == 1 ? 0 : cand;
-        }
-      }
-      if (best > 0) {
-        prefill_steps = best;
-        priced = true;
-      }
-    }
-    // partial slots: budget of two per batch token, and whatever the caller's workspace holds
-    const size_t slot_bytes = (size_t)c->cfg.n_q_heads * ps::kPartStride * sizeof(float);
-    int64_t budget = std::min<int64_t>(2 * (int64_t)b->n_tokens, (int64_t)(workspace_bytes / slot_bytes) - n_parts);
-    std::vector<TileKey> cut;
-    for (auto& t : tiles) {
-      const int qs = b->q_start[t.t.req], lq = b->q_start[t.t.req + 1] - qs;
-      const int rows = std::min(TT, lq - t.t.q0);
-      int np = split > 0 ? (int)std::min<int64_t>((t.reach + split - 1) / split, 8) : 1;
-      if (np > 1 && (int64_t)rows * np > budget) np = 1;
-      if (np == 1) {
-        t.t.tile_end = (int32_t)t.reach;
-        cut.push_back(t);
-        continue;
-      }
-      const int len = (int)((t.reach + np - 1) / np);
-      np = (int)((t.reach + len - 1) / len);  // no empty partition: every one starts inside the reach
-      budget -= (int64_t)rows * np;
-      for (int k = 0; k < np; ++k) {
-        ps::PrefillTile q = t.t;
-        q.tile_begin = k * len;
-        q.tile_end = (int32_t)std::min<int64_t>((int64_t)(k + 1) * len, t.reach);
-        q.part = n_parts;
-        q.n_parts = np;
-        q.k = k;
-        cut.push_back(TileKey{q.tile_end - q.tile_begin, q});
-      }
-      for (int row = 0; row < rows; ++row) c->plan.mitems.push_back(ps::MergeItem{qs + t.t.q0 + row, n_parts + row * np, np, 0});
-      n_parts += rows * np;
-    }
-    tiles.swap(cut);
-    if (!priced && !tiles.empty()) {  // forced partition length, or a launch too large to simulate: a bound instead
-      int64_t longest_part = 0, rows = 0;
-      for (auto& t : tiles) {
-        longest_part = std::max(longest_part, t.reach);
-        if (t.t.part >= 0 && t.t.k == 0)
-          rows += (int64_t)std::min(TT, b->q_start[t.t.req + 1] - b->q_start[t.t.req] - t.t.q0) * t.t.n_parts;
-      }
-      prefill_steps = std::max(prefill_steps, (double)longest_part) + (rows > 0 ? 4.0 : 0.0) +
-                      0.0047 * (c->cfg.n_q_heads / 32.0) * (double)rows;
-    }
-  }
+  const double prefill_steps = plan_prefill(c, b, tiles, TT, workspace_bytes, n_parts);
+
   // Decode slots.  With prefill work in the same launch the decode workgroups get the share of the
   // CUs that makes both kinds of work end together (each priced at its full-chip speed: 6.3 TB/s
   // for the cache stream, 1.92 us per KV tile step of a prefill workgroup; the decode share is cut
