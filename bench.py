@@ -5,7 +5,8 @@ A step is one pass of the hot path over one synthetic mixed batch (ps_step): hos
 description -> device and KV append (one launch), split-K decode attention and prefill-chunk
 attention side by side (one launch), merge of the split-K partials (one launch).  The
 headline workload is the Qwen3-8B-shaped layer (256 decode requests + 2048 prefill tokens in 4
-chunks).  Prints ONE JSON line; see the design doc for the fields.
+chunks).  Prints ONE JSON line: metric, value, unit, timing fields, a roofline object for the attention launch and
+the oracle's speed on the same batch as cpu_baseline.
 """
 from __future__ import annotations
 
