@@ -424,11 +424,9 @@ __global__ __launch_bounds__(256) void merge_kernel(StepParams P, int first) {
 // with its own L2), so the kv-head is taken from the low bits of the id: the workgroups that
 // share one XCD's L2 then walk the same K/V stream.
 constexpr int kPrefillWaves = 8;
-constexpr int kPrefillRB = 2;       // 32-row query blocks per wave
-constexpr int kPrefillRows = 32 * kPrefillRB;  // query tokens per wave
+constexpr int kPrefillRows = 32;    // query tokens per wave
 constexpr int kPrefillKV = 64;      // KV tokens per pipeline step
-constexpr int kStages = kPrefillRB == 1 ? 4 : 3;
-constexpr int kQLds = kPrefillRB == 1 ? 0 : 2;  // dim chunks of the Q operand a wave keeps in LDS instead of registers
+constexpr int kStages = 4;
 constexpr int kLoadsPerTile = 4;
 constexpr int kIdTiles = 512;       // block ids of up to this many KV tiles (32k tokens) are kept in LDS    // global->LDS loads each wave issues per tile
 
@@ -465,15 +463,6 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
-// The lane id, recomputed where it is used: the compiler cannot hoist or merge the asm, so values
-// derived from it inside the prefill loop do not occupy registers across the loop's arithmetic
-// (which needs all 256 of them).
-__device__ __forceinline__ int fresh_lane() {
-  int x;
-  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(x));
-  return x;
-}
-
 struct PrefillHalf {
   uint4 k[8][64];
   uint4 v[8][64];
@@ -483,8 +472,7 @@ struct PrefillStage {
 };
 
 // bid: index of the prefill workgroup in the launch; sm: the LDS ring of kStages tiles; id_lds: kIdTiles * 4 ints.
-__device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int HW, int n_zsplit, PrefillStage* sm, int* id_lds,
-                                             uint4* q_lds) {
+__device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int HW, int n_zsplit, PrefillStage* sm, int* id_lds) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int j = lane & 31;   // row of the K operand / query column of Q, P, O
@@ -506,32 +494,21 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
   const int nblk = (L + kBlockTokens - 1) >> 4;
 
   // Q^T operand: lane (query j, k-group h2) holds dims (c*2+h2)*8 .. +7 for chunk c.
-  constexpr int RB = kPrefillRB;
-  constexpr int QR = 8 - kQLds;  // chunks kept in registers; chunk c >= QR of row block rb sits in qw[(c - QR) * RB + rb]
-  bf16x8 qop[RB][QR];
-  uint4* qw = q_lds + (size_t)wave * (kQLds * RB * 64);
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    int row = q0 + 32 * rb + j;
+  bf16x8 qop[8];
+  {
+    int row = q0 + j;
     row = row < lq ? row : lq - 1;
     const uint16_t* qrow = P.q + ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
 #pragma unroll
-    for (int c = 0; c < QR; ++c) qop[rb][c] = as_bf16x8(*(const uint4*)(qrow + (c * 2 + h2) * 8));
-#pragma unroll
-    for (int c = QR; c < 8; ++c) qw[((c - QR) * RB + rb) * 64 + lane] = *(const uint4*)(qrow + (c * 2 + h2) * 8);
+    for (int c = 0; c < 8; ++c) qop[c] = as_bf16x8(*(const uint4*)(qrow + (c * 2 + h2) * 8));
   }
 
-  float m[RB], l[RB];
-  f32x16 acc[RB][4];
+  float m = PS_NEG_INF, l = 0.f;
+  f32x16 acc[4];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    m[rb] = PS_NEG_INF;
-    l[rb] = 0.f;
+  for (int n = 0; n < 4; ++n)
 #pragma unroll
-    for (int n = 0; n < 4; ++n)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[rb][n][e] = 0.f;
-  }
+    for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
 
   const int wg_last = (t.q0 + SUB * kPrefillRows < lq ? t.q0 + SUB * kPrefillRows : lq) - 1;
   const int reach = (p + wg_last) / kPrefillKV + 1;  // KV tiles any query of the workgroup can see
@@ -543,7 +520,7 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
   const int qpos = p + q0 + j;
 
   // K row j of a fragment is token pi(j) of its half: block j>>4, slot 8*bit2(j) + 4*bit3(j) + (j&3)
-  // (computed inside issue())
+  const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
   const uint32_t sm_base = (uint32_t)(uintptr_t)(&sm[0]);  // LDS byte address of the ring
 
   // Block ids of the i-th tile of the partition (clamped to its last tile; absent blocks repeat the
@@ -568,9 +545,7 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
   // V fragment `wave` (block wave/4, dims 32*(wave%4)..) of each half.  Every call issues exactly
   // kLoadsPerTile loads (past the end the last tile is fetched again): the vmcnt bookkeeping
   // below counts on it.
-  auto issue = [&](int stage, const int4& idv, int ln) {
-    const int j = ln & 31, h2 = ln >> 5;
-    const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
+  auto issue = [&](int stage, const int4& idv) {
     const int id[4] = {__builtin_amdgcn_readfirstlane(idv.x), __builtin_amdgcn_readfirstlane(idv.y),
                        __builtin_amdgcn_readfirstlane(idv.z), __builtin_amdgcn_readfirstlane(idv.w)};
     const uint32_t st = sm_base + (uint32_t)stage * (uint32_t)sizeof(PrefillStage);
@@ -605,7 +580,7 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
 #pragma unroll
   for (int i = 0; i < kStages - 1; ++i) {
     lookup(i, id);
-    issue(i, id, lane);
+    issue(i, id);
   }
   lookup(kStages - 1, id);  // ids of the tile the first iteration will issue
 
@@ -617,243 +592,137 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();  // ... and so have everybody's; everyone is done with tile-1
     asm volatile("" ::: "memory");
-    issue((it + kStages - 1) % kStages, id, fresh_lane());  // tile it + kStages-1 refills the slot of tile it-1
-    if constexpr (RB == 1) lookup(it + kStages, id);  // ids for the next iteration's issue
+    issue((it + kStages - 1) % kStages, id);  // tile it + kStages-1 refills the slot of tile it-1
+    lookup(it + kStages, id);                  // ids for the next iteration's issue
 
     if (ts + kPrefillKV > L) {
       // Last tile of the request: slots past kv_len may hold anything.  The wave that fetched a V
       // fragment zeroes those slots in LDS before anyone multiplies by them (0 * NaN is NaN).
       const int f = wave, u = f >> 2;
-      const int ln = fresh_lane();
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
-        const int first = ts + 32 * hf + 16 * u + 8 * (ln >> 5);
-        const uint4 vv = sm[stage].h[hf].v[f][ln];
+        const int first = ts + 32 * hf + 16 * u + 8 * h2;
+        const uint4 vv = sm[stage].h[hf].v[f][lane];
         const uint2 lo = zero_from(make_uint2(vv.x, vv.y), first, L);
         const uint2 hi = zero_from(make_uint2(vv.z, vv.w), first + 4, L);
-        sm[stage].h[hf].v[f][ln] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        sm[stage].h[hf].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
       }
       __syncthreads();  // workgroup-uniform branch
     }
 
     if (active && ts <= my_last) {
       const PrefillStage& S = sm[stage];
-      if constexpr (RB == 1) {
-        // all 16 K fragments of the tile are requested from LDS before the first MFMA needs one,
-        // and the 16 V fragments right behind them, so that LDS latency is paid once per tile, not
-        // once per MFMA (left alone, the compiler sinks every ds_read next to its MFMA)
-        bf16x8 kf[2][8], vf[2][8];
-  #pragma unroll
+      // all 16 K fragments of the tile are requested from LDS before the first MFMA needs one,
+      // and the 16 V fragments right behind them, so that LDS latency is paid once per tile, not
+      // once per MFMA (left alone, the compiler sinks every ds_read next to its MFMA)
+      bf16x8 kf[2][8], vf[2][8];
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) kf[hf][c] = as_bf16x8(S.h[hf].k[c][lane]);
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 s[2];
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[hf][e] = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+          s[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[hf][c], qop[c], s[hf], 0, 0, 0);
+      }
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int f = 0; f < 8; ++f) vf[hf][f] = as_bf16x8(S.h[hf].v[f][lane]);
+      __builtin_amdgcn_sched_barrier(0);
+      // s[hf][e]: token ts + 32*hf + 16*(e/8) + 8*h2 + e%8, query q0 + j (raw dot products)
+      if (ts + kPrefillKV - 1 > p + q0) {  // diagonal tile (wave-uniform test)
+#pragma unroll
         for (int hf = 0; hf < 2; ++hf)
-  #pragma unroll
-          for (int c = 0; c < 8; ++c) kf[hf][c] = as_bf16x8(S.h[hf].k[c][lane]);
-        __builtin_amdgcn_sched_barrier(0);
-        f32x16 s[2];
-  #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-  #pragma unroll
-          for (int e = 0; e < 16; ++e) s[hf][e] = 0.f;
-  #pragma unroll
-          for (int c = 0; c < 8; ++c)
-            s[hf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[hf][c], qop[0][c], s[hf], 0, 0, 0);
-        }
-  #pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
-  #pragma unroll
-          for (int f = 0; f < 8; ++f) vf[hf][f] = as_bf16x8(S.h[hf].v[f][lane]);
-        __builtin_amdgcn_sched_barrier(0);
-        // s[hf][e]: token ts + 32*hf + 16*(e/8) + 8*h2 + e%8, query q0 + j (raw dot products)
-        if (ts + kPrefillKV - 1 > p + q0) {  // diagonal tile (wave-uniform test)
-  #pragma unroll
-          for (int hf = 0; hf < 2; ++hf)
-  #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int tok = ts + 32 * hf + 16 * (e >> 3) + 8 * h2 + (e & 7);
-              if (tok > qpos) s[hf][e] = PS_NEG_INF;
-            }
-        }
-        // max3 is inline asm, so the compiler does not count the wait states the ISA requires between an
-        // MFMA and a VALU read of its result (11 for these 8-pass MFMAs); the 16 V-fragment reads above
-        // already separate them, the NOPs make it independent of instruction scheduling
-        asm volatile("s_nop 7\n\ts_nop 3" ::: "memory");
-        float tmax = max3(s[0][0], s[0][1], s[1][0]);
-  #pragma unroll
-        for (int e = 2; e < 16; e += 2) tmax = max3(tmax, s[0][e], s[0][e + 1]);
-  #pragma unroll
-        for (int e = 1; e < 15; e += 2) tmax = max3(tmax, s[1][e], s[1][e + 1]);
-        tmax = fmaxf(tmax, s[1][15]);
-        tmax = xor32_max(tmax) * P.scale_log2;
-        // a row that sees nothing in this tile keeps its m; a row that has seen nothing yet in this
-        // partition has m = -inf, l = 0 and all-zero accumulators
-        if (__builtin_amdgcn_ballot_w64(tmax > m[0]) != 0) {  // rescale only when some row's max grew
-          const float m_new = fmaxf(m[0], tmax);
-          const float alpha = m_new == PS_NEG_INF ? 1.f : __builtin_amdgcn_exp2f(m[0] - m_new);
-          l[0] *= alpha;
-          m[0] = m_new;
-  #pragma unroll
-          for (int n = 0; n < 4; ++n) acc[0][n] *= alpha;
-        }
-        const float m_use = m[0] == PS_NEG_INF ? 0.f : m[0];  // all scores of such a row are -inf: exp2 gives 0
-  #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          float psum = 0.f;
-  #pragma unroll
+#pragma unroll
           for (int e = 0; e < 16; ++e) {
-            s[hf][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[hf][e], P.scale_log2, -m_use));
-            psum += s[hf][e];
+            const int tok = ts + 32 * hf + 16 * (e >> 3) + 8 * h2 + (e & 7);
+            if (tok > qpos) s[hf][e] = PS_NEG_INF;
           }
-          l[0] += psum;
-  #pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            uint4 pv = {pack_bf16x2(s[hf][8 * u + 0], s[hf][8 * u + 1]), pack_bf16x2(s[hf][8 * u + 2], s[hf][8 * u + 3]),
-                        pack_bf16x2(s[hf][8 * u + 4], s[hf][8 * u + 5]), pack_bf16x2(s[hf][8 * u + 6], s[hf][8 * u + 7])};
-            const bf16x8 pop = as_bf16x8(pv);
-  #pragma unroll
-            for (int n = 0; n < 4; ++n)
-              acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][u * 4 + n], pop, acc[0][n], 0, 0, 0);
-          }
+      }
+      // max3 is inline asm, so the compiler does not count the wait states the ISA requires between an
+      // MFMA and a VALU read of its result (11 for these 8-pass MFMAs); the 16 V-fragment reads above
+      // already separate them, the NOPs make it independent of instruction scheduling
+      asm volatile("s_nop 7\n\ts_nop 3" ::: "memory");
+      float tmax = max3(s[0][0], s[0][1], s[1][0]);
+#pragma unroll
+      for (int e = 2; e < 16; e += 2) tmax = max3(tmax, s[0][e], s[0][e + 1]);
+#pragma unroll
+      for (int e = 1; e < 15; e += 2) tmax = max3(tmax, s[1][e], s[1][e + 1]);
+      tmax = fmaxf(tmax, s[1][15]);
+      tmax = xor32_max(tmax) * P.scale_log2;
+      // a row that sees nothing in this tile keeps its m; a row that has seen nothing yet in this
+      // partition has m = -inf, l = 0 and all-zero accumulators
+      if (__builtin_amdgcn_ballot_w64(tmax > m) != 0) {  // rescale only when some row's max grew
+        const float m_new = fmaxf(m, tmax);
+        const float alpha = m_new == PS_NEG_INF ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
+        l *= alpha;
+        m = m_new;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) acc[n] *= alpha;
+      }
+      const float m_use = m == PS_NEG_INF ? 0.f : m;  // all scores of such a row are -inf: exp2 gives 0
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          s[hf][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[hf][e], P.scale_log2, -m_use));
+          psum += s[hf][e];
         }
-      } else {
-        // 64 rows per wave: every K and V fragment read from LDS feeds two MFMAs (one per 32-row
-        // block), which halves the LDS traffic per MFMA.  The register budget (128 accumulators +
-        // 64 for the Q operand) leaves room for one half tile's scores and four fragments in
-        // flight, so the halves are taken one after the other and the fragments stream through a
-        // ring of four registers, each refilled right behind the MFMAs that consumed it.
+        l += psum;
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          if (ts + 32 * hf <= my_last) {  // wave-uniform
-            const PrefillHalf& H = S.h[hf];
-            const int lane = fresh_lane();  // shadows the function's: see fresh_lane()
-            // Fragment stream of a half: K6, K7 and the four Q fragments that live in LDS first (the
-            // score registers are not in use yet), then K0..K5 and V0..V7 through a ring of NF.
-            constexpr int NF = 3;
-            const uint4* qf = qw + lane;
-            const bf16x8 k6 = as_bf16x8(H.k[6][lane]), q06 = as_bf16x8(qf[0]), q16 = as_bf16x8(qf[64]);
-            const bf16x8 k7 = as_bf16x8(H.k[7][lane]), q07 = as_bf16x8(qf[128]), q17 = as_bf16x8(qf[192]);
-            __builtin_amdgcn_sched_barrier(0);
-            f32x16 sc[RB];
+        for (int u = 0; u < 2; ++u) {
+          uint4 pv = {pack_bf16x2(s[hf][8 * u + 0], s[hf][8 * u + 1]), pack_bf16x2(s[hf][8 * u + 2], s[hf][8 * u + 3]),
+                      pack_bf16x2(s[hf][8 * u + 4], s[hf][8 * u + 5]), pack_bf16x2(s[hf][8 * u + 6], s[hf][8 * u + 7])};
+          const bf16x8 pop = as_bf16x8(pv);
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-              for (int e = 0; e < 16; ++e) sc[rb][e] = 0.f;
-            bf16x8 fr[NF];
-            sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k6, q06, sc[0], 0, 0, 0);
-            sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k6, q16, sc[1], 0, 0, 0);
-            fr[0] = as_bf16x8(H.k[0][lane]);
-            __builtin_amdgcn_sched_barrier(0);
-            sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k7, q07, sc[0], 0, 0, 0);
-            sc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k7, q17, sc[1], 0, 0, 0);
-            fr[1] = as_bf16x8(H.k[1][lane]);
-            fr[2] = as_bf16x8(H.k[2][lane]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int c = 0; c < QR; ++c) {
-#pragma unroll
-              for (int rb = 0; rb < RB; ++rb)
-                sc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[c % NF], qop[rb][c], sc[rb], 0, 0, 0);
-              fr[c % NF] = as_bf16x8(c + NF < QR ? H.k[c + NF][lane] : H.v[c + NF - QR][lane]);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-            // sc[rb][e]: token ts + 32*hf + 16*(e/8) + 8*h2 + e%8, query q0 + 32*rb + j
-            bf16x8 pop[RB][2];
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-              if (ts + 32 * hf + 31 > p + q0 + 32 * rb) {  // diagonal (wave-uniform test)
-                // element e is the token `16 * (e / 8) + e % 8` past the lane's first; d = how many
-                // tokens past that first one the lane's query can see (one register, compared with
-                // constants: sixteen precomputed token numbers would not fit next to the rest)
-                int d = p + q0 + 32 * rb + (lane & 31) - (ts + 32 * hf + 8 * (lane >> 5));
-                asm volatile("" : "+v"(d));
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                  if (16 * (e >> 3) + (e & 7) > d) sc[rb][e] = PS_NEG_INF;
-              }
-              asm volatile("s_nop 7\n\ts_nop 3" ::: "memory");  // MFMA result -> asm VALU read, see above
-              float tmax = max3(sc[rb][0], sc[rb][1], sc[rb][2]);
-#pragma unroll
-              for (int e = 3; e < 15; e += 2) tmax = max3(tmax, sc[rb][e], sc[rb][e + 1]);
-              tmax = fmaxf(tmax, sc[rb][15]);
-              tmax = xor32_max(tmax) * P.scale_log2;
-              if (__builtin_amdgcn_ballot_w64(tmax > m[rb]) != 0) {
-                const float m_new = fmaxf(m[rb], tmax);
-                const float alpha = m_new == PS_NEG_INF ? 1.f : __builtin_amdgcn_exp2f(m[rb] - m_new);
-                l[rb] *= alpha;
-                m[rb] = m_new;
-#pragma unroll
-                for (int n = 0; n < 4; ++n) acc[rb][n] *= alpha;
-              }
-              const float m_use = m[rb] == PS_NEG_INF ? 0.f : m[rb];
-              float psum = 0.f;
-#pragma unroll
-              for (int e = 0; e < 16; ++e) {
-                sc[rb][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[rb][e], P.scale_log2, -m_use));
-                psum += sc[rb][e];
-              }
-              l[rb] += psum;
-#pragma unroll
-              for (int u = 0; u < 2; ++u) {
-                uint4 pv = {pack_bf16x2(sc[rb][8 * u + 0], sc[rb][8 * u + 1]), pack_bf16x2(sc[rb][8 * u + 2], sc[rb][8 * u + 3]),
-                            pack_bf16x2(sc[rb][8 * u + 4], sc[rb][8 * u + 5]), pack_bf16x2(sc[rb][8 * u + 6], sc[rb][8 * u + 7])};
-                pop[rb][u] = as_bf16x8(pv);
-              }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int f = 0; f < 8; ++f) {  // V fragment f: block u = f / 4, dims 32 * (f % 4) ..
-#pragma unroll
-              for (int rb = 0; rb < RB; ++rb)
-                acc[rb][f % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[(QR + f) % NF], pop[rb][f / 4], acc[rb][f % 4], 0, 0, 0);
-              if (f + NF < 8) fr[(QR + f) % NF] = as_bf16x8(H.v[f + NF][lane]);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          }
+          for (int n = 0; n < 4; ++n)
+            acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][u * 4 + n], pop, acc[n], 0, 0, 0);
         }
       }
     }
-    // with two row blocks the registers are full during the arithmetic: the ids are requested here,
-    // behind it, and arrive while the wave waits at the next barrier
-    if constexpr (RB > 1) lookup(it + kStages, id);
   }
   __builtin_amdgcn_s_waitcnt(PS_VMCNT(0));  // no load may still be writing LDS when the wave ends
 
   if (!active) return;
-  const int lane_e = fresh_lane();
+  const float ls = l + __shfl_xor(l, 32);
+  const int row = q0 + j;
+  if (row >= lq) return;
+  if (t.part < 0) {
+    const float inv = 1.f / ls;
+    const size_t ob = ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int j = lane_e & 31, h2 = lane_e >> 5;
-    const float ls = l[rb] + __shfl_xor(l[rb], 32);
-    const int row = q0 + 32 * rb + j;
-    if (row >= lq) continue;
-    if (t.part < 0) {
-      const float inv = 1.f / ls;
-      const size_t ob = ((size_t)(qs + row) * P.Hq + head) * kHeadDim;
+    for (int n = 0; n < 4; ++n)
 #pragma unroll
-      for (int n = 0; n < 4; ++n)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          const int x = n * 32 + a * 8 + h2 * 4;  // acc[rb][n][4a+b] is dim x + b
-          const float o0 = acc[rb][n][4 * a + 0] * inv, o1 = acc[rb][n][4 * a + 1] * inv;
-          const float o2 = acc[rb][n][4 * a + 2] * inv, o3 = acc[rb][n][4 * a + 3] * inv;
-          if (P.out_f32) {
-            *(f32x4*)((float*)P.out + ob + x) = (f32x4){o0, o1, o2, o3};
-          } else {
-            uint2 w = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
-            *(uint2*)((uint16_t*)P.out + ob + x) = w;
-          }
+      for (int a = 0; a < 4; ++a) {
+        const int x = n * 32 + a * 8 + h2 * 4;  // acc[n][4a+b] is dim x + b
+        const float o0 = acc[n][4 * a + 0] * inv, o1 = acc[n][4 * a + 1] * inv;
+        const float o2 = acc[n][4 * a + 2] * inv, o3 = acc[n][4 * a + 3] * inv;
+        if (P.out_f32) {
+          *(f32x4*)((float*)P.out + ob + x) = (f32x4){o0, o1, o2, o3};
+        } else {
+          uint2 w = {pack_bf16x2(o0, o1), pack_bf16x2(o2, o3)};
+          *(uint2*)((uint16_t*)P.out + ob + x) = w;
         }
-    } else {  // one of several KV partitions of this row: unnormalised partial for the merge kernel
-      const int slot = t.part + (row - t.q0) * t.n_parts + t.k;
-      float* dst = P.partials + ((size_t)slot * P.Hq + head) * kPartStride;
-#pragma unroll
-      for (int n = 0; n < 4; ++n)
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-          *(f32x4*)(dst + n * 32 + a * 8 + h2 * 4) =
-              (f32x4){acc[rb][n][4 * a], acc[rb][n][4 * a + 1], acc[rb][n][4 * a + 2], acc[rb][n][4 * a + 3]};
-      if (h2 == 0) {
-        dst[128] = m[rb];
-        dst[129] = ls;
       }
+  } else {  // one of several KV partitions of this row: unnormalised partial for the merge kernel
+    const int slot = t.part + (row - t.q0) * t.n_parts + t.k;
+    float* dst = P.partials + ((size_t)slot * P.Hq + head) * kPartStride;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        *(f32x4*)(dst + n * 32 + a * 8 + h2 * 4) =
+            (f32x4){acc[n][4 * a], acc[n][4 * a + 1], acc[n][4 * a + 2], acc[n][4 * a + 3]};
+    if (h2 == 0) {
+      dst[128] = m;
+      dst[129] = ls;
     }
   }
 }
@@ -873,15 +742,13 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void attention_kernel(StepParam
                                                                        const int32_t* __restrict__ dslots,
                                                                        const int32_t* __restrict__ block_ids, int n_slots,
                                                                        int n_decode_wgs, int HW, int n_zsplit) {
-  __shared__ __attribute__((aligned(16))) char lds[sizeof(PrefillStage) * kStages + kIdTiles * 4 * sizeof(int) +
-                                                   kPrefillWaves * kQLds * kPrefillRB * 1024];
+  __shared__ __attribute__((aligned(16))) char lds[sizeof(PrefillStage) * kStages + kIdTiles * 4 * sizeof(int)];
   static_assert(sizeof(DecodeQ) * kDecodeWaves <= sizeof(PrefillStage) * kStages, "decode Q copies fit the prefill ring");
   if ((int)blockIdx.x < n_decode_wgs)
     decode_role(P, ditems, dslots, block_ids, n_slots, blockIdx.x, (DecodeQ*)lds);
   else
     prefill_role(P, (int)blockIdx.x - n_decode_wgs, HW, n_zsplit, (PrefillStage*)lds,
-                 (int*)(lds + sizeof(PrefillStage) * kStages),
-                 (uint4*)(lds + sizeof(PrefillStage) * kStages + kIdTiles * 4 * sizeof(int)));
+                 (int*)(lds + sizeof(PrefillStage) * kStages));
 }
 
 // ------------------------------------------------------------------------------------ block copy
