@@ -91,6 +91,28 @@ def main() -> int:
             B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        # a forward pass plans and uploads the batch once: ps_step on the first layer, ps_step_next_layer on
+        # the other 35 (here every "layer" works on the same tensors); reported beside the headline figure,
+        # which rebuilds the batch description on every step
+        n_layers = 36
+        passes = max(1, steps // n_layers)
+        t0 = time.perf_counter()
+        for _ in range(passes):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+            for _ in range(n_layers - 1):
+                B.ps_step_next_layer(ctx, q, kn, vn, pool, out, ws, nbytes, stream)
+        torch.cuda.synchronize()
+        dt_pass = (time.perf_counter() - t0) / (passes * n_layers)
+        host_us = {}
+        for name in ("ps_step", "ps_step_next_layer"):   # host time of a call (enqueue only), queue empty at the start;
+            t0 = time.perf_counter()                     # three calls: the fifth ps_step in flight would wait for a staging slot
+            for _ in range(3):
+                if name == "ps_step":
+                    B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+                else:
+                    B.ps_step_next_layer(ctx, q, kn, vn, pool, out, ws, nbytes, stream)
+            host_us[name] = (time.perf_counter() - t0) / 3 * 1e6
+            torch.cuda.synchronize()
         # per-launch durations: HIP events recorded by the library on the launch stream.  Mode 1: the
         # phases as they run; mode 2: the decode and the prefill work in launches of their own
         phases = {}
@@ -103,7 +125,8 @@ def main() -> int:
                     acc[k] = acc.get(k, 0.0) + v / profile_steps
             phases[mode] = acc
         B.ps_set_profiling(ctx, 0)
-        res = dict(ms_per_step=dt / steps * 1e3, phases_ms=phases, ctx=ctx, pool=pool, q=q, out=out, kn=kn, vn=vn)
+        res = dict(ms_per_step=dt / steps * 1e3, phases_ms=phases, ctx=ctx, pool=pool, q=q, out=out, kn=kn, vn=vn,
+                   ms_per_layer_plan_reused=dt_pass * 1e3, host_us_per_call=host_us)
         return res
 
     def rooflines(batch, res):
@@ -135,6 +158,8 @@ def main() -> int:
     batch = W.make_workload(args.workload)
     res = run(batch, args.steps, args.warmup, args.decode_chunk)
     rl = rooflines(batch, res)
+    rl["ms_per_layer_plan_reused"] = res["ms_per_layer_plan_reused"]
+    rl["host_us_per_call"] = res["host_us_per_call"]
     tokens_per_s = batch.n_tokens / (res["ms_per_step"] * 1e-3)
 
     # ---- CPU baseline: the fp64 oracle, as it stands, on a bounded sample of the same workload
@@ -203,6 +228,8 @@ def main() -> int:
             rr = run(bb, 20, 5, args.decode_chunk, profile_steps=10)
             e = rooflines(bb, rr)
             e["ms_per_step"] = rr["ms_per_step"]
+            e["ms_per_layer_plan_reused"] = rr["ms_per_layer_plan_reused"]
+            e["host_us_per_call"] = rr["host_us_per_call"]
             e["tokens_per_s"] = bb.n_tokens / (rr["ms_per_step"] * 1e-3)
             extra["workload_%d" % idx] = e
             B.ps_destroy(rr.pop("ctx"))

@@ -149,6 +149,19 @@ int ps_step(ps_ctx* ctx, const ps_batch* batch, const void* q, const void* k_new
             const void* v_new, void* kv_cache, void* out, void* workspace,
             size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket);
 
+/* The same batch on another layer's tensors (Sec. 4.3 and Appendix B walk a forward pass layer by
+ * layer: the batch, its block tables and the order of work are those of the pass, only q, the new
+ * K/V rows, the cache and the output change from layer to layer). Reuses the work lists and the
+ * device copy of the batch description made by the last successful ps_step on this context: no
+ * validation of the batch, no planning, no upload -- only the kernels. Arguments as for ps_step;
+ * k_new/v_new must be given exactly when that ps_step had them; the workspace needs the same size
+ * as for that ps_step; the call must be ordered after that ps_step (same stream, or a stream
+ * that waits for it). PS_ESTATE if there is no such ps_step (none yet, the last one failed, or it
+ * had n_req == 0); other errors as for ps_step. */
+int ps_step_next_layer(ps_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                       void* kv_cache, void* out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream, uint64_t wait_ticket);
+
 /* Host only, no device needed: the decode work list ps_step builds for the decode requests (l_q == 1)
  * of `batch` when `waves` decode waves are available (ps_step itself uses four per compute unit for
  * a decode-only batch and a share of that next to prefill work). The list: the requests'

@@ -22,7 +22,7 @@ PS_OK, PS_EINVAL, PS_ENOMEM, PS_EHIP, PS_ESTATE, PS_EBUSY = 0, -1, -2, -3, -4, -
 PS_BF16, PS_F32 = 0, 1
 
 EXPORTS = [
-    "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_set_profiling",
+    "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_step_next_layer", "ps_set_profiling",
     "ps_get_step_times", "ps_plan_decode", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
     "ps_sched_create", "ps_sched_destroy", "ps_sched_add_request", "ps_form_batch", "ps_sched_counts",
 ]
@@ -91,6 +91,7 @@ def lib():
         L.ps_destroy.restype = None
         L.ps_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
         L.ps_step.argtypes = [C.c_void_p, C.POINTER(ps_batch)] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
+        L.ps_step_next_layer.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
         L.ps_set_profiling.argtypes = [C.c_void_p, C.c_int]
         L.ps_get_step_times.argtypes = [C.c_void_p, C.POINTER(ps_step_times)]
         swap_args = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.c_void_p,
@@ -188,6 +189,12 @@ def ps_step(ctx: int, batch, q, k_new, v_new, kv_cache, out, workspace, workspac
     _check(lib().ps_step(ctx, C.byref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_cache), _ptr(out),
                          _ptr(workspace), workspace_bytes, _stream(stream), wait_ticket))
     del keep
+
+
+def ps_step_next_layer(ctx: int, q, k_new, v_new, kv_cache, out, workspace, workspace_bytes: int,
+                       stream=None, wait_ticket: int = 0) -> None:
+    _check(lib().ps_step_next_layer(ctx, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_cache), _ptr(out),
+                                    _ptr(workspace), workspace_bytes, _stream(stream), wait_ticket))
 
 
 def ps_plan_decode(n_kv_heads: int, n_device_blocks: int, batch, waves: int, decode_chunk: int = 0):

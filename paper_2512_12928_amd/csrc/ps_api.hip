@@ -87,6 +87,15 @@ struct ps_ctx {
   DecodePlan plan;
   std::vector<ps::PrefillTile> ptiles;
   std::vector<ps::AppendItem> aitems;
+  // What ps_step_next_layer needs of the last ps_step: where its batch description sits on the device
+  // (offsets of the lists inside the buffer), the pinned slot it was staged in, the partials it needs.
+  struct LastStep {
+    bool valid = false;
+    int meta = 0, slot = 0;
+    size_t off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};  // q_start, kv_len, bt_start, block_ids, aitems, ditems, dslots, mitems, ptiles
+    size_t part_bytes = 0;
+    bool has_new_kv = false;
+  } last;
   std::vector<int32_t> seen;  // duplicate detection in swap lists
   std::vector<int64_t> cover;  // scratch of the decode work-list check
 };
@@ -563,9 +572,75 @@ static int find_ticket(ps_ctx* c, uint64_t ticket, hipEvent_t* ev, bool* done) {
   return PS_OK;
 }
 
+// The launches of one step over the batch description that c->last points to: prologue (upload of
+// `upload_bytes` from the pinned slot `h`, if any, and the append of the new K/V rows), attention,
+// merge.
+static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps::AppendItem* aitems_src, const void* q,
+                         const void* k_new, const void* v_new, void* kv_cache, void* out, void* workspace,
+                         hipStream_t stream) {
+  ps_ctx::MetaBuf& mb = c->meta[c->last.meta];
+  StageSlot& slot = c->step_slot[c->last.slot];
+  const size_t* off = c->last.off;
+  const int prof = c->profiling;
+  char* w = mb.dev;
+
+  ps::StepParams P;
+  P.q_start = (const int32_t*)(w + off[0]);
+  P.kv_len = (const int32_t*)(w + off[1]);
+  P.bt_start = (const int32_t*)(w + off[2]);
+  P.block_ids = (const int32_t*)(w + off[3]);
+  P.ditems = (const ps::DecodeItem*)(w + off[5]);
+  P.dslots = (const int32_t*)(w + off[6]);
+  P.mitems = (const ps::MergeItem*)(w + off[7]);
+  P.ptiles = (const ps::PrefillTile*)(w + off[8]);
+  P.partials = (float*)workspace;
+  P.q = (const uint16_t*)q;
+  P.k_new = (const uint16_t*)k_new;
+  P.v_new = (const uint16_t*)v_new;
+  P.cache = (uint16_t*)kv_cache;
+  P.out = out;
+  P.Hq = c->cfg.n_q_heads;
+  P.Hkv = c->cfg.n_kv_heads;
+  P.G = c->G;
+  P.out_f32 = c->cfg.out_dtype == PS_F32;
+  P.scale_log2 = c->scale_log2;
+
+  // Prologue: one launch.  It appends the new K/V rows and, unless the context's copy stream has
+  // already brought the batch description over, uploads it with a kernel that reads the pinned slot
+  // over the host link (a third of the latency of a DMA copy).
+  PS_HIP(ps::launch_prologue(P, h, mb.dev, upload_bytes, aitems_src, k_new ? (int)c->aitems.size() : 0, stream));
+  if (h && (upload_bytes > 0 || k_new)) PS_HIP(hipEventRecord(slot.ev, stream));  // last reader of the pinned slot
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
+  // Attention: one launch for the decode slots and the prefill tiles (decode streams the cache at
+  // HBM speed and leaves the matrix pipes idle, prefill is the opposite: they run side by side on
+  // disjoint CUs).  Profiling mode 2 gives each its own launch instead.
+  const int n_slots = (int)c->plan.dslots.size() - 1;
+  if (prof == 2) {
+    PS_HIP(ps::launch_attention(P, n_slots, 0, stream));
+    PS_HIP(hipEventRecord(c->prof_ev[3], stream));
+    PS_HIP(ps::launch_attention(P, 0, (int)c->ptiles.size(), stream));
+    PS_HIP(hipEventRecord(c->prof_ev[4], stream));
+  } else {
+    PS_HIP(ps::launch_attention(P, n_slots, (int)c->ptiles.size(), stream));
+    if (prof) {
+      PS_HIP(hipEventRecord(c->prof_ev[3], stream));
+      PS_HIP(hipEventRecord(c->prof_ev[4], stream));
+    }
+  }
+  PS_HIP(ps::launch_merge(P, 0, (int)c->plan.mitems.size(), stream));
+  if (prof) {
+    PS_HIP(hipEventRecord(c->prof_ev[5], stream));
+    c->prof_valid = true;
+    c->prof_mode = prof;
+  }
+  if (c->copy) PS_HIP(hipEventRecord(mb.done, stream));
+  return PS_OK;
+}
+
 int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, const void* v_new, void* kv_cache,
             void* out, void* workspace, size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket) {
   if (!c || !b) return fail(PS_EINVAL, "ps_step: NULL ctx or batch");
+  c->last.valid = false;  // the work lists are rebuilt below; set again once this step is enqueued
   if (b->n_req < 0 || b->n_tokens < 0) return fail(PS_EINVAL, "negative n_req / n_tokens");
   hipStream_t stream = (hipStream_t)hip_stream;
   hipEvent_t wait_ev = nullptr;
@@ -703,60 +778,49 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   slot.in_flight = true;
   mb.used = true;
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[1], stream));
-  char* w = mb.dev;
+  c->last.valid = false;
+  c->last.meta = (int)(&mb - c->meta);
+  c->last.slot = (int)(&slot - c->step_slot);
+  const size_t offs[9] = {ml.q_start, ml.kv_len, ml.bt_start, ml.block_ids, ml.aitems, ml.ditems, ml.dslots, ml.mitems, ml.ptiles};
+  for (int i = 0; i < 9; ++i) c->last.off[i] = offs[i];
+  c->last.part_bytes = part_bytes;
+  c->last.has_new_kv = k_new != nullptr;
+  rc = launch_phases(c, h, c->copy ? 0 : ml.total, (const ps::AppendItem*)(h + ml.aitems), q, k_new, v_new, kv_cache, out,
+                     workspace, stream);
+  if (rc == PS_OK) c->last.valid = true;
+  return rc;
+}
 
-  ps::StepParams P;
-  P.q_start = (const int32_t*)(w + ml.q_start);
-  P.kv_len = (const int32_t*)(w + ml.kv_len);
-  P.bt_start = (const int32_t*)(w + ml.bt_start);
-  P.block_ids = (const int32_t*)(w + ml.block_ids);
-  P.ditems = (const ps::DecodeItem*)(w + ml.ditems);
-  P.dslots = (const int32_t*)(w + ml.dslots);
-  P.mitems = (const ps::MergeItem*)(w + ml.mitems);
-  P.ptiles = (const ps::PrefillTile*)(w + ml.ptiles);
-  P.partials = (float*)workspace;
-  P.q = (const uint16_t*)q;
-  P.k_new = (const uint16_t*)k_new;
-  P.v_new = (const uint16_t*)v_new;
-  P.cache = (uint16_t*)kv_cache;
-  P.out = out;
-  P.Hq = c->cfg.n_q_heads;
-  P.Hkv = c->cfg.n_kv_heads;
-  P.G = c->G;
-  P.out_f32 = c->cfg.out_dtype == PS_F32;
-  P.scale_log2 = c->scale_log2;
-
-  // Prologue: one launch.  It appends the new K/V rows and, unless the context's copy stream has
-  // already brought the batch description over, uploads it with a kernel that reads the pinned slot
-  // over the host link (a third of the latency of a DMA copy).
-  PS_HIP(ps::launch_prologue(P, h, mb.dev, c->copy ? 0 : ml.total, (const ps::AppendItem*)(h + ml.aitems),
-                             k_new ? (int)c->aitems.size() : 0, stream));
-  if (!c->copy || k_new) PS_HIP(hipEventRecord(slot.ev, stream));  // last reader of the pinned slot
-  if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
-  // Attention: one launch for the decode slots and the prefill tiles (decode streams the cache at
-  // HBM speed and leaves the matrix pipes idle, prefill is the opposite: they run side by side on
-  // disjoint CUs).  Profiling mode 2 gives each its own launch instead.
-  const int n_slots = (int)c->plan.dslots.size() - 1;
-  if (prof == 2) {
-    PS_HIP(ps::launch_attention(P, n_slots, 0, stream));
-    PS_HIP(hipEventRecord(c->prof_ev[3], stream));
-    PS_HIP(ps::launch_attention(P, 0, (int)c->ptiles.size(), stream));
-    PS_HIP(hipEventRecord(c->prof_ev[4], stream));
-  } else {
-    PS_HIP(ps::launch_attention(P, n_slots, (int)c->ptiles.size(), stream));
-    if (prof) {
-      PS_HIP(hipEventRecord(c->prof_ev[3], stream));
-      PS_HIP(hipEventRecord(c->prof_ev[4], stream));
-    }
+int ps_step_next_layer(ps_ctx* c, const void* q, const void* k_new, const void* v_new, void* kv_cache, void* out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket) {
+  if (!c) return fail(PS_EINVAL, "ps_step_next_layer: NULL ctx");
+  if (!c->last.valid) return fail(PS_ESTATE, "ps_step_next_layer: no batch from an earlier ps_step on this context");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipEvent_t wait_ev = nullptr;
+  if (wait_ticket != 0) {
+    bool done = false;
+    int rc = find_ticket(c, wait_ticket, &wait_ev, &done);
+    if (rc != PS_OK) return rc;
+    if (done) wait_ev = nullptr;
   }
-  PS_HIP(ps::launch_merge(P, 0, (int)c->plan.mitems.size(), stream));
-  if (prof) {
-    PS_HIP(hipEventRecord(c->prof_ev[5], stream));
-    c->prof_valid = true;
-    c->prof_mode = prof;
+  if (!q || !kv_cache || !out || !workspace) return fail(PS_EINVAL, "ps_step_next_layer: NULL tensor pointer");
+  if ((k_new == nullptr) != (v_new == nullptr)) return fail(PS_EINVAL, "k_new and v_new must be given together");
+  if ((k_new != nullptr) != c->last.has_new_kv)
+    return fail(PS_EINVAL, "ps_step_next_layer: k_new/v_new must be given exactly when the ps_step it follows had them");
+  if (((uintptr_t)workspace & 255) != 0) return fail(PS_EINVAL, "workspace must be 256-byte aligned");
+  if ((((uintptr_t)q | (uintptr_t)kv_cache | (uintptr_t)out | (uintptr_t)k_new | (uintptr_t)v_new) & 15) != 0)
+    return fail(PS_EINVAL, "tensor pointers must be 16-byte aligned");
+  if (c->last.part_bytes > workspace_bytes)
+    return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", c->last.part_bytes, workspace_bytes);
+  if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
+  if (c->profiling) {
+    PS_HIP(hipEventRecord(c->prof_ev[0], stream));
+    PS_HIP(hipEventRecord(c->prof_ev[1], stream));
   }
-  if (c->copy) PS_HIP(hipEventRecord(mb.done, stream));
-  return PS_OK;
+  // the append items are taken from the device copy of the batch description this time
+  const char* w = c->meta[c->last.meta].dev;
+  return launch_phases(c, nullptr, 0, (const ps::AppendItem*)(w + c->last.off[4]), q, k_new, v_new, kv_cache, out, workspace,
+                       stream);
 }
 
 static int swap_common(ps_ctx* c, bool out_dir, const int32_t* dev_ids, const int32_t* host_ids, int32_t n,

@@ -56,6 +56,7 @@ def test_null_arguments_are_errors_not_crashes():
     L = B.lib()
     assert L.ps_create(None, None) == B.PS_EINVAL
     assert L.ps_step(None, None, None, None, None, None, None, None, 0, None, 0) == B.PS_EINVAL
+    assert L.ps_step_next_layer(None, None, None, None, None, None, None, 0, None, 0) == B.PS_EINVAL
     n, t = C.c_int32(), C.c_uint64()
     assert L.ps_swap_out(None, None, None, 0, 0, None, None, None, C.byref(n), C.byref(t)) == B.PS_EINVAL
     assert L.ps_ticket_wait(None, 1) == B.PS_EINVAL

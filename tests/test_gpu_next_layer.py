@@ -1,0 +1,85 @@
+"""ps_step_next_layer: the batch of a forward pass is planned and uploaded once (ps_step on the first
+layer), the following layers run the same work lists over their own q, new K/V rows, cache and
+output.  Every layer's output must equal the oracle's on that layer's tensors, and every layer's
+cache, after its append, the oracle's cache bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as A
+from paper_2512_12928_amd import binding as B
+from paper_2512_12928_amd import workloads as W
+from paper_2512_12928_amd.kvlayout import from_device_layout, to_device_layout
+from gpu_harness import DEV, check_close, dev_to_u16, oracle_cache, u16_to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def layer_tensors(b, ell, append):
+    t = W.make_tensors(b, seed=b.seed + 77 * (ell + 1))
+    full = oracle_cache(b, t)
+    want = A.paged_attention(t.q, full, b.q_start, b.kv_len, b.bt_start, b.block_ids)
+    start = oracle_cache(b, t, upto_prefix=True) if append else full
+    k_new, v_new = t.new_rows(b) if append else (None, None)
+    return dict(q=u16_to_dev(t.q), pool=u16_to_dev(to_device_layout(start.pool)), want=want, full=full.pool,
+                k_new=None if k_new is None else u16_to_dev(k_new), v_new=None if v_new is None else u16_to_dev(v_new))
+
+
+@pytest.mark.parametrize("append", [True, False])
+@pytest.mark.parametrize("workload,scale", [(1, 1.0), (2, 0.08), (5, 0.05)])
+def test_layers_after_the_first_reuse_the_plan(workload, scale, append):
+    b = W.make_workload(workload) if workload == 1 else W.make_workload(workload, scale=scale)
+    s = b.shape
+    n_layers = 3
+    layers = [layer_tensors(b, ell, append) for ell in range(n_layers)]
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, b.n_device_blocks, 0, out_dtype=B.PS_F32)
+    nbytes = B.ps_workspace_bytes(ctx, b.n_req, b.n_tokens, len(b.block_ids))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    outs = [torch.full((b.n_tokens, s.n_q_heads, s.head_dim), float("nan"), dtype=torch.float32, device=DEV)
+            for _ in layers]
+    stream = torch.cuda.current_stream()
+    for ell, L in enumerate(layers):
+        if ell == 0:
+            B.ps_step(ctx, b, L["q"], L["k_new"], L["v_new"], L["pool"], outs[ell], ws, nbytes, stream)
+        else:
+            B.ps_step_next_layer(ctx, L["q"], L["k_new"], L["v_new"], L["pool"], outs[ell], ws, nbytes, stream)
+    torch.cuda.synchronize()
+    for ell, L in enumerate(layers):
+        check_close(outs[ell].cpu().numpy().astype(np.float64), L["want"], False)
+        assert np.array_equal(from_device_layout(dev_to_u16(L["pool"]), s.n_kv_heads), L["full"])
+    B.ps_destroy(ctx)
+
+
+def test_next_layer_needs_a_batch():
+    b = W.make_workload(1)
+    s = b.shape
+    L = layer_tensors(b, 0, True)
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, b.n_device_blocks, 0, out_dtype=B.PS_F32)
+    nbytes = B.ps_workspace_bytes(ctx, b.n_req, b.n_tokens, len(b.block_ids))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    out = torch.zeros((b.n_tokens, s.n_q_heads, s.head_dim), dtype=torch.float32, device=DEV)
+    args = (L["q"], L["k_new"], L["v_new"], L["pool"], out, ws, nbytes)
+
+    def refused(code, *a):
+        with pytest.raises(B.PsError) as e:
+            B.ps_step_next_layer(ctx, *a)
+        assert e.value.code == code, str(e.value)
+
+    refused(B.PS_ESTATE, *args)                                  # nothing planned yet
+    B.ps_step(ctx, b, *args)
+    B.ps_step_next_layer(ctx, *args)                             # now it runs
+    refused(B.PS_EINVAL, L["q"], None, None, L["pool"], out, ws, nbytes)   # that ps_step had new K/V rows
+    refused(B.PS_EINVAL, None, L["k_new"], L["v_new"], L["pool"], out, ws, nbytes)
+    bad = W.make_workload(1)
+    bad.kv_len = bad.kv_len.copy()
+    bad.kv_len[0] += 100                                         # table length no longer matches
+    with pytest.raises(B.PsError):
+        B.ps_step(ctx, bad, *args)
+    refused(B.PS_ESTATE, *args)                                  # a failed ps_step leaves no plan behind
+    empty = W.MixedBatch(shape=s, n_device_blocks=b.n_device_blocks, q_start=np.zeros(1, np.int32), kv_len=np.zeros(0, np.int32),
+                         bt_start=np.zeros(1, np.int32), block_ids=np.zeros(0, np.int32), prio=np.zeros(0, np.uint8))
+    B.ps_step(ctx, b, *args)
+    B.ps_step(ctx, empty, *args)
+    refused(B.PS_ESTATE, *args)                                  # nor does an empty batch
+    torch.cuda.synchronize()
+    B.ps_destroy(ctx)
