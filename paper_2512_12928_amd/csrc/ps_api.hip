@@ -114,6 +114,26 @@ struct TileKey {
 // Out: tiles replaced by the launch's work items (partitions of the walks, not yet ordered), merge
 //      items and partial slots for split rows appended; returns the price of the prefill work with the
 //      whole chip, in KV tile steps per CU.
+// The time (in KV tile steps) at which a launch ends when `busy` of the n_cus compute units are taken
+// until `busy_until` (by the decode workgroups, dispatched first) and the prefill workgroups, `per_tile`
+// for each entry of `tiles` (sorted longest first), are handed one by one to whichever unit is free next.
+double mixed_makespan(const std::vector<TileKey>& tiles, int per_tile, int n_cus, int busy, double busy_until,
+                      std::vector<double>& bins) {
+  bins.assign((size_t)n_cus, 0.0);
+  for (int i = 0; i < busy && i < n_cus; ++i) bins[(size_t)i] = busy_until;
+  auto later = std::greater<double>();
+  std::make_heap(bins.begin(), bins.end(), later);
+  double end = busy > 0 ? busy_until : 0.0;
+  for (auto& t : tiles)
+    for (int w = 0; w < per_tile; ++w) {
+      std::pop_heap(bins.begin(), bins.end(), later);
+      bins.back() += (double)t.reach;
+      end = std::max(end, bins.back());
+      std::push_heap(bins.begin(), bins.end(), later);
+    }
+  return end;
+}
+
 double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, int TT, size_t workspace_bytes, int& n_parts) {
   double prefill_steps = 0;
   const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
@@ -711,8 +731,34 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     if (c->cfg.decode_waves == 0 && c->profiling != 2 && !decode_reqs.empty() && !tiles.empty()) {
       const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / 6.3e6;  // us
       const double t_p = prefill_steps * 1.92;
+      const int lo = std::min(8, c->n_cus), hi = c->n_cus - 8;
       int cus = (int)(0.95 * c->n_cus * t_d / (t_d + t_p));
-      cus = std::max(std::min(8, c->n_cus), std::min(cus, c->n_cus - 8));
+      cus = std::max(lo, std::min(cus, hi));
+      // Few, equally long prefill workgroups (one long chunk that outweighs the decode work) pack badly
+      // next to a small decode share:
+      // they run in rounds, and the decode units come free in the middle of one.  Larger shares are
+      // priced too: the decode workgroups on n units last t_d stretched by 176/n below 176 units
+      // (above, HBM is the limit) and by 5 % for the prefill traffic next to them; the launch ends when
+      // the prefill workgroups, handed to whichever unit is free next, are through.  A larger share
+      // wins only if it ends the launch 2 % sooner.
+      const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
+      if (t_p > t_d && tiles.size() * (size_t)wg_per_tile <= 1024) {
+        std::vector<TileKey> sorted(tiles);
+        std::stable_sort(sorted.begin(), sorted.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
+        std::vector<double> bins;
+        auto ends = [&](int n) {
+          const double d = t_d / 1.92 * 1.05 * std::max(1.0, 176.0 / n);
+          return mixed_makespan(sorted, wg_per_tile, c->n_cus, n, d, bins);
+        };
+        double best = ends(cus);
+        for (int n = std::max(128, (cus / 32 + 1) * 32); n <= hi; n += 32) {
+          const double e = ends(n);
+          if (e < 0.98 * best) {
+            best = e;
+            cus = n;
+          }
+        }
+      }
       waves = ps::decode_waves_per_wg() * cus;
     }
     build_decode_slots(&c->plan, c->cfg.n_kv_heads, c->cfg.decode_chunk, b, decode_reqs, n_parts, waves);
