@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of attention_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
 # plain 1 GiB copy; summary in profiles/attention_kernel_hbm_traffic_pmc.md), by workload index.
-MEASURED_ATTENTION_TRAFFIC = {2: 1.607e9, 4: 3.401e9}
+MEASURED_ATTENTION_TRAFFIC = {2: 1.607e9, 4: 3.382e9}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
