@@ -68,6 +68,13 @@ def test_next_layer_needs_a_batch():
     refused(B.PS_ESTATE, *args)                                  # nothing planned yet
     B.ps_step(ctx, b, *args)
     B.ps_step_next_layer(ctx, *args)                             # now it runs
+    B.ps_set_profiling(ctx, 1)                                   # and reports its phases like a ps_step
+    B.ps_step_next_layer(ctx, *args)
+    torch.cuda.synchronize()
+    times = B.ps_get_step_times(ctx)
+    assert times["attention_ms"] > 0 and times["append_ms"] > 0 and times["total_ms"] >= times["attention_ms"]
+    assert times["upload_ms"] < 0.5 * times["total_ms"]          # nothing is uploaded
+    B.ps_set_profiling(ctx, 0)
     refused(B.PS_EINVAL, L["q"], None, None, L["pool"], out, ws, nbytes)   # that ps_step had new K/V rows
     refused(B.PS_EINVAL, None, L["k_new"], L["v_new"], L["pool"], out, ws, nbytes)
     bad = W.make_workload(1)
