@@ -26,23 +26,24 @@ def layer_tensors(b, ell, append):
 
 
 @pytest.mark.parametrize("append", [True, False])
-@pytest.mark.parametrize("workload,scale", [(1, 1.0), (2, 0.08), (5, 0.05)])
-def test_layers_after_the_first_reuse_the_plan(workload, scale, append):
+@pytest.mark.parametrize("workload,scale,own_streams", [(1, 1.0, 0), (2, 0.08, 0), (2, 0.08, 1), (5, 0.05, 0)])
+def test_layers_after_the_first_reuse_the_plan(workload, scale, own_streams, append):
     b = W.make_workload(workload) if workload == 1 else W.make_workload(workload, scale=scale)
     s = b.shape
     n_layers = 3
     layers = [layer_tensors(b, ell, append) for ell in range(n_layers)]
-    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, b.n_device_blocks, 0, out_dtype=B.PS_F32)
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, b.n_device_blocks, 0, out_dtype=B.PS_F32, own_streams=own_streams)
     nbytes = B.ps_workspace_bytes(ctx, b.n_req, b.n_tokens, len(b.block_ids))
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     outs = [torch.full((b.n_tokens, s.n_q_heads, s.head_dim), float("nan"), dtype=torch.float32, device=DEV)
             for _ in layers]
     stream = torch.cuda.current_stream()
-    for ell, L in enumerate(layers):
-        if ell == 0:
-            B.ps_step(ctx, b, L["q"], L["k_new"], L["v_new"], L["pool"], outs[ell], ws, nbytes, stream)
-        else:
-            B.ps_step_next_layer(ctx, L["q"], L["k_new"], L["v_new"], L["pool"], outs[ell], ws, nbytes, stream)
+    for _ in range(2):   # two passes back to back: the second ps_step meets buffers the first pass's layers used
+        for ell, L in enumerate(layers):
+            if ell == 0:
+                B.ps_step(ctx, b, L["q"], L["k_new"], L["v_new"], L["pool"], outs[ell], ws, nbytes, stream)
+            else:
+                B.ps_step_next_layer(ctx, L["q"], L["k_new"], L["v_new"], L["pool"], outs[ell], ws, nbytes, stream)
     torch.cuda.synchronize()
     for ell, L in enumerate(layers):
         check_close(outs[ell].cpu().numpy().astype(np.float64), L["want"], False)
