@@ -398,25 +398,31 @@ def reload_pipeline_bench(B, W, torch, np, dev, n_layers=8):
     cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
     compute, side = torch.cuda.Stream(), torch.cuda.Stream()
 
+    def layer(ell, tk=0):   # the pass plans its batch once: ps_step on the first layer, the rest reuse it
+        if ell == 0:
+            B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute, tk)
+        else:
+            B.ps_step_next_layer(ctx, q, None, None, pools[ell], out, ws, nbytes, compute, tk)
+
     def one_pass(mode, budget=-1):
         if mode == "compute_only":
             for ell in range(n_layers):
-                B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute)
+                layer(ell)
         elif mode == "synchronous":
             for ell in range(n_layers):
                 _, tk = B.ps_swap_in(ctx, slots, dev_ids, budget, hosts[ell], pools[ell], side)
                 B.ps_ticket_wait(ctx, tk)
-                B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute)
+                layer(ell)
         elif mode == "full_reload_first":
             tks = [B.ps_swap_in(ctx, slots, dev_ids, budget, hosts[ell], pools[ell], side)[1] for ell in range(n_layers)]
             B.ps_ticket_wait(ctx, tks[-1])
             for ell in range(n_layers):
-                B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute)
+                layer(ell)
         else:  # pipelined
             tk = B.ps_swap_in(ctx, slots, dev_ids, budget, hosts[0], pools[0], side)[1]
             for ell in range(n_layers):
                 nxt = B.ps_swap_in(ctx, slots, dev_ids, budget, hosts[ell + 1], pools[ell + 1], side)[1] if ell + 1 < n_layers else 0
-                B.ps_step(ctx, cb, q, None, None, pools[ell], out, ws, nbytes, compute, tk)
+                layer(ell, tk)
                 tk = nxt
 
     def timed(mode, budget=-1, reps=10):

@@ -65,7 +65,10 @@ def test_pipelined_reload_across_layers(mode):
         tk = reload(0)
         for ell, L in enumerate(layers):
             nxt = reload(ell + 1) if ell + 1 < N_LAYERS else 0   # layer ell+1 loads while layer ell computes
-            B.ps_step(ctx, b, L["q"], None, None, L["pool"], outs[ell], ws, nbytes, compute, tk)
+            if ell == 0:                                         # the pass plans its batch once
+                B.ps_step(ctx, b, L["q"], None, None, L["pool"], outs[ell], ws, nbytes, compute, tk)
+            else:
+                B.ps_step_next_layer(ctx, L["q"], None, None, L["pool"], outs[ell], ws, nbytes, compute, tk)
             tk = nxt
     else:
         tks = [reload(ell) for ell in range(N_LAYERS)]
