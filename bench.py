@@ -237,6 +237,7 @@ def main() -> int:
             torch.cuda.empty_cache()
         extra["swap"] = swap_bench(B, W, torch, np, dev)
         extra["reload_pipeline"] = reload_pipeline_bench(B, W, torch, np, dev)
+        extra["launch_bound_pass"] = graph_bench(B, W, torch, np, dev)
         extra["sched"] = sched_bench(B, W, np, res["ms_per_step"])
 
     # the dominant kernel is the attention launch; it is priced against the roof of whichever kind of
@@ -449,6 +450,63 @@ def reload_pipeline_bench(B, W, torch, np, dev, n_layers=8):
     res["budget_blocks_that_fit"] = fit
     res["pipelined_budgeted_ms"] = timed("pipelined", fit)
     res["pipelined_budgeted_overhead_vs_compute_only"] = res["pipelined_budgeted_ms"] / res["compute_only_ms"] - 1.0
+    B.ps_destroy(ctx)
+    return res
+
+
+def graph_bench(B, W, torch, np, dev, n_layers=36):
+    """A launch-bound case: 16 decode requests of about 1 k tokens (a kernel of a few microseconds per layer).
+    One forward pass of n_layers layers, three ways: ps_step on every layer; ps_step on the first layer and
+    ps_step_next_layer on the rest; the same with the rest captured once into a HIP graph and replayed."""
+    import time as _t
+    shape = W.LayerShape(32, 8)
+    rng = np.random.default_rng(99)
+    items = [(1, int(x)) for x in rng.integers(600, 1400, size=16)]
+    batch = W.build_batch(shape, items, [1] * len(items), rng, name="16 decode requests", seed=99)
+    g = torch.Generator(device=dev)
+    g.manual_seed(99)
+    pool = torch.empty((batch.n_device_blocks, shape.block_bytes // 2), dtype=torch.bfloat16, device=dev).normal_(generator=g)
+    q = torch.randn((batch.n_tokens, shape.n_q_heads, shape.head_dim), generator=g, device=dev).to(torch.bfloat16)
+    kn = torch.randn((batch.n_tokens, shape.n_kv_heads, shape.head_dim), generator=g, device=dev).to(torch.bfloat16)
+    vn = torch.randn((batch.n_tokens, shape.n_kv_heads, shape.head_dim), generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    ctx = B.ps_create(shape.n_q_heads, shape.n_kv_heads, batch.n_device_blocks, 0)
+    nbytes = B.ps_workspace_bytes(ctx, batch.n_req, batch.n_tokens, len(batch.block_ids))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
+    side = torch.cuda.Stream()
+
+    def first():
+        B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, side)
+
+    def rest():
+        for _ in range(n_layers - 1):
+            B.ps_step_next_layer(ctx, q, kn, vn, pool, out, ws, nbytes, side)
+
+    def timed(fn, reps=20):
+        fn()
+        torch.cuda.synchronize()
+        t0 = _t.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (_t.perf_counter() - t0) / (reps * n_layers) * 1e6
+
+    res = dict(batch=batch.name, n_layers=n_layers)
+    res["ps_step_every_layer_us_per_layer"] = timed(lambda: [first() for _ in range(n_layers)])
+    res["plan_once_us_per_layer"] = timed(lambda: (first(), rest()))
+    first()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        rest()
+
+    def replayed():
+        first()
+        with torch.cuda.stream(side):
+            graph.replay()
+    res["plan_once_graph_replay_us_per_layer"] = timed(replayed)
+    del graph
     B.ps_destroy(ctx)
     return res
 

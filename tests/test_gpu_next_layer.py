@@ -91,3 +91,48 @@ def test_next_layer_needs_a_batch():
     refused(B.PS_ESTATE, *args)                                  # nor does an empty batch
     torch.cuda.synchronize()
     B.ps_destroy(ctx)
+
+
+def test_layers_after_the_first_replay_as_a_hip_graph():
+    """ps_step_next_layer is kernel launches only (no allocation, no copy, no event unless profiling or a
+    ticket is asked for), so a caller can capture the layers after the first into a HIP graph.  Every replay,
+    with eager work and synchronisation in between, must give what the eager calls give."""
+    b = W.make_workload(2, scale=0.08)
+    s = b.shape
+    n_layers = 4
+    layers = [layer_tensors(b, ell, True) for ell in range(n_layers)]
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, b.n_device_blocks, 0, out_dtype=B.PS_F32)
+    nbytes = B.ps_workspace_bytes(ctx, b.n_req, b.n_tokens, len(b.block_ids))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    outs = [torch.zeros((b.n_tokens, s.n_q_heads, s.head_dim), dtype=torch.float32, device=DEV) for _ in layers]
+    side = torch.cuda.Stream()
+
+    def first_layer():
+        L = layers[0]
+        B.ps_step(ctx, b, L["q"], L["k_new"], L["v_new"], L["pool"], outs[0], ws, nbytes, side)
+
+    def other_layers():
+        for ell in range(1, n_layers):
+            L = layers[ell]
+            B.ps_step_next_layer(ctx, L["q"], L["k_new"], L["v_new"], L["pool"], outs[ell], ws, nbytes, side)
+
+    first_layer()
+    other_layers()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        other_layers()
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        first_layer()                                            # eager, on the same stream
+        side.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        torch.cuda.synchronize()
+        for ell in range(n_layers):
+            assert torch.equal(outs[ell], eager[ell]), (rep, ell)
+            check_close(outs[ell].cpu().numpy().astype(np.float64), layers[ell]["want"], False)
+    del graph
+    B.ps_destroy(ctx)
