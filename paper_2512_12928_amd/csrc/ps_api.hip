@@ -259,7 +259,10 @@ int check_batch(const ps_batch* b, int M, int64_t* decode_kv_out) {
   return PS_OK;
 }
 
-constexpr int kMinSlotTiles = 16;  // a balanced decode slot holds at least this many 32-token tiles
+// A balanced decode slot holds at least this many 32-token tiles.  Small batches are latency-bound (a wave
+// takes its tiles one after the other, about 2 us each): with 4 instead of 16 a layer over 16 requests of
+// 1 k tokens takes 20 us instead of 31; large batches have more tiles per slot than that anyway.
+constexpr int kMinSlotTiles = 4;
 
 // Decode work list.  Every decode request is cut into segments, and the segments are dealt to
 // slots; the decode kernel runs one wave per (slot, kv-head) which walks its slot's segments.
@@ -502,11 +505,15 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
   if (!c || !out_bytes) return fail(PS_EINVAL, "ps_workspace_bytes: NULL argument");
   if (max_req < 0 || max_tokens < 0 || max_table_entries < 0) return fail(PS_EINVAL, "negative size");
   // decode partials: one per segment.  Fixed partitions: every request a decode split at that size;
-  // balanced slots: at most one extra segment per slot, and a slot holds at least kMinSlotTiles
-  // tiles (a request of n table entries has at most (n + 1) / 2 tiles).
+  // balanced slots: at most one extra segment per slot; a slot holds at least kMinSlotTiles tiles (a
+  // request of n table entries has at most (n + 1) / 2 tiles) and there are no more slots than one per
+  // decode wave and kv-head.
+  const size_t slots_by_tiles = (size_t)((max_table_entries + max_req) / (2 * kMinSlotTiles)) + 1;
+  const size_t slots_by_waves =
+      (size_t)((c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus) / c->cfg.n_kv_heads) + 1;
   const size_t max_parts = (size_t)max_req + (c->cfg.decode_chunk > 0
                                                  ? (size_t)(max_table_entries * ps::kBlockTokens / c->cfg.decode_chunk)
-                                                 : (size_t)((max_table_entries + max_req) / (2 * kMinSlotTiles)) + 1);
+                                                 : std::min(slots_by_tiles, slots_by_waves));
   // + up to two partial slots per batch token for prefill rows whose KV range is split
   *out_bytes = align_up((max_parts + 2 * (size_t)max_tokens) * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256) + 256;
   return PS_OK;

@@ -48,7 +48,7 @@ def check_plan(batch, seg, n_slots, waves, hkv, chunk=0):
         tiles[x] += -(-(int(t1) - int(t0)) // 32)
     T = int(sum(-(-int(batch.kv_len[r]) // 32) for r in dec))
     if chunk == 0:
-        assert n_slots == (max(1, min(waves // hkv, T // 16)) if dec else 0)
+        assert n_slots == (max(1, min(waves // hkv, T // 4)) if dec else 0)
         if dec:
             assert tiles.sum() == T and tiles.max() - tiles.min() <= 1
             assert sum(len(v) > 1 for v in by_req.values()) <= n_slots - 1 or n_slots == 1
@@ -90,7 +90,10 @@ def test_edge_cases():
     b3 = W.build_batch(shape, [(1, 50_000)], [0], rng, n_device_blocks=4096, seed=3)
     seg, n = B.ps_plan_decode(8, 4096, b3, 1024)
     check_plan(b3, seg, n, 1024, 8)
-    assert n == 97 and len(seg) == 97            # 1563 tiles / 16 = 97 slots (fewer than 1024 / 8)
+    assert n == 128 and len(seg) == 128          # 1563 tiles: 1024 / 8 slots of 12 or 13 tiles
+    seg, n = B.ps_plan_decode(8, 4096, b3, 4096)
+    check_plan(b3, seg, n, 4096, 8)
+    assert n == 390 and len(seg) == 390          # no slot shorter than 4 tiles: 1563 / 4 slots (fewer than 4096 / 8)
     # the headline workload at full size, with the wave count ps_step uses on a 256-CU device
     b4 = W.make_workload(2)
     seg, n = B.ps_plan_decode(8, b4.n_device_blocks, b4, 1024)
