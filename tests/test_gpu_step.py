@@ -93,6 +93,16 @@ def test_mixed_batch_decode_share_extremes():
     check_close(got, oracle_out(b, t, cache), False)
 
 
+def test_prefill_heavy_mixed_batch():
+    """A long chunk of equally long workgroups that outweighs the decode work next to it: the case in which the
+    host prices larger decode shares by simulation (decode first at full speed, prefill inheriting its CUs)."""
+    rng = np.random.default_rng(77)
+    items = [(1, int(x)) for x in rng.integers(200, 900, size=40)] + [(768, 768 + 3072)]
+    b, t = custom_batch(32, 8, items, seed=77)
+    got, cache = run_prefilled(b, t)
+    check_close(got, oracle_out(b, t, cache), False)
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_mixed_batches(seed):
     """Seeded random mixed batches (head shapes, request counts, lengths, chunk sizes and prefixes drawn at
