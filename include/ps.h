@@ -46,7 +46,7 @@ typedef enum {
   PS_EINVAL = -1, /* bad argument / inconsistent batch description            */
   PS_ENOMEM = -2, /* workspace too small, or a host allocation failed         */
   PS_EHIP = -3,   /* a HIP call failed; ps_last_error() holds its text        */
-  PS_ESTATE = -4, /* unknown ticket                                            */
+  PS_ESTATE = -4, /* unknown ticket; ps_step_next_layer without a batch to reuse */
   PS_EBUSY = -5   /* ticket still in flight (ps_ticket_query only)             */
 } ps_status;
 
