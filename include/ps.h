@@ -176,6 +176,16 @@ int ps_step_next_layer(ps_ctx* ctx, const void* q, const void* k_new, const void
 int ps_plan_decode(const ps_layer_cfg* cfg, const ps_batch* batch, int32_t waves, int32_t* seg,
                    int32_t seg_cap, int32_t* n_seg, int32_t* n_slots);
 
+/* Host only, no device needed: how ps_step lays out the attention launch of `batch` on a device with n_cus
+ * compute units (the decode work and the prefill work of a mixed batch share one launch; the decode
+ * workgroups, one compute unit each, come first and the prefill workgroups take the rest and inherit the
+ * decode units as those finish). For tests of that host logic.
+ *   out6[0] decode waves     out6[1] decode slots (waves / Hkv)     out6[2] decode workgroups
+ *   out6[3] prefill workgroups     out6[4] KV tiles (64 tokens) per partition of split prefill rows, 0 = no row split
+ *   out6[5] split-K partial slots the step uses
+ * Errors as for ps_step's validation. */
+int ps_plan_launch(const ps_layer_cfg* cfg, const ps_batch* batch, int32_t n_cus, int32_t* out6);
+
 /* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds).
  * mode 0: off; 1: the phases as they run; 2: the decode and the prefill work of the attention
  * phase in launches of their own, one after the other. PS_EINVAL for any other mode. */

@@ -23,7 +23,7 @@ PS_BF16, PS_F32 = 0, 1
 
 EXPORTS = [
     "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_step_next_layer", "ps_set_profiling",
-    "ps_get_step_times", "ps_plan_decode", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
+    "ps_get_step_times", "ps_plan_decode", "ps_plan_launch", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
     "ps_sched_create", "ps_sched_destroy", "ps_sched_add_request", "ps_form_batch", "ps_sched_counts",
 ]
 
@@ -91,6 +91,7 @@ def lib():
         L.ps_destroy.restype = None
         L.ps_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
         L.ps_step.argtypes = [C.c_void_p, C.POINTER(ps_batch)] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
+        L.ps_plan_launch.argtypes = [C.POINTER(ps_layer_cfg), C.POINTER(ps_batch), C.c_int32, C.POINTER(C.c_int32)]
         L.ps_step_next_layer.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
         L.ps_set_profiling.argtypes = [C.c_void_p, C.c_int]
         L.ps_get_step_times.argtypes = [C.c_void_p, C.POINTER(ps_step_times)]
@@ -189,6 +190,24 @@ def ps_step(ctx: int, batch, q, k_new, v_new, kv_cache, out, workspace, workspac
     _check(lib().ps_step(ctx, C.byref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_cache), _ptr(out),
                          _ptr(workspace), workspace_bytes, _stream(stream), wait_ticket))
     del keep
+
+
+def ps_plan_launch(n_q_heads: int, n_kv_heads: int, n_device_blocks: int, batch, n_cus: int = 256, **cfg_kw) -> dict:
+    """Host only.  batch: as for ps_step."""
+    cfg = ps_layer_cfg()
+    cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.block_tokens, cfg.n_device_blocks = n_q_heads, n_kv_heads, 128, 16, n_device_blocks
+    for k, v in cfg_kw.items():
+        setattr(cfg, k, v)
+    keep = None
+    if isinstance(batch, tuple):
+        batch, keep = batch
+    elif not isinstance(batch, ps_batch):
+        batch, keep = make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, getattr(batch, "prio", None))
+    out = (C.c_int32 * 6)()
+    _check(lib().ps_plan_launch(C.byref(cfg), C.byref(batch), n_cus, out))
+    del keep
+    return dict(zip(("decode_waves", "decode_slots", "decode_workgroups", "prefill_workgroups", "prefill_split_tiles",
+                     "partial_slots"), [int(x) for x in out]))
 
 
 def ps_step_next_layer(ctx: int, q, k_new, v_new, kv_cache, out, workspace, workspace_bytes: int,

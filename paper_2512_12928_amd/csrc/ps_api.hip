@@ -412,9 +412,7 @@ const char* ps_last_error(void) { return g_err.c_str(); }
 // used by the host-only scheduler translation unit
 void ps_internal_set_error(const char* text) { g_err = text ? text : ""; }
 
-int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
-  if (!cfg || !out) return fail(PS_EINVAL, "ps_create: NULL argument");
-  *out = nullptr;
+static int check_cfg(const ps_layer_cfg* cfg) {
   if (cfg->head_dim != ps::kHeadDim) return fail(PS_EINVAL, "head_dim must be 128 (got %d)", cfg->head_dim);
   if (cfg->block_tokens != ps::kBlockTokens)
     return fail(PS_EINVAL, "block_tokens must be 16 (got %d)", cfg->block_tokens);
@@ -439,11 +437,20 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
     return fail(PS_EINVAL, "decode_waves must be in [0, 65536]");
   if (!(cfg->softmax_scale >= 0.f) || std::isinf(cfg->softmax_scale))
     return fail(PS_EINVAL, "softmax_scale must be finite and >= 0");
+  return PS_OK;
+}
 
+int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
+  if (!cfg || !out) return fail(PS_EINVAL, "ps_create: NULL argument");
+  *out = nullptr;
+  {
+    int rc = check_cfg(cfg);
+    if (rc != PS_OK) return rc;
+  }
   ps_ctx* c = new (std::nothrow) ps_ctx();
   if (!c) return fail(PS_ENOMEM, "out of host memory");
   c->cfg = *cfg;
-  c->G = G;
+  c->G = cfg->n_q_heads / cfg->n_kv_heads;
   c->block_bytes = (size_t)2 * cfg->n_kv_heads * ps::kSliceElems * 2;
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   c->scale_log2 = scale * 1.4426950408889634f;
@@ -599,6 +606,98 @@ static int find_ticket(ps_ctx* c, uint64_t ticket, hipEvent_t* ev, bool* done) {
   return PS_OK;
 }
 
+// The work lists of one step (append items, decode slots, prefill tiles, merge items) into c->plan, c->ptiles
+// and c->aitems; n_parts = partial slots they use.  Host work only: c needs cfg, G, block_bytes, n_cus and
+// profiling set, nothing of the device.
+static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t workspace_bytes, int64_t decode_kv,
+                      int& n_parts_out, int64_t* prefill_split_out) {
+  const int n_req = b->n_req;
+  // ---- work lists
+  const int TT = ps::prefill_tile_tokens(c->G);
+  c->plan.ditems.clear();
+  c->plan.dslots.assign(1, 0);
+  c->plan.mitems.clear();
+  c->ptiles.clear();
+  c->aitems.clear();
+  int n_parts = 0;
+  std::vector<TileKey> tiles;
+  std::vector<int> decode_reqs;
+  for (int r = 0; r < n_req; ++r) {
+    const int qs = b->q_start[r], lq = b->q_start[r + 1] - qs, L = b->kv_len[r];
+    if (has_new_kv)
+      for (int lb = (L - lq) / ps::kBlockTokens; lb * ps::kBlockTokens < L; ++lb) {
+        const int b0 = lb * ps::kBlockTokens;
+        const int lo = std::max(L - lq, b0), hi = std::min(L, b0 + ps::kBlockTokens);  // new positions in this block
+        c->aitems.push_back(ps::AppendItem{b->block_ids[b->bt_start[r] + lb], qs + lo - (L - lq), lo - b0, hi - lo});
+      }
+    if (lq == 1) {
+      decode_reqs.push_back(r);
+    } else {
+      const int p = L - lq;
+      for (int q0 = 0; q0 < lq; q0 += TT) {
+        const int last = std::min(q0 + TT, lq) - 1;  // KV tiles (64 tokens) any query of the tile can see
+        tiles.push_back(TileKey{(p + last) / 64 + 1, ps::PrefillTile{r, q0, 0, 0, -1, 1, 0, 0}});
+      }
+    }
+  }
+  const double prefill_steps = plan_prefill(c, b, tiles, TT, workspace_bytes, n_parts);
+
+  // Decode slots.  With prefill work in the same launch the decode workgroups get the share of the
+  // CUs that makes both kinds of work end together (each priced at its full-chip speed: 6.3 TB/s
+  // for the cache stream, 1.92 us per KV tile step of a prefill workgroup; the decode share is cut
+  // by 5 %: prefill workgroups inherit CUs that decode leaves early, never the other way round).
+  {
+    int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
+    if (c->cfg.decode_waves == 0 && c->profiling != 2 && !decode_reqs.empty() && !tiles.empty()) {
+      const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / 6.3e6;  // us
+      const double t_p = prefill_steps * 1.92;
+      const int lo = std::min(8, c->n_cus), hi = c->n_cus - 8;
+      int cus = (int)(0.95 * c->n_cus * t_d / (t_d + t_p));
+      cus = std::max(lo, std::min(cus, hi));
+      // Few, equally long prefill workgroups (one long chunk that outweighs the decode work) pack badly
+      // next to a small decode share:
+      // they run in rounds, and the decode units come free in the middle of one.  Larger shares are
+      // priced too: the decode workgroups on n units last t_d stretched by 176/n below 176 units
+      // (above, HBM is the limit) and by 5 % for the prefill traffic next to them; the launch ends when
+      // the prefill workgroups, handed to whichever unit is free next, are through.  A larger share
+      // wins only if it ends the launch 2 % sooner.
+      const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
+      if (t_p > t_d && tiles.size() * (size_t)wg_per_tile <= 1024) {
+        std::vector<TileKey> sorted(tiles);
+        std::stable_sort(sorted.begin(), sorted.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
+        std::vector<double> bins;
+        auto ends = [&](int n) {
+          const double d = t_d / 1.92 * 1.05 * std::max(1.0, 176.0 / n);
+          return mixed_makespan(sorted, wg_per_tile, c->n_cus, n, d, bins);
+        };
+        double best = ends(cus);
+        for (int n = std::max(128, (cus / 32 + 1) * 32); n <= hi; n += 32) {
+          const double e = ends(n);
+          if (e < 0.98 * best) {
+            best = e;
+            cus = n;
+          }
+        }
+      }
+      waves = ps::decode_waves_per_wg() * cus;
+    }
+    build_decode_slots(&c->plan, c->cfg.n_kv_heads, c->cfg.decode_chunk, b, decode_reqs, n_parts, waves);
+    if (!decode_slots_ok(&c->plan, b, decode_reqs, c->cover))
+      return fail(PS_ESTATE, "ps_step: inconsistent decode work list (library bug)");
+  }
+
+  // heaviest partitions first, so the tail of the launch is made of short ones
+  std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
+  for (auto& t : tiles) c->ptiles.push_back(t.t);
+  n_parts_out = n_parts;
+  if (prefill_split_out) {
+    *prefill_split_out = 0;
+    for (auto& t : c->ptiles)
+      if (t.part >= 0) *prefill_split_out = std::max<int64_t>(*prefill_split_out, t.tile_end - t.tile_begin);
+  }
+  return PS_OK;
+}
+
 // The launches of one step over the batch description that c->last points to: prologue (upload of
 // `upload_bytes` from the pinned slot `h`, if any, and the append of the new K/V rows), attention,
 // merge.
@@ -700,82 +799,11 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   const int64_t n_table = b->bt_start[n_req];
 
   // ---- work lists
-  const int TT = ps::prefill_tile_tokens(c->G);
-  c->plan.ditems.clear();
-  c->plan.dslots.assign(1, 0);
-  c->plan.mitems.clear();
-  c->ptiles.clear();
-  c->aitems.clear();
   int n_parts = 0;
-  std::vector<TileKey> tiles;
-  std::vector<int> decode_reqs;
-  for (int r = 0; r < n_req; ++r) {
-    const int qs = b->q_start[r], lq = b->q_start[r + 1] - qs, L = b->kv_len[r];
-    if (k_new)
-      for (int lb = (L - lq) / ps::kBlockTokens; lb * ps::kBlockTokens < L; ++lb) {
-        const int b0 = lb * ps::kBlockTokens;
-        const int lo = std::max(L - lq, b0), hi = std::min(L, b0 + ps::kBlockTokens);  // new positions in this block
-        c->aitems.push_back(ps::AppendItem{b->block_ids[b->bt_start[r] + lb], qs + lo - (L - lq), lo - b0, hi - lo});
-      }
-    if (lq == 1) {
-      decode_reqs.push_back(r);
-    } else {
-      const int p = L - lq;
-      for (int q0 = 0; q0 < lq; q0 += TT) {
-        const int last = std::min(q0 + TT, lq) - 1;  // KV tiles (64 tokens) any query of the tile can see
-        tiles.push_back(TileKey{(p + last) / 64 + 1, ps::PrefillTile{r, q0, 0, 0, -1, 1, 0, 0}});
-      }
-    }
-  }
-  const double prefill_steps = plan_prefill(c, b, tiles, TT, workspace_bytes, n_parts);
-
-  // Decode slots.  With prefill work in the same launch the decode workgroups get the share of the
-  // CUs that makes both kinds of work end together (each priced at its full-chip speed: 6.3 TB/s
-  // for the cache stream, 1.92 us per KV tile step of a prefill workgroup; the decode share is cut
-  // by 5 %: prefill workgroups inherit CUs that decode leaves early, never the other way round).
   {
-    int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
-    if (c->cfg.decode_waves == 0 && c->profiling != 2 && !decode_reqs.empty() && !tiles.empty()) {
-      const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / 6.3e6;  // us
-      const double t_p = prefill_steps * 1.92;
-      const int lo = std::min(8, c->n_cus), hi = c->n_cus - 8;
-      int cus = (int)(0.95 * c->n_cus * t_d / (t_d + t_p));
-      cus = std::max(lo, std::min(cus, hi));
-      // Few, equally long prefill workgroups (one long chunk that outweighs the decode work) pack badly
-      // next to a small decode share:
-      // they run in rounds, and the decode units come free in the middle of one.  Larger shares are
-      // priced too: the decode workgroups on n units last t_d stretched by 176/n below 176 units
-      // (above, HBM is the limit) and by 5 % for the prefill traffic next to them; the launch ends when
-      // the prefill workgroups, handed to whichever unit is free next, are through.  A larger share
-      // wins only if it ends the launch 2 % sooner.
-      const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
-      if (t_p > t_d && tiles.size() * (size_t)wg_per_tile <= 1024) {
-        std::vector<TileKey> sorted(tiles);
-        std::stable_sort(sorted.begin(), sorted.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
-        std::vector<double> bins;
-        auto ends = [&](int n) {
-          const double d = t_d / 1.92 * 1.05 * std::max(1.0, 176.0 / n);
-          return mixed_makespan(sorted, wg_per_tile, c->n_cus, n, d, bins);
-        };
-        double best = ends(cus);
-        for (int n = std::max(128, (cus / 32 + 1) * 32); n <= hi; n += 32) {
-          const double e = ends(n);
-          if (e < 0.98 * best) {
-            best = e;
-            cus = n;
-          }
-        }
-      }
-      waves = ps::decode_waves_per_wg() * cus;
-    }
-    build_decode_slots(&c->plan, c->cfg.n_kv_heads, c->cfg.decode_chunk, b, decode_reqs, n_parts, waves);
-    if (!decode_slots_ok(&c->plan, b, decode_reqs, c->cover))
-      return fail(PS_ESTATE, "ps_step: inconsistent decode work list (library bug)");
+    int rc = plan_batch(c, b, k_new != nullptr, workspace_bytes, decode_kv, n_parts, nullptr);
+    if (rc != PS_OK) return rc;
   }
-
-  // heaviest partitions first, so the tail of the launch is made of short ones
-  std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
-  for (auto& t : tiles) c->ptiles.push_back(t.t);
 
   const MetaLayout ml = meta_layout(n_req, c->aitems.size(), n_table, c->plan.ditems.size(), c->plan.dslots.size(),
                                      c->plan.mitems.size(), c->ptiles.size());
@@ -874,6 +902,42 @@ int ps_step_next_layer(ps_ctx* c, const void* q, const void* k_new, const void* 
   const char* w = c->meta[c->last.meta].dev;
   return launch_phases(c, nullptr, 0, (const ps::AppendItem*)(w + c->last.off[4]), q, k_new, v_new, kv_cache, out, workspace,
                        stream);
+}
+
+int ps_plan_launch(const ps_layer_cfg* cfg, const ps_batch* b, int32_t n_cus, int32_t* out6) {
+  if (!cfg || !b || !out6) return fail(PS_EINVAL, "ps_plan_launch: NULL argument");
+  for (int i = 0; i < 6; ++i) out6[i] = 0;
+  {
+    int rc = check_cfg(cfg);
+    if (rc != PS_OK) return rc;
+  }
+  if (n_cus < 1 || n_cus > 65536) return fail(PS_EINVAL, "ps_plan_launch: n_cus must be in [1, 65536]");
+  if (b->n_req < 0 || b->n_tokens < 0) return fail(PS_EINVAL, "negative n_req / n_tokens");
+  if (b->n_req == 0) return b->n_tokens == 0 ? PS_OK : fail(PS_EINVAL, "n_tokens != 0 with n_req == 0");
+  if (!b->q_start || !b->kv_len || !b->bt_start || !b->block_ids) return fail(PS_EINVAL, "ps_plan_launch: NULL batch array");
+  int64_t decode_kv = 0;
+  {
+    int rc = check_batch(b, cfg->n_device_blocks, &decode_kv);
+    if (rc != PS_OK) return rc;
+  }
+  ps_ctx c;  // host fields only: nothing of the device is created or touched
+  c.cfg = *cfg;
+  c.G = cfg->n_q_heads / cfg->n_kv_heads;
+  c.block_bytes = (size_t)2 * cfg->n_kv_heads * ps::kSliceElems * 2;
+  c.n_cus = n_cus;
+  int n_parts = 0;
+  int64_t split = 0;
+  int rc = plan_batch(&c, b, false, (size_t)1 << 62, decode_kv, n_parts, &split);
+  if (rc != PS_OK) return rc;
+  const int n_slots = (int)c.plan.dslots.size() - 1;
+  const int dw = ps::decode_waves_per_wg();
+  out6[0] = n_slots * cfg->n_kv_heads;
+  out6[1] = n_slots;
+  out6[2] = n_slots > 0 ? (n_slots + dw - 1) / dw * cfg->n_kv_heads : 0;
+  out6[3] = (int32_t)c.ptiles.size() * cfg->n_kv_heads * (c.G / ps::prefill_heads_per_wg(c.G));
+  out6[4] = (int32_t)split;
+  out6[5] = n_parts;
+  return PS_OK;
 }
 
 static int swap_common(ps_ctx* c, bool out_dir, const int32_t* dev_ids, const int32_t* host_ids, int32_t n,

@@ -1,0 +1,96 @@
+"""Host logic of the mixed attention launch (no GPU): how many compute units the decode workgroups of a batch
+get next to its prefill workgroups, and when prefill rows are split along their KV range.  Checked through
+ps_plan_launch on the benchmark workloads and on seeded random batches."""
+import numpy as np
+import pytest
+
+from paper_2512_12928_amd import binding as B
+from paper_2512_12928_amd import workloads as W
+
+
+def plan(b, n_cus=256, **kw):
+    s = b.shape
+    return B.ps_plan_launch(s.n_q_heads, s.n_kv_heads, b.n_device_blocks, b, n_cus, **kw)
+
+
+def decode_tiles(b):
+    return int(sum(-(-int(b.kv_len[r]) // 32) for r in b.decode_reqs))
+
+
+def test_decode_only_batch_gets_one_wave_per_simd():
+    b = W.build_batch(W.LayerShape(32, 8), [(1, 4000)] * 300, [1] * 300, np.random.default_rng(1), seed=1)
+    p = plan(b)
+    assert p["decode_waves"] == 1024 and p["decode_slots"] == 128 and p["decode_workgroups"] == 256
+    assert p["prefill_workgroups"] == 0 and p["prefill_split_tiles"] == 0
+    p = plan(b, n_cus=64)
+    assert p["decode_waves"] == 256 and p["decode_workgroups"] == 64
+    p = plan(b, decode_waves=512)
+    assert p["decode_waves"] == 512
+
+
+def test_prefill_only_batch_has_no_decode_workgroups():
+    b = W.build_batch(W.LayerShape(32, 8), [(512, 512), (256, 4096)], [1, 1], np.random.default_rng(2), seed=2)
+    p = plan(b, prefill_split_tiles=-1)
+    assert p["decode_workgroups"] == 0 and p["decode_waves"] == 0
+    # 64-token query tiles for four heads per kv-head: (8 + 4) tiles x 8 kv-heads
+    assert p["prefill_workgroups"] == 12 * 8 and p["partial_slots"] == 0
+
+
+def test_shares_of_the_benchmark_workloads():
+    """Decode-heavy batch: the share at which both kinds of work end together, a little under t_d / (t_d + t_p)
+    of the chip.  One long chunk of equally long workgroups that outweighs the decode work: decode gets most
+    of the chip first and leaves it to the prefill workgroups.  Many prefill workgroups of all lengths next to
+    moderate decode work: the proportional share again."""
+    p2, p4, p5 = plan(W.make_workload(2)), plan(W.make_workload(4)), plan(W.make_workload(5))
+    assert 170 <= p2["decode_workgroups"] <= 200 and p2["prefill_split_tiles"] > 0      # 64-tile rows cut in two
+    assert 160 <= p4["decode_workgroups"] <= 248 and p4["prefill_workgroups"] == 512 and p4["prefill_split_tiles"] == 0
+    assert 64 <= p5["decode_workgroups"] <= 128 and p5["prefill_workgroups"] == 2048
+    for p in (p2, p4, p5):
+        assert p["decode_waves"] == p["decode_slots"] * 8
+        assert p["decode_workgroups"] == -(-p["decode_slots"] // 4) * 8
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches_keep_the_launch_within_bounds(seed):
+    rng = np.random.default_rng(9000 + seed)
+    Hq, Hkv = [(32, 8), (64, 8), (8, 2), (16, 1)][seed % 4]
+    n_cus = [256, 128, 304, 64][seed % 4]
+    items = [(1, int(rng.integers(1, 20000))) for _ in range(int(rng.integers(0, 200)))]
+    n_pre = int(rng.integers(0 if items else 1, 5))
+    for _ in range(n_pre):
+        lq = int(rng.integers(2, 3000))
+        items.append((lq, lq + int(rng.integers(0, 20000))))
+    b = W.build_batch(W.LayerShape(Hq, Hkv), items, [1] * len(items), rng, seed=seed)
+    p = plan(b, n_cus)
+    n_dec, T = len(b.decode_reqs), decode_tiles(b)
+    assert (p["decode_slots"] > 0) == (n_dec > 0)
+    if n_dec:
+        assert p["decode_slots"] <= max(1, T // 4)                     # no slot shorter than four tiles
+        assert p["decode_waves"] <= 4 * n_cus                           # never more than one wave per SIMD
+        if n_pre:                                                       # prefill keeps at least 8 compute units
+            assert p["decode_waves"] <= 4 * max(8, n_cus - 8)
+    G = Hq // Hkv
+    hw = 8 if G % 8 == 0 else 4 if G % 4 == 0 else 2 if G % 2 == 0 else 1
+    tt = (8 // hw) * 32
+    tiles = sum(-(-b.l_q(int(r)) // tt) for r in b.prefill_reqs)
+    assert p["prefill_workgroups"] >= tiles * Hkv * (G // hw)          # more only when rows are split
+    assert (p["prefill_workgroups"] > tiles * Hkv * (G // hw)) == (p["prefill_split_tiles"] > 0)
+    # partial slots: cut decode requests (at most one cut per slot boundary) and split prefill rows
+    assert p["partial_slots"] >= 0
+    if p["prefill_split_tiles"] == 0:
+        assert p["partial_slots"] <= 2 * max(0, p["decode_slots"] - 1)
+    # the plan is a function of the batch alone
+    assert plan(b, n_cus) == p
+
+
+def test_bad_arguments():
+    b = W.make_workload(1)
+    with pytest.raises(B.PsError):
+        plan(b, n_cus=0)
+    with pytest.raises(B.PsError):
+        B.ps_plan_launch(8, 3, 64, b)                                   # Hq not a multiple of Hkv
+    bad = W.make_workload(1)
+    bad.kv_len = bad.kv_len.copy()
+    bad.kv_len[0] += 100
+    with pytest.raises(B.PsError):
+        plan(bad)
