@@ -612,7 +612,6 @@ static int find_ticket(ps_ctx* c, uint64_t ticket, hipEvent_t* ev, bool* done) {
 static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t workspace_bytes, int64_t decode_kv,
                       int& n_parts_out, int64_t* prefill_split_out) {
   const int n_req = b->n_req;
-  // ---- work lists
   const int TT = ps::prefill_tile_tokens(c->G);
   c->plan.ditems.clear();
   c->plan.dslots.assign(1, 0);
