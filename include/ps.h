@@ -239,8 +239,12 @@ typedef struct {
   int64_t rho_num, rho_den;     /* a request that waited >= rho*tau is never an eviction victim */
   int64_t t_block_ps;       /* profiled copy time of one block (Sec. 4.3)                     */
   int32_t n_off_base;       /* offload threshold n_off of class 1; halves per class, floor 1  */
-  int32_t reserved;
+  int32_t order_policy;     /* PS_ORDER_SLIDEBATCHING (0): Alg. 1 line 13 with the starvation rule;
+                               PS_ORDER_FCFS: arrival order only, the first-come-first-served arm
+                               of the comparisons in Sec. 5 (everything else of the round as is)   */
 } ps_sched_cfg;
+
+enum { PS_ORDER_SLIDEBATCHING = 0, PS_ORDER_FCFS = 1 };
 
 /* Result of one scheduling round. Every pointer refers to memory owned by the scheduler and
  * stays valid until the next call on the same ps_sched. `batch` can be handed to ps_step as is:
@@ -267,6 +271,9 @@ typedef struct {
   const int32_t* emitted_index;      /* ... and 1-based token index                          */
   int32_t n_finished, reserved;
   const int64_t* finished;           /* requests that delivered their last token             */
+  int64_t round;                     /* 1-based count of ps_form_batch calls on this scheduler:
+                                        names the offload list of this round towards
+                                        ps_sched_offloads_done                                */
 } ps_batch_out;
 
 /* dev_free_order / host_free_order: the block ids of the two pools in the order they are to be
@@ -283,8 +290,52 @@ int ps_sched_add_request(ps_sched* s, int64_t rid, int64_t arrival_ps, int32_t p
  * computes the copy budget, admits requests (evicting from the tail under memory pressure),
  * and applies the round to the state (blocks, computed tokens, delivered tokens, offloads). */
 int ps_form_batch(ps_sched* s, int64_t now_ps, ps_batch_out* out);
+/* Completion report of the offload thread (Sec. 4.3, Asynchronous Offloading): every device-to-host
+ * copy issued by rounds <= upto_round (ps_batch_out.round) has landed, e.g. because ps_ticket_query
+ * says so of that round's ps_swap_out.  Copies on one stream complete in issue order, so a watermark
+ * is enough.  Until a copy is reported its host slot does not count at an eviction: the victim's device
+ * blocks are freed at once, the pending transfer is discarded (its host slot released) and the tokens
+ * it would have covered are recomputed.  Rounds whose offload list is empty need no report.
+ * PS_EINVAL: a round that has not been formed. */
+int ps_sched_offloads_done(ps_sched* s, int64_t upto_round);
 /* Queue and pool occupancy, for tests and monitoring. Any pointer may be NULL. */
 int ps_sched_counts(const ps_sched* s, int32_t* n_queued, int32_t* n_dev_free, int32_t* n_host_free);
+
+/* Eq. 3 for one request of class prio: *gain = sum over the n_times delivered tokens of w_r(i) where
+ * token_times[i-1] (relative to the request's arrival) is strictly before deadline_{r,i} = TTFT_SLO +
+ * (i-1) TPOT_SLO; w_r(1) = w_first * class weight, w_r(i>1) = w_decode * class weight.  *ideal_gain = the
+ * gain of out_len tokens all on time (Ideal_Gain of Sec. 5.1); *slo_attained = 1 iff the first token is
+ * strictly before TTFT_SLO and the mean gap of the later ones strictly below TPOT_SLO (Sec. 5.1, Metrics).
+ * token_times HOST [n_times]; any output pointer may be NULL.  Only the weights and SLOs of cfg are read. */
+int ps_tdg_score(const ps_sched_cfg* cfg, int32_t prio, int32_t out_len, const int64_t* token_times,
+                 int32_t n_times, int64_t* gain, int64_t* ideal_gain, int32_t* slo_attained);
+
+typedef struct {
+  int64_t rid, arrival_ps;
+  int32_t prio, prompt_len, out_len, reserved;
+} ps_trace_req;
+
+typedef struct {
+  int64_t gain, ideal_gain; /* summed over the finished requests (TDG ratio = gain / ideal_gain)   */
+  int32_t slo_attained, finished, steps, reserved;
+  int64_t end_ps;           /* the clock when the run stopped                                      */
+} ps_sim_result;
+
+/* Single-instance serving run on a virtual clock (host only): the requests of `trace` join the queue at
+ * their arrival, every round is one ps_form_batch, the clock advances by its T_pd(B) (Eq. 7; by eta when
+ * nothing could be admitted, to the next arrival when the queue is empty), tokens are delivered when their
+ * batch ends and scored with Eq. 3.  The offload thread of Sec. 4.3 runs on the same clock: the copies a
+ * round issues start when its batch has been computed and the earlier copies are through, take t_block per
+ * block, and are reported (ps_sched_offloads_done) at the first round that starts at or after their end.
+ * Stops after max_steps rounds or when the trace is exhausted.
+ *   trace        HOST [n_trace], any order, distinct ids
+ *   token_times  HOST int64 [sum of out_len], may be NULL: delivery times relative to arrival, request i of
+ *                `trace` at offset sum_{j<i} out_len[j]
+ *   n_delivered  HOST int32 [n_trace], may be NULL: tokens delivered per request
+ * Errors as for ps_sched_create / ps_sched_add_request. */
+int ps_sched_simulate(const ps_sched_cfg* cfg, const int32_t* dev_free_order, int32_t n_dev,
+                      const int32_t* host_free_order, int32_t n_host, const ps_trace_req* trace, int32_t n_trace,
+                      int32_t max_steps, int64_t* token_times, int32_t* n_delivered, ps_sim_result* out);
 
 #ifdef __cplusplus
 }

@@ -83,6 +83,8 @@ class SchedConfig:
     t_block: int = 1
     block_tokens: int = 16
     n_off_base: int = 8                # offload threshold of class 1; halves per class, floor 1
+    order_policy: int = 0              # 0: Alg. 1 line 13 + starvation rule; 1: arrival order only (the
+                                       # first-come-first-served arm the paper compares against, Sec. 5)
 
     def n_off(self, prio: int) -> int:
         return max(1, self.n_off_base >> (prio - 1))
@@ -152,7 +154,8 @@ class Request:
     generated: int = 0                 # output tokens delivered
     last_sched: int = 0
     dev_blocks: List[int] = field(default_factory=list)     # logical order
-    host_slots: List[int] = field(default_factory=list)     # host copies of logical blocks 0..n-1
+    host_slots: List[int] = field(default_factory=list)     # host copies of logical blocks 0..n-1 (issued)
+    host_round: List[int] = field(default_factory=list)     # scheduling round that issued each of them
     token_times: List[int] = field(default_factory=list)    # relative to arrival
 
     @property
@@ -169,6 +172,7 @@ class Request:
 @dataclass
 class StepResult:
     now: int
+    round: int = 0                                     # 1-based count of form_batch calls; names this round's offloads
     t_budget: int = 0
     phi: int = 0
     b_copy: int = 0
@@ -181,6 +185,7 @@ class StepResult:
     swap_in: List[Tuple[int, int]] = field(default_factory=list)     # (host_slot, dev_block)
     swap_out: List[Tuple[int, int]] = field(default_factory=list)    # (dev_block, host_slot)
     evicted: List[int] = field(default_factory=list)
+    dropped_pending: int = 0                           # host copies still in flight that evictions discarded
     emitted: List[Tuple[int, int]] = field(default_factory=list)     # (rid, token index)
     finished: List[int] = field(default_factory=list)
 
@@ -200,6 +205,21 @@ class SlideBatcher:
         self.n_host = len(self.host_free)
         self.reqs: Dict[int, Request] = {}
         self.finished_requests: Dict[int, Request] = {}
+        self.round = 0                 # scheduling rounds so far
+        self.offloads_done_upto = 0    # every offload issued in a round <= this has completed
+
+    # -- Sec. 4.3 "Asynchronous Offloading": the copy thread reports completion
+    def offloads_done(self, upto_round: int) -> None:
+        """The device-to-host copies issued by rounds <= upto_round have all landed (copies on the
+        offload stream complete in issue order, so a watermark is enough)."""
+        self.offloads_done_upto = max(self.offloads_done_upto, int(upto_round))
+
+    def confirmed(self, r: Request) -> int:
+        """Leading host copies of r whose transfer is known to be complete."""
+        n = 0
+        while n < len(r.host_round) and r.host_round[n] <= self.offloads_done_upto:
+            n += 1
+        return n
 
     # -- queue
     def add_request(self, rid: int, arrival: int, prio: int, prompt_len: int, out_len: int) -> None:
@@ -221,17 +241,27 @@ class SlideBatcher:
         return ex, remain, w
 
     def _evict(self, v: Request, res: StepResult) -> None:
-        """Free every device block of v.  Host copies stay; tokens without a host copy are
-        dropped and will be recomputed (Sec. 4.3: evict directly, discard pending transfer)."""
+        """Free every device block of v at once (Sec. 4.3, Asynchronous Offloading: evict directly
+        and discard the pending transfer, no on-demand synchronisation).  Host copies whose transfer
+        has completed stay; a copy still in flight is discarded (its host slot is released, in
+        logical order) and the tokens it would have covered, like those never offloaded, are
+        recomputed."""
         for b in v.dev_blocks:
             self.dev_free.append(b)
         v.dev_blocks = []
-        v.computed = min(v.computed, len(v.host_slots) * self.cfg.block_tokens)
+        conf = self.confirmed(v)
+        for s in v.host_slots[conf:]:
+            self.host_free.append(s)
+        res.dropped_pending += len(v.host_slots) - conf
+        v.host_slots = v.host_slots[:conf]
+        v.host_round = v.host_round[:conf]
+        v.computed = min(v.computed, conf * self.cfg.block_tokens)
         res.evicted.append(v.rid)
 
     def form_batch(self, now: int) -> StepResult:
         cfg, blk = self.cfg, self.cfg.block_tokens
-        res = StepResult(now=now)
+        self.round += 1
+        res = StepResult(now=now, round=self.round)
         Q = [r for r in self.reqs.values() if r.arrival <= now]
         if not Q:
             return res
@@ -254,6 +284,8 @@ class SlideBatcher:
         nor = [r for r in Q if r.rid not in urgent and r.rid not in st_ids]
         nor.sort(key=lambda r: (met[r.rid][1], r.arrival, r.rid))
         order = starving + urg + nor
+        if cfg.order_policy == 1:
+            order = sorted(Q, key=lambda r: (r.arrival, r.rid))
         # line 14
         t_fwd_min = cfg.t_c + sum_exec
         b_missing = sum(r.b_miss for r in Q)
@@ -324,6 +356,7 @@ class SlideBatcher:
                 for s in r.host_slots[k:]:
                     self.host_free.append(s)
                 r.host_slots = r.host_slots[:k]
+                r.host_round = r.host_round[:k]
                 r.dev_blocks = new_dev
                 r.computed = comp
                 b_rem -= k
@@ -353,7 +386,7 @@ class SlideBatcher:
                         self.dev_free.append(b)
                     for s in r.host_slots:
                         self.host_free.append(s)
-                    r.dev_blocks, r.host_slots = [], []
+                    r.dev_blocks, r.host_slots, r.host_round = [], [], []
                     res.finished.append(r.rid)
         for rid in res.finished:
             self.finished_requests[rid] = self.reqs.pop(rid)
@@ -367,6 +400,7 @@ class SlideBatcher:
                 for b in range(len(r.host_slots), full):
                     s = self.host_free.pop()
                     r.host_slots.append(s)
+                    r.host_round.append(self.round)
                     res.swap_out.append((r.dev_blocks[b], s))
         return res
 
@@ -375,12 +409,18 @@ class SlideBatcher:
 def simulate(cfg: SchedConfig, trace, dev_free_order, host_free_order, max_steps: int,
              on_step=None):
     """Virtual-clock run: requests join the queue at their arrival; the clock advances by
-    T_pd(B) per step, or jumps to the next arrival when the queue is empty."""
+    T_pd(B) per step, or jumps to the next arrival when the queue is empty.  The offload thread
+    is modelled on the same clock: the copies a round issues start when its batch has been
+    computed and the earlier copies are through, take t_block per block (the paper profiles
+    one per-block copy time), and are reported complete at the first round that starts at or
+    after their end."""
     sb = SlideBatcher(cfg, dev_free_order, host_free_order)
     pending = sorted(trace, key=lambda x: (x.arrival_ps, x.rid))
     nxt = 0
     now = 0
     steps: List[StepResult] = []
+    inflight: List[Tuple[int, int]] = []      # (round, completion time) of offload lists, oldest first
+    copy_free_at = 0
     while len(steps) < max_steps:
         while nxt < len(pending) and pending[nxt].arrival_ps <= now:
             p = pending[nxt]
@@ -391,8 +431,13 @@ def simulate(cfg: SchedConfig, trace, dev_free_order, host_free_order, max_steps
                 break
             now = pending[nxt].arrival_ps
             continue
+        while inflight and inflight[0][1] <= now:
+            sb.offloads_done(inflight.pop(0)[0])
         res = sb.form_batch(now)
         steps.append(res)
+        if res.swap_out:
+            copy_free_at = max(copy_free_at, now + res.t_batch) + len(res.swap_out) * cfg.t_block
+            inflight.append((res.round, copy_free_at))
         if on_step is not None:
             on_step(sb, res)
         now += res.t_batch if res.t_batch > 0 else cfg.eta

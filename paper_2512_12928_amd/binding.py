@@ -25,6 +25,7 @@ EXPORTS = [
     "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_step_next_layer", "ps_set_profiling",
     "ps_get_step_times", "ps_plan_decode", "ps_plan_launch", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
     "ps_sched_create", "ps_sched_destroy", "ps_sched_add_request", "ps_form_batch", "ps_sched_counts",
+    "ps_sched_offloads_done", "ps_tdg_score", "ps_sched_simulate",
 ]
 
 
@@ -54,7 +55,20 @@ class ps_sched_cfg(C.Structure):
                 ("a_d", C.c_int64), ("b_d", C.c_int64), ("t_c", C.c_int64), ("eta_ps", C.c_int64),
                 ("tau_ps", C.c_int64), ("gamma_num", C.c_int64), ("gamma_den", C.c_int64),
                 ("beta_num", C.c_int64), ("beta_den", C.c_int64), ("rho_num", C.c_int64), ("rho_den", C.c_int64),
-                ("t_block_ps", C.c_int64), ("n_off_base", C.c_int32), ("reserved", C.c_int32)]
+                ("t_block_ps", C.c_int64), ("n_off_base", C.c_int32), ("order_policy", C.c_int32)]
+
+
+PS_ORDER_SLIDEBATCHING, PS_ORDER_FCFS = 0, 1
+
+
+class ps_trace_req(C.Structure):
+    _fields_ = [("rid", C.c_int64), ("arrival_ps", C.c_int64), ("prio", C.c_int32), ("prompt_len", C.c_int32),
+                ("out_len", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ps_sim_result(C.Structure):
+    _fields_ = [("gain", C.c_int64), ("ideal_gain", C.c_int64), ("slo_attained", C.c_int32), ("finished", C.c_int32),
+                ("steps", C.c_int32), ("reserved", C.c_int32), ("end_ps", C.c_int64)]
 
 
 class ps_batch_out(C.Structure):
@@ -66,7 +80,8 @@ class ps_batch_out(C.Structure):
                 ("swap_out_dev_blocks", C.POINTER(C.c_int32)), ("swap_out_host_slots", C.POINTER(C.c_int32)),
                 ("n_evicted", C.c_int32), ("n_emitted", C.c_int32), ("evicted", C.POINTER(C.c_int64)),
                 ("emitted_req", C.POINTER(C.c_int64)), ("emitted_index", C.POINTER(C.c_int32)),
-                ("n_finished", C.c_int32), ("reserved", C.c_int32), ("finished", C.POINTER(C.c_int64))]
+                ("n_finished", C.c_int32), ("reserved", C.c_int32), ("finished", C.POINTER(C.c_int64)),
+                ("round", C.c_int64)]
 
 
 class PsError(RuntimeError):
@@ -108,6 +123,12 @@ def lib():
         L.ps_sched_add_request.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32]
         L.ps_form_batch.argtypes = [C.c_void_p, C.c_int64, C.POINTER(ps_batch_out)]
         L.ps_sched_counts.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 3
+        L.ps_sched_offloads_done.argtypes = [C.c_void_p, C.c_int64]
+        L.ps_tdg_score.argtypes = [C.POINTER(ps_sched_cfg), C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.c_int32,
+                                   C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
+        L.ps_sched_simulate.argtypes = [C.POINTER(ps_sched_cfg), C.POINTER(C.c_int32), C.c_int32, C.POINTER(C.c_int32),
+                                        C.c_int32, C.POINTER(ps_trace_req), C.c_int32, C.c_int32, C.POINTER(C.c_int64),
+                                        C.POINTER(C.c_int32), C.POINTER(ps_sim_result)]
         _lib = L
     return _lib
 
@@ -277,8 +298,7 @@ def ps_ticket_wait(ctx: int, ticket: int) -> None:
 
 
 # ---------------------------------------------------------------------------- batch former
-def ps_sched_create(cfg: dict, dev_free_order, host_free_order) -> int:
-    """cfg: field name -> integer for ps_sched_cfg (class_weight as a list)."""
+def _sched_cfg(cfg: dict) -> ps_sched_cfg:
     c = ps_sched_cfg()
     for k, v in cfg.items():
         if k == "class_weight":
@@ -286,6 +306,42 @@ def ps_sched_create(cfg: dict, dev_free_order, host_free_order) -> int:
                 c.class_weight[i] = int(w)
         else:
             setattr(c, k, int(v))
+    return c
+
+
+def ps_tdg_score(cfg: dict, prio: int, out_len: int, token_times) -> Tuple[int, int, int]:
+    """(gain, ideal gain, SLO attained) of one request; token_times relative to its arrival."""
+    c = _sched_cfg(cfg)
+    t = np.ascontiguousarray(token_times, dtype=np.int64)
+    g, ideal, ok = C.c_int64(), C.c_int64(), C.c_int32()
+    _check(lib().ps_tdg_score(C.byref(c), prio, out_len, t.ctypes.data_as(C.POINTER(C.c_int64)), len(t), C.byref(g),
+                              C.byref(ideal), C.byref(ok)))
+    return g.value, ideal.value, ok.value
+
+
+def ps_sched_simulate(cfg: dict, dev_free_order, host_free_order, trace, max_steps: int) -> dict:
+    """trace: objects with rid, arrival_ps, prio, prompt_len, out_len.  Returns the ps_sim_result fields plus
+    token_times (one int64 array per request, in the order of `trace`)."""
+    c = _sched_cfg(cfg)
+    d, h = _i32(dev_free_order), _i32(host_free_order)
+    tr = (ps_trace_req * max(len(trace), 1))()
+    for i, p in enumerate(trace):
+        tr[i] = ps_trace_req(p.rid, p.arrival_ps, p.prio, p.prompt_len, p.out_len, 0)
+    offs = np.zeros(len(trace) + 1, dtype=np.int64)
+    offs[1:] = np.cumsum([p.out_len for p in trace])
+    times = np.zeros(max(int(offs[-1]), 1), dtype=np.int64)
+    counts = np.zeros(max(len(trace), 1), dtype=np.int32)
+    out = ps_sim_result()
+    _check(lib().ps_sched_simulate(C.byref(c), _i32p(d), len(d), _i32p(h), len(h), tr, len(trace), max_steps,
+                                   times.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(counts), C.byref(out)))
+    res = {n: getattr(out, n) for n, _ in ps_sim_result._fields_ if n != "reserved"}
+    res["token_times"] = [times[offs[i]:offs[i] + counts[i]].copy() for i in range(len(trace))]
+    return res
+
+
+def ps_sched_create(cfg: dict, dev_free_order, host_free_order) -> int:
+    """cfg: field name -> integer for ps_sched_cfg (class_weight as a list)."""
+    c = _sched_cfg(cfg)
     d, h = _i32(dev_free_order), _i32(host_free_order)
     out = C.c_void_p()
     _check(lib().ps_sched_create(C.byref(c), _i32p(d), len(d), _i32p(h), len(h), C.byref(out)))
@@ -304,6 +360,10 @@ def ps_sched_counts(s: int) -> Tuple[int, int, int]:
     a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
     _check(lib().ps_sched_counts(s, C.byref(a), C.byref(b), C.byref(c)))
     return a.value, b.value, c.value
+
+
+def ps_sched_offloads_done(s: int, upto_round: int) -> None:
+    _check(lib().ps_sched_offloads_done(s, upto_round))
 
 
 def ps_form_batch(s: int, now_ps: int) -> dict:
@@ -327,4 +387,5 @@ def ps_form_batch(s: int, now_ps: int) -> dict:
         swap_out_dev_blocks=arr(o.swap_out_dev_blocks, o.n_swap_out, np.int32),
         swap_out_host_slots=arr(o.swap_out_host_slots, o.n_swap_out, np.int32),
         evicted=arr(o.evicted, o.n_evicted, np.int64), emitted_req=arr(o.emitted_req, o.n_emitted, np.int64),
-        emitted_index=arr(o.emitted_index, o.n_emitted, np.int32), finished=arr(o.finished, o.n_finished, np.int64))
+        emitted_index=arr(o.emitted_index, o.n_emitted, np.int32), finished=arr(o.finished, o.n_finished, np.int64),
+        round=o.round)

@@ -27,7 +27,8 @@ struct Req {
   int64_t generated = 0;  // output tokens delivered
   int64_t last_sched = 0;
   std::vector<int32_t> dev_blocks;  // logical order
-  std::vector<int32_t> host_slots;  // host copies of logical blocks 0..n-1
+  std::vector<int32_t> host_slots;  // host copies of logical blocks 0..n-1 (issued, maybe still in flight)
+  std::vector<int64_t> host_round;  // the scheduling round that issued each of them
   // per-round scratch
   int64_t exec = 0, remain = 0, weight = 0;
   bool urgent = false, starving = false, in_batch = false, evicted_now = false;
@@ -46,6 +47,8 @@ struct ps_sched {
   std::vector<int32_t> dev_free, host_free;  // LIFO: back() is handed out next
   std::unordered_map<int64_t, Req*> by_id;
   std::vector<Req*> reqs;  // active requests
+  int64_t round = 0;        // ps_form_batch calls so far
+  int64_t done_upto = 0;    // offloads issued in rounds <= this have completed (ps_sched_offloads_done)
   // result storage
   std::vector<int32_t> q_start, kv_len, bt_start, block_ids, si_host, si_dev, so_dev, so_host, emitted_index;
   std::vector<uint8_t> prio;
@@ -122,6 +125,8 @@ int ps_sched_create(const ps_sched_cfg* cfg, const int32_t* dev_free_order, int3
       cfg->rho_num < 0)
     return sched_fail(PS_EINVAL, "gamma / beta / rho must be non-negative fractions with positive denominators");
   if (cfg->t_block_ps <= 0) return sched_fail(PS_EINVAL, "t_block must be positive");
+  if (cfg->order_policy != PS_ORDER_SLIDEBATCHING && cfg->order_policy != PS_ORDER_FCFS)
+    return sched_fail(PS_EINVAL, "order_policy must be PS_ORDER_SLIDEBATCHING or PS_ORDER_FCFS");
   if (cfg->a_p < 0 || cfg->b_p < 0 || cfg->c_p < 0 || cfg->a_d < 0 || cfg->b_d < 0 || cfg->t_c < 0)
     return sched_fail(PS_EINVAL, "estimator coefficients must be non-negative");
   if (n_dev < 0 || n_host < 0 || (n_dev > 0 && !dev_free_order) || (n_host > 0 && !host_free_order))
@@ -178,8 +183,16 @@ int ps_sched_counts(const ps_sched* s, int32_t* n_queued, int32_t* n_dev_free, i
   return PS_OK;
 }
 
+int ps_sched_offloads_done(ps_sched* s, int64_t upto_round) {
+  if (!s) return sched_fail(PS_EINVAL, "NULL scheduler");
+  if (upto_round > s->round) return sched_fail(PS_EINVAL, "round %lld has not been formed yet", (long long)upto_round);
+  if (upto_round > s->done_upto) s->done_upto = upto_round;
+  return PS_OK;
+}
+
 int ps_form_batch(ps_sched* s, int64_t now, ps_batch_out* out) {
   if (!s || !out) return sched_fail(PS_EINVAL, "ps_form_batch: NULL argument");
+  s->round += 1;
   const ps_sched_cfg& c = s->cfg;
   const int64_t blk = c.block_tokens;
   for (auto* v : {&s->q_start, &s->kv_len, &s->bt_start, &s->block_ids, &s->si_host, &s->si_dev, &s->so_dev,
@@ -221,7 +234,8 @@ int ps_form_batch(ps_sched* s, int64_t now, ps_batch_out* out) {
     }
     // line 13 and the starvation rule: starving (longest wait first), URGENT by density
     // descending, NORMAL by remaining time ascending; ties by arrival, then id
-    auto group = [](const Req* r) { return r->starving ? 0 : (r->urgent ? 1 : 2); };
+    const bool fcfs = c.order_policy == PS_ORDER_FCFS;  // comparison arm: arrival order, nothing else
+    auto group = [&](const Req* r) { return fcfs ? 3 : (r->starving ? 0 : (r->urgent ? 1 : 2)); };
     std::sort(Q.begin(), Q.end(), [&](const Req* a, const Req* b) {
       const int ga = group(a), gb = group(b);
       if (ga != gb) return ga < gb;
@@ -232,7 +246,7 @@ int ps_form_batch(ps_sched* s, int64_t now, ps_batch_out* out) {
         const i128 da = (i128)a->weight * std::max<int64_t>(b->exec, 1);  // a.w/a.exec vs b.w/b.exec
         const i128 db = (i128)b->weight * std::max<int64_t>(a->exec, 1);
         if (da != db) return da > db;
-      } else {
+      } else if (ga == 2) {
         if (a->remain != b->remain) return a->remain < b->remain;
       }
       if (a->arrival != b->arrival) return a->arrival < b->arrival;
@@ -284,7 +298,14 @@ int ps_form_batch(ps_sched* s, int64_t now, ps_batch_out* out) {
           if ((i128)(now - v->last_sched) * c.rho_den >= (i128)c.rho_num * c.tau_ps) continue;
           for (int32_t b : v->dev_blocks) s->dev_free.push_back(b);
           v->dev_blocks.clear();
-          v->computed = std::min<int64_t>(v->computed, (int64_t)v->host_slots.size() * blk);
+          // host copies still in flight are discarded with the eviction (Sec. 4.3, Asynchronous
+          // Offloading): only completed ones keep their tokens from being recomputed
+          size_t conf = 0;
+          while (conf < v->host_round.size() && v->host_round[conf] <= s->done_upto) ++conf;
+          for (size_t b = conf; b < v->host_slots.size(); ++b) s->host_free.push_back(v->host_slots[b]);
+          v->host_slots.resize(conf);
+          v->host_round.resize(conf);
+          v->computed = std::min<int64_t>(v->computed, (int64_t)conf * blk);
           v->evicted_now = true;
           s->evicted.push_back(v->rid);
         }
@@ -309,6 +330,7 @@ int ps_form_batch(ps_sched* s, int64_t now, ps_batch_out* out) {
         }
         for (size_t b = (size_t)k; b < r->host_slots.size(); ++b) s->host_free.push_back(r->host_slots[b]);
         r->host_slots.resize((size_t)k);
+        r->host_round.resize((size_t)k);
         r->dev_blocks = fresh;
         r->computed = comp;
         b_rem -= k;
@@ -352,6 +374,7 @@ int ps_form_batch(ps_sched* s, int64_t now, ps_batch_out* out) {
       for (int32_t h : r->host_slots) s->host_free.push_back(h);
       r->dev_blocks.clear();
       r->host_slots.clear();
+      r->host_round.clear();
       s->finished.push_back(r->rid);
     }
   }
@@ -368,6 +391,7 @@ int ps_form_batch(ps_sched* s, int64_t now, ps_batch_out* out) {
         const int32_t h = s->host_free.back();
         s->host_free.pop_back();
         r->host_slots.push_back(h);
+        r->host_round.push_back(s->round);
         s->so_dev.push_back(r->dev_blocks[(size_t)b]);
         s->so_host.push_back(h);
       }
@@ -409,6 +433,124 @@ int ps_form_batch(ps_sched* s, int64_t now, ps_batch_out* out) {
   out->emitted_index = s->emitted_index.data();
   out->n_finished = (int32_t)s->finished.size();
   out->finished = s->finished.data();
+  out->round = s->round;
+  return PS_OK;
+}
+
+// Eq. 3 and the two metrics of Sec. 5.1 for one request.
+int ps_tdg_score(const ps_sched_cfg* cfg, int32_t prio, int32_t out_len, const int64_t* token_times, int32_t n_times,
+                 int64_t* gain, int64_t* ideal_gain, int32_t* slo_attained) {
+  if (!cfg || (n_times > 0 && !token_times)) return sched_fail(PS_EINVAL, "ps_tdg_score: NULL argument");
+  if (prio < 1 || prio > cfg->n_classes || cfg->n_classes > 8 || out_len < 0 || n_times < 0)
+    return sched_fail(PS_EINVAL, "ps_tdg_score: bad class, out_len or n_times");
+  const int64_t wc = cfg->class_weight[prio - 1];
+  int64_t g = 0;
+  for (int32_t i = 1; i <= n_times; ++i) {
+    const int64_t deadline = cfg->ttft_slo_ps + (int64_t)(i - 1) * cfg->tpot_slo_ps;
+    if (token_times[i - 1] < deadline) g += (i == 1 ? cfg->w_first : cfg->w_decode) * wc;
+  }
+  if (gain) *gain = g;
+  if (ideal_gain) *ideal_gain = out_len > 0 ? (cfg->w_first + (int64_t)(out_len - 1) * cfg->w_decode) * wc : 0;
+  if (slo_attained) {
+    bool ok = n_times > 0 && token_times[0] < cfg->ttft_slo_ps;
+    if (ok && n_times > 1)
+      ok = (i128)(token_times[n_times - 1] - token_times[0]) < (i128)cfg->tpot_slo_ps * (n_times - 1);
+    *slo_attained = ok ? 1 : 0;
+  }
+  return PS_OK;
+}
+
+// Virtual-clock run of the batch former over an arrival trace.
+int ps_sched_simulate(const ps_sched_cfg* cfg, const int32_t* dev_free_order, int32_t n_dev, const int32_t* host_free_order,
+                      int32_t n_host, const ps_trace_req* trace, int32_t n_trace, int32_t max_steps, int64_t* token_times,
+                      int32_t* n_delivered, ps_sim_result* out) {
+  if (!cfg || !out || (n_trace > 0 && !trace) || n_trace < 0 || max_steps < 0)
+    return sched_fail(PS_EINVAL, "ps_sched_simulate: bad argument");
+  std::memset(out, 0, sizeof *out);
+  ps_sched* s = nullptr;
+  int rc = ps_sched_create(cfg, dev_free_order, n_dev, host_free_order, n_host, &s);
+  if (rc != PS_OK) return rc;
+  // arrival order (ties by id); where each request's token times go
+  std::vector<int32_t> by_arrival((size_t)n_trace);
+  std::vector<int64_t> t_off((size_t)n_trace + 1, 0);
+  std::unordered_map<int64_t, int32_t> index_of;
+  for (int32_t i = 0; i < n_trace; ++i) {
+    by_arrival[(size_t)i] = i;
+    t_off[(size_t)i + 1] = t_off[(size_t)i] + std::max(trace[i].out_len, 0);
+    if (!index_of.emplace(trace[i].rid, i).second) {
+      ps_sched_destroy(s);
+      return sched_fail(PS_EINVAL, "ps_sched_simulate: duplicate request id %lld", (long long)trace[i].rid);
+    }
+  }
+  std::sort(by_arrival.begin(), by_arrival.end(), [&](int32_t a, int32_t b) {
+    if (trace[a].arrival_ps != trace[b].arrival_ps) return trace[a].arrival_ps < trace[b].arrival_ps;
+    return trace[a].rid < trace[b].rid;
+  });
+  std::vector<int64_t> own_times;
+  std::vector<int32_t> own_counts;
+  if (!token_times) {
+    own_times.assign((size_t)t_off[(size_t)n_trace], 0);
+    token_times = own_times.data();
+  }
+  if (!n_delivered) {
+    own_counts.assign((size_t)n_trace, 0);
+    n_delivered = own_counts.data();
+  }
+  for (int32_t i = 0; i < n_trace; ++i) n_delivered[i] = 0;
+  // the offload thread on the same clock: a round's copies start when its batch has been computed and
+  // the earlier copies are through, and take t_block per block
+  std::vector<std::pair<int64_t, int64_t>> inflight;  // (round, completion time), oldest first
+  size_t inflight_head = 0;
+  int64_t copy_free_at = 0, now = 0;
+  int32_t nxt = 0, steps = 0;
+  ps_batch_out fb;
+  while (steps < max_steps) {
+    while (nxt < n_trace && trace[by_arrival[(size_t)nxt]].arrival_ps <= now) {
+      const ps_trace_req& p = trace[by_arrival[(size_t)nxt]];
+      rc = ps_sched_add_request(s, p.rid, p.arrival_ps, p.prio, p.prompt_len, p.out_len);
+      if (rc != PS_OK) {
+        ps_sched_destroy(s);
+        return rc;
+      }
+      ++nxt;
+    }
+    if (s->reqs.empty()) {
+      if (nxt >= n_trace) break;
+      now = trace[by_arrival[(size_t)nxt]].arrival_ps;
+      continue;
+    }
+    while (inflight_head < inflight.size() && inflight[inflight_head].second <= now)
+      (void)ps_sched_offloads_done(s, inflight[inflight_head++].first);
+    rc = ps_form_batch(s, now, &fb);
+    if (rc != PS_OK) {
+      ps_sched_destroy(s);
+      return rc;
+    }
+    ++steps;
+    if (fb.n_swap_out > 0) {
+      copy_free_at = std::max(copy_free_at, now + fb.t_batch_ps) + (int64_t)fb.n_swap_out * cfg->t_block_ps;
+      inflight.emplace_back(fb.round, copy_free_at);
+    }
+    for (int32_t e = 0; e < fb.n_emitted; ++e) {  // tokens are delivered when the batch ends
+      const int32_t i = index_of[fb.emitted_req[e]];
+      token_times[t_off[(size_t)i] + n_delivered[i]] = now + fb.t_batch_ps - trace[i].arrival_ps;
+      n_delivered[i] += 1;
+    }
+    for (int32_t f = 0; f < fb.n_finished; ++f) {
+      const int32_t i = index_of[fb.finished[f]];
+      int64_t g = 0, ideal = 0;
+      int32_t ok = 0;
+      (void)ps_tdg_score(cfg, trace[i].prio, trace[i].out_len, token_times + t_off[(size_t)i], n_delivered[i], &g, &ideal, &ok);
+      out->gain += g;
+      out->ideal_gain += ideal;
+      out->slo_attained += ok;
+      out->finished += 1;
+    }
+    now += fb.t_batch_ps > 0 ? fb.t_batch_ps : cfg->eta_ps;
+  }
+  out->steps = steps;
+  out->end_ps = now;
+  ps_sched_destroy(s);
   return PS_OK;
 }
 

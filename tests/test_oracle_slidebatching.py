@@ -235,6 +235,7 @@ def test_eviction_takes_from_tail_and_spares_near_starved():
     r = sb.form_batch(0)
     assert sorted(x[0] for x in r.batch) == [0, 1] and len(sb.dev_free) == 4
     assert len(r.swap_out) == 8               # class 3, n_off = 1: every full block offloaded at once
+    sb.offloads_done(r.round)                 # the copy thread reports those eight copies complete
     # make request 1 near-starved (waited >= 0.9 tau), request 0 recently scheduled
     sb.reqs[0].last_sched = 950 * MS
     sb.reqs[1].last_sched = 50 * MS

@@ -18,25 +18,28 @@ def cfg_pair(n_layers=36, n_classes=3, **kw):
              w_first=4, w_decode=1, a_p=(13 * n_layers) // 2, b_p=13 * n_layers, c_p=50 * NS * n_layers,
              a_d=730 * n_layers, b_d=1 * US * n_layers, t_c=2 * MS, eta=10 * MS, tau=30_000 * MS,
              t_block=1200 * NS * n_layers, gamma_num=9, gamma_den=10, beta_num=2, beta_den=1, rho_num=9, rho_den=10,
-             n_off_base=8)
+             n_off_base=8, order_policy=0)
     d.update(kw)
     oc = S.SchedConfig(**d)
     lib = dict(n_classes=n_classes, block_tokens=16, class_weight=d["class_weight"], w_first=d["w_first"],
                w_decode=d["w_decode"], ttft_slo_ps=d["ttft_slo"], tpot_slo_ps=d["tpot_slo"], a_p=d["a_p"], b_p=d["b_p"],
                c_p=d["c_p"], a_d=d["a_d"], b_d=d["b_d"], t_c=d["t_c"], eta_ps=d["eta"], tau_ps=d["tau"],
                gamma_num=d["gamma_num"], gamma_den=d["gamma_den"], beta_num=d["beta_num"], beta_den=d["beta_den"],
-               rho_num=d["rho_num"], rho_den=d["rho_den"], t_block_ps=d["t_block"], n_off_base=d["n_off_base"])
+               rho_num=d["rho_num"], rho_den=d["rho_den"], t_block_ps=d["t_block"], n_off_base=d["n_off_base"],
+               order_policy=d["order_policy"])
     return oc, lib
 
 
-def run_both(oc, lib_cfg, trace, M, Mh, max_steps, seed):
+def run_both(oc, lib_cfg, trace, M, Mh, max_steps, seed, lag=0):
+    """lag: how many rounds an offload list stays in flight before both sides are told that it has landed
+    (0: reported before the next round; None: never reported)."""
     rng = np.random.default_rng(seed)
     dev_order, host_order = rng.permutation(M).astype(np.int32), rng.permutation(Mh).astype(np.int32)
     sb = S.SlideBatcher(oc, dev_order, host_order)
     ls = B.ps_sched_create(lib_cfg, dev_order, host_order)
     pending = sorted(trace, key=lambda x: (x.arrival_ps, x.rid))
     nxt, now, steps = 0, 0, 0
-    stats = dict(evicted=0, swap_in=0, swap_out=0, admitted=0, partial=0, chunks=0, finished=0)
+    stats = dict(evicted=0, swap_in=0, swap_out=0, admitted=0, partial=0, chunks=0, finished=0, dropped_pending=0)
     try:
         while steps < max_steps:
             while nxt < len(pending) and pending[nxt].arrival_ps <= now:
@@ -49,9 +52,13 @@ def run_both(oc, lib_cfg, trace, M, Mh, max_steps, seed):
                     break
                 now = pending[nxt].arrival_ps
                 continue
+            if lag is not None and steps - lag > 0:
+                sb.offloads_done(steps - lag)
+                B.ps_sched_offloads_done(ls, steps - lag)
             want = sb.form_batch(now)
             got = B.ps_form_batch(ls, now)
             steps += 1
+            assert got["round"] == want.round == steps
             tag = "step %d now %d" % (steps, now)
             assert got["req_ids"].tolist() == [r for r, _, _ in want.batch], tag          # membership and order
             assert np.diff(got["q_start"]).tolist() == [c for _, c, _ in want.batch], tag  # chunk sizes
@@ -69,6 +76,7 @@ def run_both(oc, lib_cfg, trace, M, Mh, max_steps, seed):
             assert got["finished"].tolist() == want.finished, tag
             nq, ndf, nhf = B.ps_sched_counts(ls)
             assert (nq, ndf, nhf) == (len(sb.reqs), len(sb.dev_free), len(sb.host_free)), tag
+            stats["dropped_pending"] += want.dropped_pending
             stats["evicted"] += len(want.evicted); stats["swap_in"] += len(want.swap_in)
             stats["swap_out"] += len(want.swap_out); stats["admitted"] += len(want.batch)
             stats["chunks"] += sum(1 for _, c, _ in want.batch if c > 1); stats["finished"] += len(want.finished)
@@ -94,6 +102,18 @@ def test_preemption_heavy_trace():
     assert steps >= 600 and st["evicted"] > 100 and st["swap_in"] > 100 and st["swap_out"] > 100 and st["chunks"] > 10
 
 
+@pytest.mark.parametrize("lag", [2, 5, None])
+def test_preemption_with_offloads_in_flight(lag):
+    """Offload lists stay in flight for several rounds (or are never reported): evictions discard the pending
+    copies (Sec. 4.3, Asynchronous Offloading) and both sides must still agree on everything."""
+    oc, lc = cfg_pair(tau=3000 * MS, n_off_base=2)
+    tr = W.make_trace(3, 250, rate_per_s=200.0, seed=1, prompt_mean=600, prompt_max=3000, out_mean=40, out_max=200)
+    steps, st = run_both(oc, lc, tr, 300, 600, 800, seed=1, lag=lag)
+    assert steps >= 500 and st["evicted"] > 50 and st["dropped_pending"] > 0
+    if lag is None:
+        assert st["swap_in"] == 0           # nothing was ever confirmed, so nothing can be reloaded
+
+
 def test_bursty_four_class_trace():
     oc, lc = cfg_pair(n_layers=80, n_classes=4, tau=5000 * MS)
     tr = W.make_trace(5, 300, rate_per_s=40.0, seed=5, prompt_mean=2000, prompt_max=16384, out_mean=64, out_max=512,
@@ -104,7 +124,7 @@ def test_bursty_four_class_trace():
 
 @pytest.mark.parametrize("kw", [dict(gamma_num=0), dict(gamma_num=10 ** 6), dict(beta_num=1, beta_den=1),
                                 dict(n_off_base=1), dict(tau=200 * MS), dict(eta=3 * MS, t_c=1 * MS),
-                                dict(t_block=40 * US * 36)])
+                                dict(t_block=40 * US * 36), dict(order_policy=1)])
 def test_parameter_corners(kw):
     oc, lc = cfg_pair(**kw)
     tr = W.make_trace(2, 120, rate_per_s=150.0, seed=9, prompt_mean=500, prompt_max=2500, out_mean=30, out_max=120)
