@@ -4,8 +4,9 @@
 A step is one pass of the hot path over one synthetic mixed batch (ps_step): host batch
 description -> device and KV append (one launch), split-K decode attention and prefill-chunk
 attention side by side (one launch), merge of the split-K partials (one launch).  The
-headline workload is the Qwen3-8B-shaped layer (256 decode requests + 2048 prefill tokens in 4
-chunks).  Prints ONE JSON line: metric, value, unit, timing fields, a roofline object for the attention launch and
+headline workload is the largest single-GPU configuration, the Llama-70B-shaped layer (64 query / 8 KV
+heads; 512 decode requests + 8192 prefill tokens in 4 chunks); the Qwen3-8B-shaped and the long-context
+workloads are reported under "extra", each with its own roofline object.  Prints ONE JSON line: metric, value, unit, timing fields, a roofline object for the attention launch and
 the oracle's speed on the same batch as cpu_baseline.
 """
 from __future__ import annotations
@@ -20,9 +21,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of attention_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
-# plain 1 GiB copy; summary in profiles/attention_kernel_hbm_traffic_pmc.md), by workload index.
+# HBM bytes per launch of attention_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in runs of
+# their own (scaled by a plain 1 GiB copy; summary in profiles/attention_kernel_hbm_traffic_pmc.md), by workload
+# index.  Not measured in this run: counters need the profiler.
 MEASURED_ATTENTION_TRAFFIC = {2: 1.607e9, 4: 3.382e9}
+TRAFFIC_SOURCE = "profiles/attention_kernel_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; runs of their own)"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
@@ -32,7 +35,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=2, help="workload index 1..5 (2 = headline)")
+    ap.add_argument("--workload", type=int, default=5, help="workload index 1..5 (5 = headline)")
     ap.add_argument("--decode-chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads / swap figures")
@@ -166,29 +169,46 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import attention as A
+        from threadpoolctl import threadpool_info          # missing => fail loudly rather than report a guess
+        pools = [p.get("num_threads", 0) for p in threadpool_info() if p.get("user_api") == "blas"]
+        assert pools, "no BLAS thread pool found: cannot say how many cores the numpy oracle uses"
+        cores = max(pools)
+        cpu_model = "unknown"
         try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            cores = 1
+            with open("/proc/cpuinfo") as f:
+                for ln in f:
+                    if ln.startswith("model name"):
+                        cpu_model = ln.split(":", 1)[1].strip()
+                        break
+        except OSError:
+            pass
         s = batch.shape
         torch.cuda.synchronize()
-        # sample: requests in batch order until about 4 M (query, key) pairs (10-30 s of fp64 numpy);
-        # on the headline workload that is the whole batch
-        budget = 4_000_000
+        # sample: requests until about 32 M (query, key) pair-heads x Hq (10-30 s of fp64 numpy), decode
+        # requests and prefill rows in the batch's own proportion of pairs
+        budget = int(1.0e9 / s.n_q_heads)
         q_host = res["q"].view(torch.int16).cpu().numpy().view(np.uint16)
         pairs = 0
         t_cpu = 0.0
         n_dec = n_rows = 0
-        order = [int(r) for r in batch.prefill_reqs] + [int(r) for r in batch.decode_reqs]
-        for r in order:
-            if pairs >= budget:
+        total_pairs = batch.decode_kv_tokens() + batch.causal_pairs()
+        frac = min(1.0, budget / total_pairs)
+        order = []                                  # (request, rows): every chunk's leading rows, then decode requests
+        for r in [int(x) for x in batch.prefill_reqs]:
+            lq_r, p_r = batch.l_q(r), int(batch.kv_len[r]) - batch.l_q(r)
+            rows_r = lq_r
+            while rows_r > 1 and rows_r * p_r + rows_r * (rows_r + 1) // 2 > frac * (lq_r * p_r + lq_r * (lq_r + 1) // 2):
+                rows_r -= max(1, rows_r // 16)
+            order.append((r, rows_r))
+        dec_budget = frac * batch.decode_kv_tokens()
+        for r in [int(x) for x in batch.decode_reqs]:
+            if dec_budget <= 0:
                 break
+            order.append((r, 1))
+            dec_budget -= int(batch.kv_len[r])
+        for r, rows in order:
             L, lq = int(batch.kv_len[r]), batch.l_q(r)
             p = L - lq
-            rows = lq
-            while rows > 1 and rows * p + rows * (rows + 1) // 2 > budget - pairs:
-                rows //= 2                          # leading rows of the chunk only
             tab = torch.from_numpy(batch.table(r).astype(np.int64)).to(dev)
             blocks = res["pool"][tab].view(torch.int16).cpu().numpy().view(np.uint16)
             k_bits, v_bits = request_kv(blocks, s.n_kv_heads, L)
@@ -207,9 +227,9 @@ def main() -> int:
             got = res["out"][a:a + rows].float().cpu().numpy().astype(np.float64)
             err = np.abs(got - ref)
             assert (err <= 1e-2 + 2.0 ** -8 * np.abs(ref)).all(), "bench sample disagrees with the oracle"
-        total_pairs = batch.decode_kv_tokens() + batch.causal_pairs()
         est_step_s = t_cpu * total_pairs / max(pairs, 1)
         cpu = dict(value=batch.n_tokens / est_step_s, unit="tokens/s", cores=int(cores), kind="oracle",
+                   cpu_model=cpu_model, nproc=os.cpu_count(), seconds=t_cpu,
                    sample="%d decode requests + %d prefill rows of %s (%.0f%% of its (query,key) pairs): %.1f s of "
                           "numpy fp64, every sampled output checked against the GPU's; scaled to the whole batch by pair "
                           "count" % (n_dec, n_rows, batch.name, 100.0 * pairs / (batch.decode_kv_tokens() + batch.causal_pairs()), t_cpu))
@@ -221,7 +241,7 @@ def main() -> int:
         for k in ("pool", "q", "out", "kn", "vn"):
             res.pop(k, None)
         torch.cuda.empty_cache()
-        for idx in (4, 5):
+        for idx in (2, 4, 5):
             if idx == args.workload:
                 continue
             bb = W.make_workload(idx)
@@ -238,16 +258,12 @@ def main() -> int:
         extra["swap"] = swap_bench(B, W, torch, np, dev)
         extra["reload_pipeline"] = reload_pipeline_bench(B, W, torch, np, dev)
         extra["launch_bound_pass"] = graph_bench(B, W, torch, np, dev)
-        extra["sched"] = sched_bench(B, W, np, res["ms_per_step"])
+        extra["sched"] = sched_bench(B, W, np, extra["workload_2"]["ms_per_step"] if "ms_per_step" in extra.get("workload_2", {}) else res["ms_per_step"])
 
-    # the dominant kernel is the attention launch; it is priced against the roof of whichever kind of
-    # work would take longer on its own
-    if rl["decode_alone_ms"] >= rl["prefill_alone_ms"]:
-        roof = dict(bound="hbm", kernel="attention_kernel", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=rl["attention_hbm_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get(args.workload))
-    else:
-        roof = dict(bound="mfma", kernel="attention_kernel", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
-                    unit="TFLOP/s", frac=rl["attention_mfma_frac"], traffic=None)
+    roof = roof_of(rl, args.workload)
+    for k, e in extra.items():
+        if k.startswith("workload_") and k != "workload_%d" % args.workload:
+            e["roofline"] = roof_of(e, int(k.split("_")[1]))
     line = {
         "metric": "mixed-batch paged-attn tokens/s per layer", "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
@@ -259,6 +275,25 @@ def main() -> int:
     }
     print(json.dumps(line))
     return 0
+
+
+def roof_of(rl, workload):
+    """The roofline object of the dominant kernel, the one attention launch of the mixed batch.  It does two kinds of
+    work at once; the roof that binds it is the one that gives the later earliest end: all algorithmic bytes at the
+    HBM peak, or all prefill FLOPs at the bf16 MFMA peak."""
+    t_hbm = rl["attention_bytes"] / (HBM_PEAK_GBS * 1e9)
+    t_mfma = rl["prefill_flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mfma:
+        return dict(bound="hbm", kernel="attention_kernel", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=rl["attention_hbm_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get(workload),
+                    traffic_source=TRAFFIC_SOURCE if workload in MEASURED_ATTENTION_TRAFFIC else None,
+                    other_roof=dict(bound="mfma", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                                    frac=rl["attention_mfma_frac"]))
+    return dict(bound="mfma", kernel="attention_kernel", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
+                unit="TFLOP/s", frac=rl["attention_mfma_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get(workload),
+                traffic_source=TRAFFIC_SOURCE if workload in MEASURED_ATTENTION_TRAFFIC else None,
+                other_roof=dict(bound="hbm", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
+                                frac=rl["attention_hbm_frac"]))
 
 
 def swap_bench(B, W, torch, np, dev):

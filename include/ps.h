@@ -134,7 +134,9 @@ int ps_workspace_bytes(const ps_ctx* ctx, int32_t max_req, int32_t max_tokens,
  *   out      DEVICE [n_tokens][Hq][d], bf16 or f32 per cfg.out_dtype
  *   workspace DEVICE, 256-byte aligned, at least ps_workspace_bytes(...) bytes; its contents
  *            are scratch and may be reused by the next call on the same stream (calls on
- *            different streams need different workspaces)
+ *            different streams need different workspaces; the context's own two copies of the
+ *            batch description are guarded by the library: a step that would overwrite a copy
+ *            which a step on another stream may still read waits for that step first)
  *   hip_stream  hipStream_t (NULL = default stream); the step is ordered on it: it starts after
  *            the stream's earlier work and the stream's later work starts after it (with
  *            cfg.own_streams parts of it run on the context's streams in between)

@@ -74,7 +74,8 @@ struct ps_ctx {
     char* dev = nullptr;
     size_t cap = 0;
     hipEvent_t uploaded = nullptr;  // on the copy stream, after the upload
-    hipEvent_t done = nullptr;      // on the caller's stream, after the last kernel that reads it
+    hipEvent_t done = nullptr;      // on the launching stream, after the last kernel that reads it
+    hipStream_t last_stream = nullptr;  // the stream `done` was last recorded on
     bool used = false;
   } meta[2];
   int meta_next = 0;
@@ -91,7 +92,9 @@ struct ps_ctx {
   // (offsets of the lists inside the buffer), the pinned slot it was staged in, the partials it needs.
   struct LastStep {
     bool valid = false;
-    int meta = 0, slot = 0;
+    char* meta_dev = nullptr;       // device copy of the batch description
+    MetaBuf* mb = nullptr;          // the context's buffer it lives in
+    int slot = 0;
     size_t off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};  // q_start, kv_len, bt_start, block_ids, aitems, ditems, dslots, mitems, ptiles
     size_t part_bytes = 0;
     bool has_new_kv = false;
@@ -460,8 +463,9 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   hipError_t e = hipGetDevice(&c->device);
   if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, c->device);
   if (e == hipSuccess && c->n_cus < 1) c->n_cus = 1;
-  for (int i = 0; i < kStepSlots && e == hipSuccess; ++i)
+  for (int i = 0; i < kStepSlots && e == hipSuccess; ++i) {
     e = hipEventCreateWithFlags(&c->step_slot[i].ev, hipEventDisableTiming);
+  }
   for (int i = 0; i < kSwapSlots && e == hipSuccess; ++i)
     e = hipEventCreateWithFlags(&c->swap_slot[i].ev, hipEventDisableTiming);
   for (int i = 0; i < kTicketRing && e == hipSuccess; ++i)
@@ -703,11 +707,10 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
 static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps::AppendItem* aitems_src, const void* q,
                          const void* k_new, const void* v_new, void* kv_cache, void* out, void* workspace,
                          hipStream_t stream) {
-  ps_ctx::MetaBuf& mb = c->meta[c->last.meta];
   StageSlot& slot = c->step_slot[c->last.slot];
   const size_t* off = c->last.off;
   const int prof = c->profiling;
-  char* w = mb.dev;
+  char* w = c->last.meta_dev;
 
   ps::StepParams P;
   P.q_start = (const int32_t*)(w + off[0]);
@@ -733,7 +736,7 @@ static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps
   // Prologue: one launch.  It appends the new K/V rows and, unless the context's copy stream has
   // already brought the batch description over, uploads it with a kernel that reads the pinned slot
   // over the host link (a third of the latency of a DMA copy).
-  PS_HIP(ps::launch_prologue(P, h, mb.dev, upload_bytes, aitems_src, k_new ? (int)c->aitems.size() : 0, stream));
+  PS_HIP(ps::launch_prologue(P, h, w, upload_bytes, aitems_src, k_new ? (int)c->aitems.size() : 0, stream));
   if (h && (upload_bytes > 0 || k_new)) PS_HIP(hipEventRecord(slot.ev, stream));  // last reader of the pinned slot
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
   // Attention: one launch for the decode slots and the prefill tiles (decode streams the cache at
@@ -758,7 +761,9 @@ static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps
     c->prof_valid = true;
     c->prof_mode = prof;
   }
-  if (c->copy) PS_HIP(hipEventRecord(mb.done, stream));
+  // whoever writes this copy of the batch description next (two steps on, maybe from another stream) waits for this
+  PS_HIP(hipEventRecord(c->last.mb->done, stream));
+  c->last.mb->last_stream = stream;
   return PS_OK;
 }
 
@@ -826,6 +831,7 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   if (!c->plan.mitems.empty()) std::memcpy(h + ml.mitems, c->plan.mitems.data(), c->plan.mitems.size() * sizeof(ps::MergeItem));
   if (!c->ptiles.empty()) std::memcpy(h + ml.ptiles, c->ptiles.data(), c->ptiles.size() * sizeof(ps::PrefillTile));
 
+  const int prof = c->profiling;
   // upload on the copy stream into the buffer that step n-2 used, once that step is done with it
   ps_ctx::MetaBuf& mb = c->meta[c->meta_next];
   c->meta_next ^= 1;
@@ -841,7 +847,6 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     mb.cap = cap;
     mb.used = false;
   }
-  const int prof = c->profiling;
   if (c->copy) {  // own copy stream: the upload does not wait for the caller's earlier work
     if (mb.used) PS_HIP(hipStreamWaitEvent(c->copy, mb.done, 0));
     PS_HIP(hipMemcpyAsync(mb.dev, h, ml.total, hipMemcpyHostToDevice, c->copy));
@@ -852,6 +857,9 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
     PS_HIP(hipStreamWaitEvent(stream, mb.uploaded, 0));
   } else {  // everything on the caller's stream (the two buffers still alternate)
     if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
+    // the step before last read this copy of the description; on the same stream it is over by order, on another
+    // stream this one waits for it before the prologue overwrites the lists
+    if (mb.used && mb.last_stream != stream) PS_HIP(hipStreamWaitEvent(stream, mb.done, 0));
     if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
     // the upload is part of the prologue kernel launched below
   }
@@ -859,7 +867,8 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   mb.used = true;
   if (prof) PS_HIP(hipEventRecord(c->prof_ev[1], stream));
   c->last.valid = false;
-  c->last.meta = (int)(&mb - c->meta);
+  c->last.meta_dev = mb.dev;
+  c->last.mb = &mb;
   c->last.slot = (int)(&slot - c->step_slot);
   const size_t offs[9] = {ml.q_start, ml.kv_len, ml.bt_start, ml.block_ids, ml.aitems, ml.ditems, ml.dslots, ml.mitems, ml.ptiles};
   for (int i = 0; i < 9; ++i) c->last.off[i] = offs[i];
@@ -898,7 +907,9 @@ int ps_step_next_layer(ps_ctx* c, const void* q, const void* k_new, const void* 
     PS_HIP(hipEventRecord(c->prof_ev[1], stream));
   }
   // the append items are taken from the device copy of the batch description this time
-  const char* w = c->meta[c->last.meta].dev;
+  const char* w = c->last.meta_dev;
+  // a call on another stream than the one the batch was uploaded on: ordered by the caller (see ps.h), but the wait is cheap
+  if (c->last.mb->last_stream != stream) PS_HIP(hipStreamWaitEvent(stream, c->last.mb->done, 0));
   return launch_phases(c, nullptr, 0, (const ps::AppendItem*)(w + c->last.off[4]), q, k_new, v_new, kv_cache, out, workspace,
                        stream);
 }

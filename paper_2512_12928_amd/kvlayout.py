@@ -33,3 +33,14 @@ def request_kv(flat_blocks: np.ndarray, Hkv: int, kv_len: int, blk: int = 16, d:
     k = pool[:, 0].transpose(0, 2, 1, 3).reshape(-1, Hkv, d)[:kv_len]
     v = pool[:, 1].transpose(0, 2, 1, 3).reshape(-1, Hkv, d)[:kv_len]
     return np.ascontiguousarray(k), np.ascontiguousarray(v)
+
+
+def scatter_token_rows(pool, Hkv: int, blocks, slots, k_rows, v_rows, blk: int = 16, d: int = 128) -> None:
+    """torch, in place: writes token rows k_rows / v_rows [n, Hkv, d] into slots[i] of blocks[i] of a
+    device-layout pool tensor [M, 2*Hkv*blk*d] (any 16-bit dtype)."""
+    M = pool.shape[0]
+    kview = pool.view(M, 2, Hkv, d // 8, blk, 8)
+    vview = pool.view(M, 2, Hkv, d, blk)
+    n = blocks.shape[0]
+    kview[blocks, 0, :, :, slots, :] = k_rows.reshape(n, Hkv, d // 8, 8)
+    vview[blocks, 1, :, :, slots] = v_rows

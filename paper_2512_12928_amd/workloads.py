@@ -297,13 +297,85 @@ def make_trace(index: int, n_requests: int, rate_per_s: float, seed: Optional[in
             for i, (a, c, pl, ol) in enumerate(reqs)]
 
 
+# --------------------------------------------------------------------------- "needle" inputs
+NEEDLE_TILE = 32
+NEEDLE_K_GAINS = (0.6875, 0.6953125, 0.703125, 0.7109375, 0.71875)   # bf16-exact
+
+
+@dataclass
+class NeedlePlan:
+    """A second input recipe for long contexts.  With plain N(0,1) inputs an attention output over n keys is
+    an average of ~n values and shrinks like 1/sqrt(n): losing a whole 32-token tile of a 24 k context moves
+    it by less than any usable tolerance.  Here every 32-token tile of every request holds one planted token
+    whose key is aligned with a direction u (per request and kv-head) that is also added to the request's
+    queries, so that its score stands out (q.k/sqrt(d) about +8), and whose value row is a +-A sign pattern
+    of its own, with A growing with the request's tile count so that every single tile carries a visible
+    share of every output row that can see it.  Only draws and sizes: no attention arithmetic here."""
+    pos: List[np.ndarray]        # per request: planted token positions, one per tile, increasing
+    gain: List[np.ndarray]       # per request: float32 key gain of each planted token
+    amp: np.ndarray              # per request: float32 amplitude A of its planted value rows
+    u: np.ndarray                # float32 [n_req, Hkv, d] of +-1
+    vsign: List[np.ndarray]      # per request: int8 [n_planted, Hkv, d] of +-1
+
+    def k_rows(self, r: int) -> np.ndarray:
+        """bf16 bits [n_planted, Hkv, d] of request r's planted keys."""
+        return f32_to_bf16_bits(self.gain[r][:, None, None] * self.u[r][None])
+
+    def v_rows(self, r: int) -> np.ndarray:
+        return f32_to_bf16_bits(self.amp[r] * self.vsign[r].astype(np.float32))
+
+
+def make_needle_plan(batch: MixedBatch, seed: Optional[int] = None) -> NeedlePlan:
+    rng = np.random.default_rng((batch.seed if seed is None else seed) + 104729)
+    s = batch.shape
+    pos, gain, vsign = [], [], []
+    amp = np.empty(batch.n_req, dtype=np.float32)
+    u = rng.choice(np.array([-1.0, 1.0], dtype=np.float32), size=(batch.n_req, s.n_kv_heads, s.head_dim))
+    for r in range(batch.n_req):
+        L = int(batch.kv_len[r])
+        nt = -(-L // NEEDLE_TILE)
+        first = np.arange(nt, dtype=np.int64) * NEEDLE_TILE
+        width = np.minimum(NEEDLE_TILE, L - first)
+        pos.append(first + rng.integers(0, width))
+        gain.append(rng.choice(np.array(NEEDLE_K_GAINS, dtype=np.float32), size=nt))
+        vsign.append(rng.choice(np.array([-1, 1], dtype=np.int8), size=(nt, s.n_kv_heads, s.head_dim)))
+        amp[r] = bf16_bits_to_f32(f32_to_bf16_bits(np.array([max(1.0, nt / 48.0)], dtype=np.float32)))[0]
+    return NeedlePlan(pos=pos, gain=gain, amp=amp, u=u, vsign=vsign)
+
+
+def make_needle_tensors(batch: MixedBatch, seed: Optional[int] = None) -> Tuple[StepTensors, NeedlePlan]:
+    """CPU-sized form of the needle recipe: N(0,1) tensors as make_tensors draws them, the request's direction
+    added to its queries, the planted rows written over the plain ones."""
+    plan = make_needle_plan(batch, seed)
+    rng = np.random.default_rng((batch.seed if seed is None else seed) + 7919)
+    s = batch.shape
+    q = rng.standard_normal(size=(batch.n_tokens, s.n_q_heads, s.head_dim), dtype=np.float32)
+    for r in range(batch.n_req):
+        a, b = int(batch.q_start[r]), int(batch.q_start[r + 1])
+        q[a:b] += np.repeat(plan.u[r], s.group, axis=0)[None]
+    t = StepTensors(q=f32_to_bf16_bits(q))
+    for r in range(batch.n_req):
+        L = int(batch.kv_len[r])
+        k = normal_bf16(rng, (L, s.n_kv_heads, s.head_dim))
+        v = normal_bf16(rng, (L, s.n_kv_heads, s.head_dim))
+        k[plan.pos[r]] = plan.k_rows(r)
+        v[plan.pos[r]] = plan.v_rows(r)
+        t.k.append(k)
+        t.v.append(v)
+    return t, plan
+
+
 # --------------------------------------------------------------------------- full-size device inputs
-def device_inputs(batch: MixedBatch, seed: int, device: str = "cuda:0"):
+def device_inputs(batch: MixedBatch, seed: int, device: str = "cuda:0", recipe: str = "normal"):
     """Full-size inputs generated on the GPU with torch's seeded generator (plumbing, not the HIP
     path): the whole device pool, q, and this step's k_new / v_new, all N(0,1) rounded to bf16.
     Returns (pool [M, block_elems], q, k_new, v_new) as bf16 tensors.  Filling the raw pool with
-    i.i.d. values makes every logical K/V entry N(0,1) whatever the in-block layout."""
+    i.i.d. values makes every logical K/V entry N(0,1) whatever the in-block layout.
+    recipe "needle": on top of that, the planted tokens of make_needle_plan (the cached ones written
+    into the pool through the block tables, this step's own into k_new / v_new) and each request's
+    direction added to its queries."""
     import torch
+    from .kvlayout import scatter_token_rows
     s = batch.shape
     g = torch.Generator(device=device)
     g.manual_seed(seed)
@@ -313,8 +385,36 @@ def device_inputs(batch: MixedBatch, seed: int, device: str = "cuda:0"):
     for a in range(0, pool_elems, step):       # N(0,1) in fp32, rounded to bf16, in slabs
         n = min(step, pool_elems - a)
         pool[a:a + n] = torch.randn(n, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    pool = pool.view(batch.n_device_blocks, -1)
 
     def rows(heads):
-        return torch.randn((batch.n_tokens, heads, s.head_dim), generator=g, device=device).to(torch.bfloat16)
+        return torch.randn((batch.n_tokens, heads, s.head_dim), generator=g, device=device)
 
-    return pool.view(batch.n_device_blocks, -1), rows(s.n_q_heads), rows(s.n_kv_heads), rows(s.n_kv_heads)
+    q, kn, vn = rows(s.n_q_heads), rows(s.n_kv_heads).to(torch.bfloat16), rows(s.n_kv_heads).to(torch.bfloat16)
+    if recipe == "needle":
+        plan = make_needle_plan(batch, seed)
+        lq = np.diff(batch.q_start)
+        req_of_token = np.repeat(np.arange(batch.n_req), lq)
+        u_dev = torch.from_numpy(plan.u).to(device)                                  # [n_req, Hkv, d]
+        q += u_dev[torch.from_numpy(req_of_token).to(device)].repeat_interleave(s.group, dim=1)
+        blocks, slots, krows, vrows, new_at, new_k, new_v = [], [], [], [], [], [], []
+        for r in range(batch.n_req):
+            L, p = int(batch.kv_len[r]), int(batch.kv_len[r]) - int(lq[r])
+            pos, kr, vr = plan.pos[r], plan.k_rows(r), plan.v_rows(r)
+            old = pos < p
+            blocks.append(batch.table(r)[pos[old] // s.block_tokens])
+            slots.append(pos[old] % s.block_tokens)
+            krows.append(kr[old]); vrows.append(vr[old])
+            new_at.append(int(batch.q_start[r]) + (pos[~old] - p))
+            new_k.append(kr[~old]); new_v.append(vr[~old])
+
+        def bits(a):
+            return torch.from_numpy(np.ascontiguousarray(np.concatenate(a)).view(np.int16)).to(device).view(torch.bfloat16)
+        scatter_token_rows(pool, s.n_kv_heads, torch.from_numpy(np.concatenate(blocks).astype(np.int64)).to(device),
+                           torch.from_numpy(np.concatenate(slots).astype(np.int64)).to(device), bits(krows), bits(vrows))
+        at = torch.from_numpy(np.concatenate(new_at).astype(np.int64)).to(device)
+        kn[at] = bits(new_k)
+        vn[at] = bits(new_v)
+    elif recipe != "normal":
+        raise ValueError("recipe must be 'normal' or 'needle'")
+    return pool, q.to(torch.bfloat16), kn, vn

@@ -42,7 +42,7 @@ def test_engine_loop_matches_oracle():
     nxt, now, steps = 0, 0, 0
     seen = dict(evicted=0, swap_in=0, swap_out=0, recomputed=0)
     hist_len = {}                                  # rid -> tokens whose KV the engine believes it holds
-    out_ticket = 0
+    out_tickets = []                               # (round, ticket) of offload lists still in flight, oldest first
     worst = 0.0
     while steps < 160:
         while nxt < len(pending) and pending[nxt].arrival_ps <= now:
@@ -54,6 +54,10 @@ def test_engine_loop_matches_oracle():
                 break
             now = pending[nxt].arrival_ps
             continue
+        # the copy thread's report (Sec. 4.3, Asynchronous Offloading): offloads whose ticket has completed count
+        # as host copies from now on; nobody waits for one -- an eviction discards what is still in flight
+        while out_tickets and B.ps_ticket_query(ctx, out_tickets[0][1]) == B.PS_OK:
+            B.ps_sched_offloads_done(sched, out_tickets.pop(0)[0])
         fb = B.ps_form_batch(sched, now)
         steps += 1
         seen["evicted"] += len(fb["evicted"]); seen["swap_in"] += len(fb["swap_in_dev_blocks"])
@@ -61,9 +65,6 @@ def test_engine_loop_matches_oracle():
         if fb["n_req"] == 0:
             now += oc.eta
             continue
-        # the previous step's offload must have landed before its device blocks can be evicted and reused
-        if out_ticket:
-            B.ps_ticket_wait(ctx, out_ticket)
         n_in, tk_in = B.ps_swap_in(ctx, fb["swap_in_host_slots"], fb["swap_in_dev_blocks"], int(fb["copy_budget"]),
                                    host, cache, side_in)
         assert n_in == len(fb["swap_in_dev_blocks"])
@@ -86,10 +87,12 @@ def test_engine_loop_matches_oracle():
         compute.synchronize()
         worst = max(worst, check_close(out.cpu().numpy().astype(np.float64), np.concatenate(want), False))
         # offload after the step (the new rows are in the cache now)
-        _, out_ticket = B.ps_swap_out(ctx, fb["swap_out_dev_blocks"], fb["swap_out_host_slots"], -1, cache, host, side_out)
+        n_out, tk = B.ps_swap_out(ctx, fb["swap_out_dev_blocks"], fb["swap_out_host_slots"], -1, cache, host, side_out)
+        if n_out:
+            out_tickets.append((fb["round"], tk))
         now += fb["t_batch"]
-    if out_ticket:
-        B.ps_ticket_wait(ctx, out_ticket)
+    for _, tk in out_tickets:
+        B.ps_ticket_wait(ctx, tk)
     torch.cuda.synchronize()
     print("steps", steps, seen, "worst abs err %.4g" % worst)
     assert seen["evicted"] > 0 and seen["swap_in"] > 0 and seen["swap_out"] > 0
