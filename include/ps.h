@@ -164,6 +164,21 @@ int ps_step_next_layer(ps_ctx* ctx, const void* q, const void* k_new, const void
                        void* kv_cache, void* out, void* workspace, size_t workspace_bytes,
                        void* hip_stream, uint64_t wait_ticket);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, serving loops and harnesses
+ * that forbid hipMalloc.  ps_step, with the split-K partials and the device copy of the batch description in a
+ * fixed array of PS_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on until the process ends,
+ * in place of the caller's workspace and of the context's growable buffers.  The call allocates nothing, on the
+ * device or pinned: the staging it uses was allocated by ps_create.  Arguments and errors as for ps_step;
+ * PS_ENOMEM if the batch needs more than the array holds (2 MiB of batch description, i.e. about 500 000
+ * block-table entries; PS_STATIC_SCRATCH_BYTES - 4 MiB of partials, e.g. 840 partial rows of 64 heads); nothing
+ * is enqueued then.  Every call on a GPU shares that GPU's array, whatever the context: the array keeps the last
+ * call's contents (nothing in it has to start at zero: a step writes every entry it reads), and calls that
+ * overlap on one GPU race -- keep them on one stream, or order the streams.  ps_step_next_layer does not follow
+ * this call (PS_ESTATE). */
+#define PS_STATIC_SCRATCH_BYTES (32u << 20)
+int ps_step_static(ps_ctx* ctx, const ps_batch* batch, const void* q, const void* k_new, const void* v_new,
+                   void* kv_cache, void* out, void* hip_stream, uint64_t wait_ticket);
+
 /* Host only, no device needed: the decode work list ps_step builds for the decode requests (l_q == 1)
  * of `batch` when `waves` decode waves are available (ps_step itself uses four per compute unit for
  * a decode-only batch and a share of that next to prefill work). The list: the requests'

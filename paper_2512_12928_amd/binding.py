@@ -25,7 +25,7 @@ EXPORTS = [
     "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_step_next_layer", "ps_set_profiling",
     "ps_get_step_times", "ps_plan_decode", "ps_plan_launch", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
     "ps_sched_create", "ps_sched_destroy", "ps_sched_add_request", "ps_form_batch", "ps_sched_counts",
-    "ps_sched_offloads_done", "ps_tdg_score", "ps_sched_simulate",
+    "ps_sched_offloads_done", "ps_tdg_score", "ps_sched_simulate", "ps_step_static",
 ]
 
 
@@ -106,6 +106,7 @@ def lib():
         L.ps_destroy.restype = None
         L.ps_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
         L.ps_step.argtypes = [C.c_void_p, C.POINTER(ps_batch)] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
+        L.ps_step_static.argtypes = [C.c_void_p, C.POINTER(ps_batch)] + [C.c_void_p] * 5 + [C.c_void_p, C.c_uint64]
         L.ps_plan_launch.argtypes = [C.POINTER(ps_layer_cfg), C.POINTER(ps_batch), C.c_int32, C.POINTER(C.c_int32)]
         L.ps_step_next_layer.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
         L.ps_set_profiling.argtypes = [C.c_void_p, C.c_int]
@@ -210,6 +211,22 @@ def ps_step(ctx: int, batch, q, k_new, v_new, kv_cache, out, workspace, workspac
                                  getattr(batch, "prio", None))
     _check(lib().ps_step(ctx, C.byref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_cache), _ptr(out),
                          _ptr(workspace), workspace_bytes, _stream(stream), wait_ticket))
+    del keep
+
+
+PS_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def ps_step_static(ctx: int, batch, q, k_new, v_new, kv_cache, out, stream=None, wait_ticket: int = 0) -> None:
+    """ps_step without a workspace argument and without any allocation; batch as for ps_step."""
+    keep = None
+    if isinstance(batch, tuple):
+        batch, keep = batch
+    elif not isinstance(batch, ps_batch):
+        batch, keep = make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids,
+                                 getattr(batch, "prio", None))
+    _check(lib().ps_step_static(ctx, C.byref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kv_cache), _ptr(out),
+                                _stream(stream), wait_ticket))
     del keep
 
 

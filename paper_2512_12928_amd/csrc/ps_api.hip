@@ -48,6 +48,23 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
+// ---- device memory of ps_step_static: one fixed array per GPU, held until the process ends.
+// [0, 2 * kStaticMeta): two copies of the batch description, used alternately; the rest: split-K partials.
+constexpr size_t kStaticMeta = (size_t)2 << 20;
+constexpr size_t kStaticBytes = (size_t)PS_STATIC_SCRATCH_BYTES;
+constexpr size_t kStaticPartials = kStaticBytes - 2 * kStaticMeta;
+constexpr size_t kStepStaging = kStaticMeta;  // pinned staging per slot, allocated at ps_create
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  unsigned char* ptr = nullptr;   // device address of `scratch` on this GPU (hipGetSymbolAddress)
+  int next = 0;                   // which of the two description copies the next call takes
+  hipEvent_t done[2] = {nullptr, nullptr};
+  hipStream_t last_stream[2] = {nullptr, nullptr};
+  bool used[2] = {false, false};
+};
+static StaticScratch g_static[kMaxDevices];
+
 // The decode work list of a step (and the merge items of the step: decode's first, prefill's appended).
 struct DecodePlan {
   std::vector<ps::DecodeItem> ditems;
@@ -93,7 +110,7 @@ struct ps_ctx {
   struct LastStep {
     bool valid = false;
     char* meta_dev = nullptr;       // device copy of the batch description
-    MetaBuf* mb = nullptr;          // the context's buffer it lives in
+    MetaBuf* mb = nullptr;          // the context's buffer it lives in (NULL: the static array)
     int slot = 0;
     size_t off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};  // q_start, kv_len, bt_start, block_ids, aitems, ditems, dslots, mitems, ptiles
     size_t part_bytes = 0;
@@ -465,6 +482,10 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   if (e == hipSuccess && c->n_cus < 1) c->n_cus = 1;
   for (int i = 0; i < kStepSlots && e == hipSuccess; ++i) {
     e = hipEventCreateWithFlags(&c->step_slot[i].ev, hipEventDisableTiming);
+    // staging for the batch description, large enough for every batch ps_step_static accepts, so that a step
+    // only allocates when a batch is larger than that
+    if (e == hipSuccess) e = hipHostMalloc(&c->step_slot[i].pinned, kStepStaging, hipHostMallocDefault);
+    if (e == hipSuccess) c->step_slot[i].cap = kStepStaging;
   }
   for (int i = 0; i < kSwapSlots && e == hipSuccess; ++i)
     e = hipEventCreateWithFlags(&c->swap_slot[i].ev, hipEventDisableTiming);
@@ -762,13 +783,39 @@ static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps
     c->prof_mode = prof;
   }
   // whoever writes this copy of the batch description next (two steps on, maybe from another stream) waits for this
-  PS_HIP(hipEventRecord(c->last.mb->done, stream));
-  c->last.mb->last_stream = stream;
+  if (c->last.mb) {
+    PS_HIP(hipEventRecord(c->last.mb->done, stream));
+    c->last.mb->last_stream = stream;
+  } else {
+    StaticScratch& ss = g_static[c->device];
+    const int which = w == (char*)ss.ptr ? 0 : 1;
+    PS_HIP(hipEventRecord(ss.done[which], stream));
+    ss.last_stream[which] = stream;
+  }
   return PS_OK;
 }
 
-int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, const void* v_new, void* kv_cache,
-            void* out, void* workspace, size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket) {
+// Brings the address of this GPU's `scratch` array into g_static (once per device, with that device current).
+static int static_scratch(ps_ctx* c, StaticScratch** out) {
+  int cur = -1;
+  PS_HIP(hipGetDevice(&cur));
+  if (cur != c->device) return fail(PS_ESTATE, "ps_step_static: the context was created on device %d, current is %d", c->device, cur);
+  if (cur < 0 || cur >= kMaxDevices) return fail(PS_EINVAL, "ps_step_static: device index %d not supported", cur);
+  StaticScratch& ss = g_static[cur];
+  if (!ss.ptr) {
+    void* p = nullptr;
+    PS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(PS_EHIP, "hipGetSymbolAddress returned NULL");
+    for (int i = 0; i < 2; ++i) PS_HIP(hipEventCreateWithFlags(&ss.done[i], hipEventDisableTiming));
+    ss.ptr = (unsigned char*)p;
+  }
+  *out = &ss;
+  return PS_OK;
+}
+
+static int step_impl(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, const void* v_new, void* kv_cache,
+                     void* out, void* workspace, size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket,
+                     bool use_static) {
   if (!c || !b) return fail(PS_EINVAL, "ps_step: NULL ctx or batch");
   c->last.valid = false;  // the work lists are rebuilt below; set again once this step is enqueued
   if (b->n_req < 0 || b->n_tokens < 0) return fail(PS_EINVAL, "negative n_req / n_tokens");
@@ -787,6 +834,13 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   }
   if (!b->q_start || !b->kv_len || !b->bt_start || !b->block_ids)
     return fail(PS_EINVAL, "ps_step: NULL batch array");
+  StaticScratch* ss = nullptr;
+  if (use_static) {  // the library's fixed array takes the place of the caller's workspace
+    int rc = static_scratch(c, &ss);
+    if (rc != PS_OK) return rc;
+    workspace = ss->ptr + 2 * kStaticMeta;
+    workspace_bytes = kStaticPartials;
+  }
   if (!q || !kv_cache || !out || !workspace) return fail(PS_EINVAL, "ps_step: NULL tensor pointer");
   if ((k_new == nullptr) != (v_new == nullptr)) return fail(PS_EINVAL, "k_new and v_new must be given together");
   if (((uintptr_t)workspace & 255) != 0) return fail(PS_EINVAL, "workspace must be 256-byte aligned");
@@ -813,10 +867,16 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
                                      c->plan.mitems.size(), c->ptiles.size());
   const size_t part_bytes = align_up((size_t)n_parts * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256);
   if (part_bytes > workspace_bytes)
-    return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", part_bytes, workspace_bytes);
+    return fail(PS_ENOMEM, use_static ? "ps_step_static: the batch needs %zu bytes of split-K partials, the fixed array holds %zu"
+                                      : "workspace too small: need %zu bytes, have %zu", part_bytes, workspace_bytes);
+  if (use_static && ml.total > kStaticMeta)
+    return fail(PS_ENOMEM, "ps_step_static: the batch description takes %zu bytes, the fixed array holds %zu per step", ml.total,
+                kStaticMeta);
 
   // ---- stage + upload metadata
   StageSlot& slot = c->step_slot[c->step_next];
+  if (use_static && slot.cap < ml.total)  // cannot happen while kStepStaging >= kStaticMeta; never allocate here
+    return fail(PS_ENOMEM, "ps_step_static: staging slot of %zu bytes too small for %zu", slot.cap, ml.total);
   c->step_next = (c->step_next + 1) % kStepSlots;
   int rc = acquire_slot(slot, ml.total);
   if (rc != PS_OK) return rc;
@@ -832,6 +892,30 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   if (!c->ptiles.empty()) std::memcpy(h + ml.ptiles, c->ptiles.data(), c->ptiles.size() * sizeof(ps::PrefillTile));
 
   const int prof = c->profiling;
+  if (use_static) {
+    // the copy of the batch description that the call before last used; if that call ran on another stream this
+    // one waits for it (calls that overlap on one GPU share the array: the caller keeps them ordered)
+    const int which = ss->next;
+    ss->next ^= 1;
+    if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
+    if (ss->used[which] && ss->last_stream[which] != stream) PS_HIP(hipStreamWaitEvent(stream, ss->done[which], 0));
+    ss->used[which] = true;
+    if (prof) {
+      PS_HIP(hipEventRecord(c->prof_ev[0], stream));
+      PS_HIP(hipEventRecord(c->prof_ev[1], stream));
+    }
+    slot.in_flight = true;
+    c->last.valid = false;
+    c->last.meta_dev = (char*)ss->ptr + (size_t)which * kStaticMeta;
+    c->last.mb = nullptr;
+    c->last.slot = (int)(&slot - c->step_slot);
+    const size_t offs[9] = {ml.q_start, ml.kv_len, ml.bt_start, ml.block_ids, ml.aitems, ml.ditems, ml.dslots, ml.mitems, ml.ptiles};
+    for (int i = 0; i < 9; ++i) c->last.off[i] = offs[i];
+    c->last.part_bytes = part_bytes;
+    c->last.has_new_kv = k_new != nullptr;
+    // ps_step_next_layer does not follow a static step: last.valid stays false
+    return launch_phases(c, h, ml.total, (const ps::AppendItem*)(h + ml.aitems), q, k_new, v_new, kv_cache, out, workspace, stream);
+  }
   // upload on the copy stream into the buffer that step n-2 used, once that step is done with it
   ps_ctx::MetaBuf& mb = c->meta[c->meta_next];
   c->meta_next ^= 1;
@@ -880,6 +964,16 @@ int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, cons
   return rc;
 }
 
+int ps_step(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, const void* v_new, void* kv_cache,
+            void* out, void* workspace, size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket) {
+  return step_impl(c, b, q, k_new, v_new, kv_cache, out, workspace, workspace_bytes, hip_stream, wait_ticket, false);
+}
+
+int ps_step_static(ps_ctx* c, const ps_batch* b, const void* q, const void* k_new, const void* v_new, void* kv_cache,
+                   void* out, void* hip_stream, uint64_t wait_ticket) {
+  return step_impl(c, b, q, k_new, v_new, kv_cache, out, nullptr, 0, hip_stream, wait_ticket, true);
+}
+
 int ps_step_next_layer(ps_ctx* c, const void* q, const void* k_new, const void* v_new, void* kv_cache, void* out,
                        void* workspace, size_t workspace_bytes, void* hip_stream, uint64_t wait_ticket) {
   if (!c) return fail(PS_EINVAL, "ps_step_next_layer: NULL ctx");
@@ -909,7 +1003,7 @@ int ps_step_next_layer(ps_ctx* c, const void* q, const void* k_new, const void* 
   // the append items are taken from the device copy of the batch description this time
   const char* w = c->last.meta_dev;
   // a call on another stream than the one the batch was uploaded on: ordered by the caller (see ps.h), but the wait is cheap
-  if (c->last.mb->last_stream != stream) PS_HIP(hipStreamWaitEvent(stream, c->last.mb->done, 0));
+  if (c->last.mb && c->last.mb->last_stream != stream) PS_HIP(hipStreamWaitEvent(stream, c->last.mb->done, 0));
   return launch_phases(c, nullptr, 0, (const ps::AppendItem*)(w + c->last.off[4]), q, k_new, v_new, kv_cache, out, workspace,
                        stream);
 }
