@@ -338,61 +338,74 @@ def swap_bench(B, W, torch, np, dev):
     # different copy engines); both directions at once: one stream each
     res["link_d2h_GBps"] = max(link(True, False), link(True, False, own_streams=False))
     res["link_h2d_GBps"] = max(link(False, True), link(False, True, own_streams=False))
-    res["link_bidir_each_way_GBps"] = link(True, True)
+    res["link_bidir_each_way_GBps"] = max(link(True, True) for _ in range(3))     # the best of three: this figure wanders from run to run
     del d1, d2, h1, h2
     torch.cuda.empty_cache()
 
-    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, Mh)
-    rng = np.random.default_rng(33)
-    used = batch.block_ids
-    out_ids, out_slots = W.make_swap_lists(512, batch.n_device_blocks, Mh, rng, exclude_device=used)
-    free = np.setdiff1d(np.arange(batch.n_device_blocks, dtype=np.int32), np.concatenate([used, out_ids]))
-    in_ids = rng.permutation(free)[:512].astype(np.int32)
-    in_slots = np.setdiff1d(np.arange(Mh, dtype=np.int32), out_slots)[:512].astype(np.int32)
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, Mh, swap_dma_runs=64)
     nbytes = B.ps_workspace_bytes(ctx, batch.n_req, batch.n_tokens, len(batch.block_ids))
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     q = torch.randn((batch.n_tokens, s.n_q_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
     kn = torch.randn((batch.n_tokens, s.n_kv_heads, s.head_dim), generator=g, device=dev).to(torch.bfloat16)
     out = torch.empty_like(q)
     cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
-
-    def run(n, do_attn, do_out, do_in):
-        torch.cuda.synchronize()
-        t0 = _t.perf_counter()
-        for _ in range(n):
-            if do_out:
-                B.ps_swap_out(ctx, out_ids, out_slots, -1, pool, host, side_out)
-            if do_in:
-                B.ps_swap_in(ctx, in_slots, in_ids, -1, host, pool, side_in)
-            if do_attn:
-                B.ps_step(ctx, cb, q, kn, kn, pool, out, ws, nbytes, compute)
-        torch.cuda.synchronize()
-        return (_t.perf_counter() - t0) / n
-
     step_bytes = 512 * bb
-    run(5, True, True, True)
-    n = 40
 
-    def med(*mode):          # median of three runs of n steps
-        return sorted(run(n, *mode) for _ in range(3))[1]
+    def measure(host_run):
+        """host_run 1: host slots scattered one by one (moved by a copy kernel that addresses host memory itself);
+        32: host slots in 16 runs of 32 consecutive slots (moved by the copy engines, one DMA per run, through the
+        context's staging buffers)."""
+        rng = np.random.default_rng(33)
+        used = batch.block_ids
+        out_ids, out_slots = W.make_swap_lists(512, batch.n_device_blocks, Mh // 2, rng, exclude_device=used, host_run=host_run)
+        free = np.setdiff1d(np.arange(batch.n_device_blocks, dtype=np.int32), np.concatenate([used, out_ids]))
+        in_ids = rng.permutation(free)[:512].astype(np.int32)
+        _, in_slots = W.make_swap_lists(512, batch.n_device_blocks, Mh // 2, rng, host_run=host_run)
+        in_slots = (in_slots + Mh // 2).astype(np.int32)          # the other half of the host pool
 
-    t = med(True, False, False)
-    res["attn_ms_swaps_off"] = t * 1e3
-    res["swap_out_only_GBps"] = step_bytes / med(False, True, False) / 1e9
-    res["swap_in_only_GBps"] = step_bytes / med(False, False, True) / 1e9
-    res["swap_both_each_way_GBps"] = step_bytes / med(False, True, True) / 1e9
-    t = med(True, True, True)
-    res["overlap_both_each_way_GBps"] = step_bytes / t / 1e9
-    res["overlap_both_step_ms"] = t * 1e3
-    t = med(True, True, False)
-    res["overlap_out_GBps"] = step_bytes / t / 1e9
-    res["overlap_out_step_ms"] = t * 1e3
-    t = med(True, False, True)
-    res["overlap_in_GBps"] = step_bytes / t / 1e9
-    res["overlap_in_step_ms"] = t * 1e3
-    res["overlap_both_frac_of_bidir_link"] = res["overlap_both_each_way_GBps"] / res["link_bidir_each_way_GBps"]
-    res["overlap_out_frac_of_link"] = res["overlap_out_GBps"] / res["link_d2h_GBps"]
-    res["overlap_in_frac_of_link"] = res["overlap_in_GBps"] / res["link_h2d_GBps"]
+        def run(n, do_attn, do_out, do_in):
+            torch.cuda.synchronize()
+            t0 = _t.perf_counter()
+            for _ in range(n):
+                if do_out:
+                    B.ps_swap_out(ctx, out_ids, out_slots, -1, pool, host, side_out)
+                if do_in:
+                    B.ps_swap_in(ctx, in_slots, in_ids, -1, host, pool, side_in)
+                if do_attn:
+                    B.ps_step(ctx, cb, q, kn, kn, pool, out, ws, nbytes, compute)
+            torch.cuda.synchronize()
+            return (_t.perf_counter() - t0) / n
+
+        run(5, True, True, True)
+        n = 40
+
+        def med(*mode):          # median of three runs of n steps
+            return sorted(run(n, *mode) for _ in range(3))[1]
+
+        r = {}
+        t = med(True, False, False)
+        r["attn_ms_swaps_off"] = t * 1e3
+        r["swap_out_only_GBps"] = step_bytes / med(False, True, False) / 1e9
+        r["swap_in_only_GBps"] = step_bytes / med(False, False, True) / 1e9
+        r["swap_both_each_way_GBps"] = step_bytes / med(False, True, True) / 1e9
+        t = med(True, True, True)
+        r["overlap_both_each_way_GBps"] = step_bytes / t / 1e9
+        r["overlap_both_step_ms"] = t * 1e3
+        t = med(True, True, False)
+        r["overlap_out_GBps"] = step_bytes / t / 1e9
+        r["overlap_out_step_ms"] = t * 1e3
+        t = med(True, False, True)
+        r["overlap_in_GBps"] = step_bytes / t / 1e9
+        r["overlap_in_step_ms"] = t * 1e3
+        r["overlap_both_frac_of_bidir_link"] = r["overlap_both_each_way_GBps"] / res["link_bidir_each_way_GBps"]
+        r["overlap_out_frac_of_link"] = r["overlap_out_GBps"] / res["link_d2h_GBps"]
+        r["overlap_in_frac_of_link"] = r["overlap_in_GBps"] / res["link_h2d_GBps"]
+        # what the link alone needs for this step's bytes: the floor of a step that swaps 32 MiB each way
+        r["link_ms_for_both"] = step_bytes / (res["link_bidir_each_way_GBps"] * 1e9) * 1e3
+        return r
+
+    res.update(measure(1))
+    res["host_slots_in_runs_of_32_by_copy_engines"] = measure(32)       # cfg.swap_dma_runs = 64 on this context
     B.ps_destroy(ctx)
     return res
 

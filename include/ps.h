@@ -82,6 +82,29 @@ typedef struct {
   int32_t decode_waves;    /* waves of a decode launch when decode_chunk is 0 (each walks one
                               slot of one kv-head); 0 (default) => one per SIMD, i.e. four per
                               compute unit of the device; else in [1, 65536]                   */
+  /* What the launch planner assumes of the machine when it prices the decode work against the
+     prefill work of a mixed batch (which share of the compute units each gets) and a split of long
+     prefill rows against its merge.  0 => the value measured on an MI355X, given in brackets;
+     another part, clock or power limit wants its own (time two probe launches: a decode-only and a
+     prefill-only batch with ps_set_profiling(ctx, 2)).                                            */
+  float plan_stream_TBps;      /* rate at which decode waves on the whole chip stream the cache [6.3]  */
+  float plan_tile_step_us;     /* one 64-token KV tile step of a prefill workgroup [1.92]              */
+  float plan_merge_launch_steps; /* a merge launch, in tile steps [4.0]                                */
+  float plan_merge_row_steps;  /* merging one split row of 32 heads, in tile steps [0.0047]            */
+  float plan_decode_share;     /* fraction of the balanced decode share actually given to decode: the
+                                  prefill workgroups inherit units that decode leaves early, never the
+                                  other way round [0.95]                                               */
+  int32_t plan_decode_knee_cus;/* compute units below which the decode work slows in proportion
+                                  (above, HBM is the limit) [176]                                      */
+  int32_t swap_dma_runs;   /* 0 (default): swap lists are moved by a kernel that reads or writes the
+                              pinned host pool itself.  N > 0: a list whose host slots form at most N
+                              runs of consecutive slots (in list order) and that fits the context's
+                              staging buffer (1024 blocks) crosses the host link on the copy engines
+                              instead: a kernel packs the listed device blocks into the staging
+                              buffer (or unpacks them from it) and every run is one hipMemcpyAsync.
+                              Measured on an MI355X with 512 blocks in 16 runs of 32: slower one way
+                              (41 against 54 GB/s), faster when both directions run at once (36
+                              against 32 GB/s each way), hence opt-in.  In [0, 65536]              */
 } ps_layer_cfg;
 
 /* One mixed batch (the output of Alg. 1 as the attention layer sees it). HOST arrays. */
@@ -228,8 +251,13 @@ int ps_swap_in(ps_ctx* ctx, const int32_t* host_slot_ids, const int32_t* dev_blo
                int32_t n, int32_t copy_budget, const void* host_pool, void* kv_cache,
                void* side_stream, int32_t* n_done, uint64_t* ticket);
 
-int ps_ticket_query(ps_ctx* ctx, uint64_t ticket); /* PS_OK done | PS_EBUSY | PS_ESTATE */
-int ps_ticket_wait(ps_ctx* ctx, uint64_t ticket);  /* host blocks until done            */
+/* A ticket is the completion event of one swap call (Appendix B: reloads signal one event per layer
+ * chunk, which the compute stream waits on only just before it needs the blocks; offloads run on a
+ * stream of their own outside the forward path and are polled).  Tickets count up from 1; the library
+ * keeps the events of the last 64, an older ticket counts as complete (its event was waited for before
+ * its slot was reused).  PS_ESTATE: 0, or a ticket that was never handed out. */
+int ps_ticket_query(ps_ctx* ctx, uint64_t ticket); /* PS_OK done | PS_EBUSY in flight | PS_ESTATE */
+int ps_ticket_wait(ps_ctx* ctx, uint64_t ticket);  /* host blocks until done                      */
 
 /* ------------------------------------------------------------------------------------------
  * Host-only batch former: SlideBatching (Alg. 1) with the block management of Sec. 4.3.

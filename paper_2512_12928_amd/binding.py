@@ -34,7 +34,9 @@ class ps_layer_cfg(C.Structure):
                 ("block_tokens", C.c_int32), ("n_device_blocks", C.c_int32), ("n_host_blocks", C.c_int32),
                 ("softmax_scale", C.c_float), ("out_dtype", C.c_int32), ("decode_chunk", C.c_int32),
                 ("swap_workgroups", C.c_int32), ("own_streams", C.c_int32), ("prefill_split_tiles", C.c_int32),
-                ("decode_waves", C.c_int32)]
+                ("decode_waves", C.c_int32), ("plan_stream_TBps", C.c_float), ("plan_tile_step_us", C.c_float),
+                ("plan_merge_launch_steps", C.c_float), ("plan_merge_row_steps", C.c_float), ("plan_decode_share", C.c_float),
+                ("plan_decode_knee_cus", C.c_int32), ("swap_dma_runs", C.c_int32)]
 
 
 class ps_batch(C.Structure):
@@ -171,10 +173,15 @@ def _i32p(a: np.ndarray):
 def ps_create(n_q_heads: int, n_kv_heads: int, n_device_blocks: int, n_host_blocks: int = 0,
               softmax_scale: float = 0.0, out_dtype: int = PS_BF16, decode_chunk: int = 0,
               swap_workgroups: int = 0, head_dim: int = 128, block_tokens: int = 16,
-              own_streams: int = 0, prefill_split_tiles: int = 0, decode_waves: int = 0) -> int:
+              own_streams: int = 0, prefill_split_tiles: int = 0, decode_waves: int = 0, **plan) -> int:
+    """plan: the planner constants of ps_layer_cfg by name (plan_stream_TBps, ...); 0 or absent = default."""
     cfg = ps_layer_cfg(n_q_heads, n_kv_heads, head_dim, block_tokens, n_device_blocks, n_host_blocks,
                        softmax_scale, out_dtype, decode_chunk, swap_workgroups, own_streams, prefill_split_tiles,
                        decode_waves)
+    for k, v in plan.items():
+        if not (k.startswith("plan_") or k == "swap_dma_runs"):
+            raise TypeError("unknown ps_layer_cfg field %r" % k)
+        setattr(cfg, k, v)
     h = C.c_void_p()
     _check(lib().ps_create(C.byref(cfg), C.byref(h)))
     return h.value

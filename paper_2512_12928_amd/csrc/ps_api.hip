@@ -36,6 +36,7 @@ constexpr int kStepSlots = 4;     // pinned staging buffers for ps_step metadata
 constexpr int kSwapSlots = 8;     // id staging for swaps
 constexpr int kMaxSwap = 16384;   // blocks per swap call
 constexpr int kTicketRing = 64;
+constexpr int kStagingBlocks = 1024;  // blocks a swap staging buffer holds (64 MiB at 64 KiB per block)
 
 struct StageSlot {
   void* pinned = nullptr;
@@ -116,11 +117,36 @@ struct ps_ctx {
     size_t part_bytes = 0;
     bool has_new_kv = false;
   } last;
+  // Device staging of the copy-engine swap path, one buffer per direction ([0] out, [1] in), allocated at ps_create
+  // when there is a host pool; `done`: the last call that used it, `last_stream`: where.
+  struct Staging {
+    char* dev = nullptr;
+    int blocks = 0;
+    hipEvent_t done = nullptr;
+    hipStream_t last_stream = nullptr;
+    bool used = false;
+  } staging[2];
   std::vector<int32_t> seen;  // duplicate detection in swap lists
   std::vector<int64_t> cover;  // scratch of the decode work-list check
 };
 
 namespace {
+
+// The planner's picture of the machine: cfg value, or the MI355X default.
+struct PlanTuning {
+  double stream_TBps, tile_step_us, merge_launch_steps, merge_row_steps, decode_share;
+  int knee_cus;
+};
+PlanTuning tuning_of(const ps_layer_cfg& c) {
+  PlanTuning t;
+  t.stream_TBps = c.plan_stream_TBps > 0.f ? c.plan_stream_TBps : 6.3;
+  t.tile_step_us = c.plan_tile_step_us > 0.f ? c.plan_tile_step_us : 1.92;
+  t.merge_launch_steps = c.plan_merge_launch_steps > 0.f ? c.plan_merge_launch_steps : 4.0;
+  t.merge_row_steps = c.plan_merge_row_steps > 0.f ? c.plan_merge_row_steps : 0.0047;
+  t.decode_share = c.plan_decode_share > 0.f ? c.plan_decode_share : 0.95;
+  t.knee_cus = c.plan_decode_knee_cus > 0 ? c.plan_decode_knee_cus : 176;
+  return t;
+}
 
 // A prefill work item while the launch is being planned: `reach` = its length in 64-token KV tiles.
 struct TileKey {
@@ -156,6 +182,7 @@ double mixed_makespan(const std::vector<TileKey>& tiles, int per_tile, int n_cus
 
 double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, int TT, size_t workspace_bytes, int& n_parts) {
   double prefill_steps = 0;
+  const PlanTuning tune = tuning_of(c->cfg);
   const int wg_per_tile = c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
   int64_t longest = 0;
   for (auto& t : tiles) longest = std::max(longest, t.reach);
@@ -199,7 +226,8 @@ double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, i
           std::push_heap(bins.begin(), bins.end(), later);
         }
       const int64_t makespan = *std::max_element(bins.begin(), bins.end());
-      const double cost = (double)makespan + (rows > 0 ? 4.0 : 0.0) + 0.0047 * (c->cfg.n_q_heads / 32.0) * (double)rows;
+      const double cost = (double)makespan + (rows > 0 ? tune.merge_launch_steps : 0.0) +
+                          tune.merge_row_steps * (c->cfg.n_q_heads / 32.0) * (double)rows;
       if (k == 1 || cost < best) {
         best = cost;
         split = k == 1 ? 0 : cand;
@@ -247,8 +275,8 @@ double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, i
       if (t.t.part >= 0 && t.t.k == 0)
         rows += (int64_t)std::min(TT, b->q_start[t.t.req + 1] - b->q_start[t.t.req] - t.t.q0) * t.t.n_parts;
     }
-    prefill_steps = std::max(prefill_steps, (double)longest_part) + (rows > 0 ? 4.0 : 0.0) +
-                    0.0047 * (c->cfg.n_q_heads / 32.0) * (double)rows;
+    prefill_steps = std::max(prefill_steps, (double)longest_part) + (rows > 0 ? tune.merge_launch_steps : 0.0) +
+                    tune.merge_row_steps * (c->cfg.n_q_heads / 32.0) * (double)rows;
   }
   return prefill_steps;
 }
@@ -450,6 +478,7 @@ static int check_cfg(const ps_layer_cfg* cfg) {
       (cfg->decode_chunk < kMinChunk || cfg->decode_chunk > 65536 || cfg->decode_chunk % 32 != 0))
     return fail(PS_EINVAL, "decode_chunk must be 0 or a multiple of 32 in [32, 65536]");
   if (cfg->swap_workgroups < 0 || cfg->swap_workgroups > 65536) return fail(PS_EINVAL, "bad swap_workgroups");
+  if (cfg->swap_dma_runs < 0 || cfg->swap_dma_runs > 65536) return fail(PS_EINVAL, "swap_dma_runs must be in [0, 65536]");
   if (cfg->own_streams != 0 && cfg->own_streams != 1) return fail(PS_EINVAL, "own_streams must be 0 or 1");
   if (cfg->prefill_split_tiles < -1 || cfg->prefill_split_tiles > 65536)
     return fail(PS_EINVAL, "prefill_split_tiles must be -1, 0 or a positive tile count");
@@ -457,6 +486,11 @@ static int check_cfg(const ps_layer_cfg* cfg) {
     return fail(PS_EINVAL, "decode_waves must be in [0, 65536]");
   if (!(cfg->softmax_scale >= 0.f) || std::isinf(cfg->softmax_scale))
     return fail(PS_EINVAL, "softmax_scale must be finite and >= 0");
+  for (float v : {cfg->plan_stream_TBps, cfg->plan_tile_step_us, cfg->plan_merge_launch_steps, cfg->plan_merge_row_steps,
+                  cfg->plan_decode_share})
+    if (!(v >= 0.f) || std::isinf(v)) return fail(PS_EINVAL, "planner constants must be finite and >= 0 (0 = default)");
+  if (cfg->plan_decode_share > 1.f) return fail(PS_EINVAL, "plan_decode_share must be at most 1");
+  if (cfg->plan_decode_knee_cus < 0) return fail(PS_EINVAL, "plan_decode_knee_cus must be >= 0");
   return PS_OK;
 }
 
@@ -499,6 +533,14 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
     e = hipEventCreateWithFlags(&c->meta[i].uploaded, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->meta[i].done, hipEventDisableTiming);
   }
+  if (cfg->n_host_blocks > 0 && cfg->swap_dma_runs > 0) {
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+      ps_ctx::Staging& st = c->staging[i];
+      st.blocks = std::min(cfg->n_host_blocks, kStagingBlocks);
+      e = hipMalloc((void**)&st.dev, (size_t)st.blocks * c->block_bytes);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&st.done, hipEventDisableTiming);
+    }
+  }
   if (e != hipSuccess) {
     int rc = fail(PS_EHIP, "ps_create: %s", hipGetErrorString(e));
     ps_destroy(c);
@@ -524,6 +566,10 @@ void ps_destroy(ps_ctx* c) {
   for (auto& e : c->prof_ev)
     if (e) (void)hipEventDestroy(e);
   if (c->copy) (void)hipStreamDestroy(c->copy);
+  for (auto& st : c->staging) {
+    if (st.dev) (void)hipFree(st.dev);
+    if (st.done) (void)hipEventDestroy(st.done);
+  }
   for (auto& mb : c->meta) {
     if (mb.dev) (void)hipFree(mb.dev);
     if (mb.uploaded) (void)hipEventDestroy(mb.uploaded);
@@ -673,10 +719,11 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
   {
     int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
     if (c->cfg.decode_waves == 0 && c->profiling != 2 && !decode_reqs.empty() && !tiles.empty()) {
-      const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / 6.3e6;  // us
-      const double t_p = prefill_steps * 1.92;
+      const PlanTuning tune = tuning_of(c->cfg);
+      const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / (tune.stream_TBps * 1e6);  // us
+      const double t_p = prefill_steps * tune.tile_step_us;
       const int lo = std::min(8, c->n_cus), hi = c->n_cus - 8;
-      int cus = (int)(0.95 * c->n_cus * t_d / (t_d + t_p));
+      int cus = (int)(tune.decode_share * c->n_cus * t_d / (t_d + t_p));
       cus = std::max(lo, std::min(cus, hi));
       // Few, equally long prefill workgroups (one long chunk that outweighs the decode work) pack badly
       // next to a small decode share:
@@ -691,7 +738,7 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
         std::stable_sort(sorted.begin(), sorted.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
         std::vector<double> bins;
         auto ends = [&](int n) {
-          const double d = t_d / 1.92 * 1.05 * std::max(1.0, 176.0 / n);
+          const double d = t_d / tune.tile_step_us * 1.05 * std::max(1.0, (double)tune.knee_cus / n);
           return mixed_makespan(sorted, wg_per_tile, c->n_cus, n, d, bins);
         };
         double best = ends(cus);
@@ -1077,7 +1124,7 @@ static int swap_common(ps_ctx* c, bool out_dir, const int32_t* dev_ids, const in
   (void)si;
   c->swap_next = (c->swap_next + 1) % kSwapSlots;
   StageSlot& slot = c->swap_slot[si];
-  int rc = acquire_slot(slot, (size_t)2 * kMaxSwap * sizeof(int32_t));
+  int rc = acquire_slot(slot, (size_t)3 * kMaxSwap * sizeof(int32_t));
   if (rc != PS_OK) return rc;
   int32_t* h = (int32_t*)slot.pinned;
   std::memcpy(h, dev_ids, (size_t)m * 4);
@@ -1086,12 +1133,46 @@ static int swap_common(ps_ctx* c, bool out_dir, const int32_t* dev_ids, const in
   // link in its prologue).  A separate host-to-device copy of the ids in front of every kernel put
   // a link round trip, queued behind the bulk traffic, between consecutive copy kernels.
   int32_t* d = h;
-  // measured next to a running attention step: 8 workgroups move more than 32 or 128 do
-  const int wgs = c->cfg.swap_workgroups > 0 ? c->cfg.swap_workgroups : 8;
-  if (out_dir)
-    PS_HIP(ps::launch_block_copy(d, d + m, m, kv_cache, const_cast<void*>(host_pool), c->block_bytes, wgs, stream));
-  else
-    PS_HIP(ps::launch_block_copy(d + m, d, m, host_pool, const_cast<void*>(kv_cache), c->block_bytes, wgs, stream));
+  // Runs of consecutive host slots in list order: few runs => the copy engines move the bytes, one DMA per run,
+  // between the host pool and a device staging buffer that a kernel packs from / unpacks into the listed blocks.
+  int runs = 1;
+  for (int k = 1; k < m; ++k) runs += host_ids[k] != host_ids[k - 1] + 1;
+  ps_ctx::Staging& st = c->staging[out_dir ? 0 : 1];
+  if (st.dev && runs <= c->cfg.swap_dma_runs && m <= st.blocks) {
+    if (st.used && st.last_stream != stream) PS_HIP(hipStreamWaitEvent(stream, st.done, 0));  // the buffer's last user
+    for (int k = 0; k < m; ++k) h[2 * m + k] = k;  // positions in the staging buffer
+    const size_t bb = c->block_bytes;
+    char* hp = (char*)const_cast<void*>(host_pool);
+    if (out_dir) {
+      PS_HIP(ps::launch_block_copy(d, d + 2 * m, m, kv_cache, st.dev, bb, 64, stream));
+      for (int k0 = 0; k0 < m;) {
+        int k1 = k0 + 1;
+        while (k1 < m && host_ids[k1] == host_ids[k1 - 1] + 1) ++k1;
+        PS_HIP(hipMemcpyAsync(hp + (size_t)host_ids[k0] * bb, st.dev + (size_t)k0 * bb, (size_t)(k1 - k0) * bb,
+                              hipMemcpyDeviceToHost, stream));
+        k0 = k1;
+      }
+    } else {
+      for (int k0 = 0; k0 < m;) {
+        int k1 = k0 + 1;
+        while (k1 < m && host_ids[k1] == host_ids[k1 - 1] + 1) ++k1;
+        PS_HIP(hipMemcpyAsync(st.dev + (size_t)k0 * bb, hp + (size_t)host_ids[k0] * bb, (size_t)(k1 - k0) * bb,
+                              hipMemcpyHostToDevice, stream));
+        k0 = k1;
+      }
+      PS_HIP(ps::launch_block_copy(d + 2 * m, d, m, st.dev, const_cast<void*>(kv_cache), bb, 64, stream));
+    }
+    PS_HIP(hipEventRecord(st.done, stream));
+    st.last_stream = stream;
+    st.used = true;
+  } else {
+    // measured next to a running attention step: 8 workgroups move more than 32 or 128 do
+    const int wgs = c->cfg.swap_workgroups > 0 ? c->cfg.swap_workgroups : 8;
+    if (out_dir)
+      PS_HIP(ps::launch_block_copy(d, d + m, m, kv_cache, const_cast<void*>(host_pool), c->block_bytes, wgs, stream));
+    else
+      PS_HIP(ps::launch_block_copy(d + m, d, m, host_pool, const_cast<void*>(kv_cache), c->block_bytes, wgs, stream));
+  }
   PS_HIP(hipEventRecord(slot.ev, stream));
   slot.in_flight = true;
 

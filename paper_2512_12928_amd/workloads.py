@@ -242,8 +242,10 @@ def make_tensors(batch: MixedBatch, seed: Optional[int] = None) -> StepTensors:
 
 # --------------------------------------------------------------------------- swap lists
 def make_swap_lists(n: int, n_device_blocks: int, n_host_blocks: int, rng: np.random.Generator,
-                    exclude_device: Optional[np.ndarray] = None):
-    """n distinct device block ids (avoiding ``exclude_device``) and n distinct host slots."""
+                    exclude_device: Optional[np.ndarray] = None, host_run: int = 1):
+    """n distinct device block ids (avoiding ``exclude_device``) and n distinct host slots.  host_run > 1:
+    the host slots come in runs of that many consecutive slots (a host pool handed out in extents, one
+    per offloaded request), the runs themselves scattered; the device blocks stay scattered."""
     pool = np.arange(n_device_blocks, dtype=np.int32)
     if exclude_device is not None and len(exclude_device):
         mask = np.ones(n_device_blocks, dtype=bool)
@@ -251,7 +253,13 @@ def make_swap_lists(n: int, n_device_blocks: int, n_host_blocks: int, rng: np.ra
         pool = pool[mask]
     assert len(pool) >= n and n_host_blocks >= n
     dev = rng.permutation(pool)[:n].astype(np.int32)
-    host = rng.permutation(n_host_blocks)[:n].astype(np.int32)
+    if host_run <= 1:
+        host = rng.permutation(n_host_blocks)[:n].astype(np.int32)
+    else:
+        n_runs = -(-n // host_run)
+        assert n_host_blocks // host_run >= n_runs
+        starts = rng.permutation(n_host_blocks // host_run)[:n_runs] * host_run
+        host = (starts[:, None] + np.arange(host_run)[None, :]).reshape(-1)[:n].astype(np.int32)
     return dev, host
 
 

@@ -37,13 +37,13 @@ def test_struct_sizes_match_header(tmp_path):
     sizes = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     assert sizes == [C.sizeof(B.ps_layer_cfg), C.sizeof(B.ps_batch), C.sizeof(B.ps_step_times),
                      C.sizeof(B.ps_sched_cfg), C.sizeof(B.ps_batch_out)]
-    assert sizes[:3] == [52, 48, 28]
+    assert sizes[:3] == [80, 48, 28]
 
 
 @pytest.mark.parametrize("kw", [dict(head_dim=64), dict(block_tokens=32), dict(n_q_heads=6, n_kv_heads=4),
                                 dict(n_q_heads=34, n_kv_heads=2), dict(n_device_blocks=0), dict(out_dtype=7),
                                 dict(decode_chunk=48), dict(decode_chunk=16), dict(softmax_scale=-1.0),
-                                dict(decode_waves=-1)])
+                                dict(decode_waves=-1), dict(swap_dma_runs=-1), dict(plan_decode_share=2.0)])
 def test_create_rejects_bad_cfg_without_a_device(kw):
     args = dict(n_q_heads=8, n_kv_heads=2, n_device_blocks=64)
     args.update(kw)

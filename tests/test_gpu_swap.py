@@ -56,6 +56,36 @@ def test_swap_out_then_in_matches_oracle(Hkv, n, budget):
     B.ps_destroy(ctx)
 
 
+@pytest.mark.parametrize("n,host_run,dma_runs", [(512, 32, 64), (512, 32, 0), (300, 7, 64), (64, 64, 1), (200, 1, 64), (200, 1, 1000),
+                                                  (1500, 500, 64)])
+def test_swap_lists_with_runs_of_host_slots(n, host_run, dma_runs):
+    """Host slots in runs of consecutive slots: such lists cross the link on the copy engines through the
+    context's staging buffers (swap_dma_runs > 0; 0 is the copy kernel, a large value the copy engines even for
+    scattered slots, more blocks than the staging holds fall back to the kernel).  Out on one stream, in on
+    another, twice, so that each staging buffer is reused; bytes against the copy oracle every time."""
+    shape = W.LayerShape(32, 8)
+    M, Mh = 2200, 4096
+    dev_np, host_np = pools(shape, M, Mh, n)
+    dev = torch.from_numpy(dev_np).to(DEV)
+    host = torch.from_numpy(host_np.copy()).pin_memory()
+    ctx = B.ps_create(32, 8, M, Mh, swap_dma_runs=dma_runs)
+    s_out, s_in = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(2):
+        rng = np.random.default_rng(1000 * rep + n)
+        d_ids, h_ids = W.make_swap_lists(n, M, Mh, rng, host_run=host_run)
+        nd, tk = B.ps_swap_out(ctx, d_ids, h_ids, -1, dev, host, s_out)
+        assert nd == C.swap_out(dev_np, host_np, d_ids, h_ids, -1) == n
+        B.ps_ticket_wait(ctx, tk)
+        assert np.array_equal(host.numpy(), host_np)
+        d2, _ = W.make_swap_lists(n, M, Mh, np.random.default_rng(1000 * rep + n + 1))
+        nd2, tk2 = B.ps_swap_in(ctx, h_ids, d2, -1, host, dev, s_in if rep == 0 else s_out)
+        assert nd2 == C.swap_in(host_np, dev_np, h_ids, d2, -1) == n
+        B.ps_ticket_wait(ctx, tk2)
+        torch.cuda.synchronize()
+        assert np.array_equal(dev.cpu().numpy(), dev_np) and np.array_equal(host.numpy(), host_np)
+    B.ps_destroy(ctx)
+
+
 def test_swap_validation():
     shape = W.LayerShape(8, 2)
     M, Mh = 16, 8

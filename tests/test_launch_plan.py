@@ -94,3 +94,23 @@ def test_bad_arguments():
     bad.kv_len[0] += 100
     with pytest.raises(B.PsError):
         plan(bad)
+
+
+def test_planner_constants_move_the_share_and_the_split():
+    """The machine constants the planner prices with are configuration (ps_layer_cfg.plan_*; 0 = the MI355X default):
+    a faster cache stream shrinks the decode share, a slower prefill tile step shrinks it too, the defaults written
+    out give the default plan, a dear merge forbids the row split."""
+    b = W.make_workload(2)
+    base = plan(b)
+    same = plan(b, plan_stream_TBps=6.3, plan_tile_step_us=1.92, plan_merge_launch_steps=4.0, plan_merge_row_steps=0.0047,
+                plan_decode_share=0.95, plan_decode_knee_cus=176)
+    assert same == base
+    assert plan(b, plan_stream_TBps=12.6)["decode_workgroups"] < base["decode_workgroups"]
+    assert plan(b, plan_tile_step_us=3.84)["decode_workgroups"] < base["decode_workgroups"]
+    assert plan(b, plan_decode_share=0.5)["decode_workgroups"] < base["decode_workgroups"]
+    assert base["prefill_split_tiles"] > 0 and plan(b, plan_merge_launch_steps=1000.0)["prefill_split_tiles"] == 0
+    for bad in (dict(plan_stream_TBps=-1.0), dict(plan_decode_share=1.5), dict(plan_decode_knee_cus=-3),
+                dict(plan_tile_step_us=float("inf"))):
+        with pytest.raises(B.PsError) as e:
+            plan(b, **bad)
+        assert e.value.code == B.PS_EINVAL
