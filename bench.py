@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of attention_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in runs of
 # their own (scaled by a plain 1 GiB copy; summary in profiles/attention_kernel_hbm_traffic_pmc.md), by workload
 # index.  Not measured in this run: counters need the profiler.
-MEASURED_ATTENTION_TRAFFIC = {2: 1.607e9, 4: 3.382e9}
+MEASURED_ATTENTION_TRAFFIC = {2: 1.607e9, 4: 3.382e9, 5: 4.690e9}
 TRAFFIC_SOURCE = "profiles/attention_kernel_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; runs of their own)"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
@@ -39,6 +39,9 @@ def main() -> int:
     ap.add_argument("--decode-chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads / swap figures")
+    ap.add_argument("--swap-only", action="store_true",
+                    help="only the workload-3 swap figures (block copies next to attention steps), as one JSON object: "
+                         "the command the swap kernel's profile in profiles/ is taken with")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (a known amount of HBM traffic) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -150,6 +153,10 @@ def main() -> int:
                     prefill_alone_ms=alone["prefill_ms"], prefill_alone_TFLOPs=pre_tf,
                     prefill_alone_frac=pre_tf / MFMA_BF16_PEAK_TFLOPS)
 
+    if args.swap_only:
+        print(json.dumps({"swap": swap_bench(B, W, torch, np, dev)}))
+        return 0
+
     if args.pmc_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -257,6 +264,7 @@ def main() -> int:
             torch.cuda.empty_cache()
         extra["swap"] = swap_bench(B, W, torch, np, dev)
         extra["reload_pipeline"] = reload_pipeline_bench(B, W, torch, np, dev)
+        extra["closed_loop"] = closed_loop_bench(B, W, torch, np, dev, extra["swap"])
         extra["launch_bound_pass"] = graph_bench(B, W, torch, np, dev)
         extra["sched"] = sched_bench(B, W, np, extra["workload_2"]["ms_per_step"] if "ms_per_step" in extra.get("workload_2", {}) else res["ms_per_step"])
 
@@ -499,6 +507,54 @@ def reload_pipeline_bench(B, W, torch, np, dev, n_layers=8):
     res["pipelined_budgeted_ms"] = timed("pipelined", fit)
     res["pipelined_budgeted_overhead_vs_compute_only"] = res["pipelined_budgeted_ms"] / res["compute_only_ms"] - 1.0
     B.ps_destroy(ctx)
+    return res
+
+
+def closed_loop_bench(B, W, torch, np, dev, swap, n_layers=4, steps=300):
+    """The closed loop of Sec. 4.3 over an n_layers forward pass, driven by ps_form_batch on a trace that keeps the device
+    pool under pressure (evictions, reloads): the scheduler's t_block is the block's bytes over the link rate measured in
+    this run, its estimator constants the fit of profiles/estimator_fit_mi355x.md, both times n_layers.  Arms, side by
+    side (Sec. 5.3, block-management ablation): the copy budget as ps_form_batch sets it with the reload pipelined layer
+    by layer; the same with everything reloaded whatever it costs (t_block tiny), pipelined, layer-synchronous, and all
+    up front; and no host copies at all (evicted requests are recomputed).  pass_ms is GPU time of the forward passes
+    (from the first reload's issue to the last layer's end), summed over the rounds."""
+    from paper_2512_12928_amd.closed_loop import ClosedLoop
+    Hq, Hkv, M, Mh = 32, 8, 1200, 3000
+    bb = 2 * Hkv * 16 * 128 * 2
+    L = n_layers
+    MS, US = 10 ** 9, 10 ** 6
+    link = min(swap["link_h2d_GBps"], swap["link_d2h_GBps"])
+    t_block = int(bb / (link * 1e9) * 1e12) * L
+    base = dict(n_classes=3, block_tokens=16, class_weight=[4, 2, 1], w_first=4, w_decode=1, ttft_slo_ps=2000 * MS,
+                tpot_slo_ps=100 * MS, a_p=3 * L, b_p=19 * L, c_p=5682 * L, a_d=554 * L, b_d=15784 * L, t_c=28 * US * L,
+                eta_ps=2 * MS, tau_ps=30_000 * MS, gamma_num=9, gamma_den=10, beta_num=2, beta_den=1, rho_num=9, rho_den=10,
+                t_block_ps=t_block, n_off_base=8)
+    trace = W.make_trace(3, 400, rate_per_s=4000.0, seed=21, prompt_mean=700, prompt_max=3000, out_mean=24, out_max=96)
+    g = torch.Generator(device=dev)
+    g.manual_seed(77)
+    bank = {h: torch.randn((4096, h, 128), generator=g, device=dev).to(torch.bfloat16) for h in (Hq, Hkv)}
+
+    def rows(rid, pos0, n, heads, what, layer):      # timing run: any rows will do
+        return bank[heads][:n] if n <= 4096 else bank[heads].repeat((n + 4095) // 4096, 1, 1)[:n]
+
+    arms = {"budgeted_pipelined": (base, "pipelined"),
+            "copy_all_pipelined": (dict(base, t_block_ps=1), "pipelined"),
+            "copy_all_layer_synchronous": (dict(base, t_block_ps=1), "synchronous"),
+            "copy_all_full_reload_first": (dict(base, t_block_ps=1), "full_reload_first"),
+            "recompute_no_host_copies": (dict(base, n_off_base=1 << 30), "pipelined")}
+    res = dict(n_layers=L, device_blocks=M, host_slots=Mh, t_block_ps=t_block, rounds=steps)
+    rng = np.random.default_rng(5)
+    dev_order, host_order = rng.permutation(M), rng.permutation(Mh)
+    for name, (cfg, mode) in arms.items():
+        loop = ClosedLoop(Hq, Hkv, M, Mh, L, cfg, dev_order, host_order, rows, reload_mode=mode, out_dtype=B.PS_BF16, device=dev)
+        st = loop.run(trace, steps)
+        loop.close()
+        res[name] = dict(pass_ms=st["pass_ms"], ms_per_round=st["pass_ms"] / max(st["steps"], 1), tokens=st["tokens"],
+                         evicted=st["evicted"], blocks_reloaded=st["blocks_reloaded"], blocks_offloaded=st["blocks_offloaded"],
+                         recomputed_tokens=st["recomputed_tokens"],
+                         tokens_per_pass_ms=st["tokens"] / st["pass_ms"] if st["pass_ms"] else 0.0)
+        del loop
+        torch.cuda.empty_cache()
     return res
 
 
