@@ -36,6 +36,23 @@ def build(verbose: bool = True) -> str:
     return LIB_PATH
 
 
+def build_host_checks(out_path: str, driver: str, verbose: bool = False) -> str:
+    """CPU build of the whole library plus a driver program with AddressSanitizer and UndefinedBehaviorSanitizer on the
+    host code (the device code is compiled as usual and never runs): for the host logic -- the batch former, the launch
+    planners, the validation paths.  Returns the executable's path."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = ["--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fno-omit-frame-pointer", "-Xclang", "-target-feature", "-Xclang",
+             "-packed-fp32-ops", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-sanitize-recover=undefined", "-I", os.path.join(os.path.dirname(HERE), "include")]
+    cmd = [hipcc] + flags + [driver] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out_path]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l))
+    return out_path
+
+
 if __name__ == "__main__":
     build()
     print("built", LIB_PATH)
