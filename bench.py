@@ -28,6 +28,7 @@ MEASURED_ATTENTION_TRAFFIC = {2: 1.607e9, 4: 3.382e9, 5: 4.690e9}
 TRAFFIC_SOURCE = "profiles/attention_kernel_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; runs of their own)"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+NOMINAL_MHZ = 2400.0           # the shader clock the published matrix peak is quoted at
 
 
 def main() -> int:
@@ -151,7 +152,13 @@ def main() -> int:
                     # the two kinds of work in launches of their own, each with the whole chip
                     decode_alone_ms=alone["decode_ms"], decode_alone_GBps=dec_gbs, decode_alone_frac=dec_gbs / HBM_PEAK_GBS,
                     prefill_alone_ms=alone["prefill_ms"], prefill_alone_TFLOPs=pre_tf,
-                    prefill_alone_frac=pre_tf / MFMA_BF16_PEAK_TFLOPS)
+                    prefill_alone_frac=pre_tf / MFMA_BF16_PEAK_TFLOPS,
+                    # the shader clock the workgroups of each kind ran at (their own clock counters, read in the kernel):
+                    # the published peaks are for 2400 MHz, the chip lowers the clock under load
+                    shader_mhz=dict(mixed_decode=run_["decode_mhz"], mixed_prefill=run_["prefill_mhz"],
+                                    decode_alone=alone["decode_mhz"], prefill_alone=alone["prefill_mhz"]),
+                    prefill_alone_frac_of_peak_at_its_clock=(pre_tf / (MFMA_BF16_PEAK_TFLOPS * alone["prefill_mhz"] / NOMINAL_MHZ)
+                                                             if alone["prefill_mhz"] > 0 else None))
 
     if args.swap_only:
         print(json.dumps({"swap": swap_bench(B, W, torch, np, dev)}))
@@ -193,7 +200,7 @@ def main() -> int:
         torch.cuda.synchronize()
         # sample: requests until about 32 M (query, key) pair-heads x Hq (10-30 s of fp64 numpy), decode
         # requests and prefill rows in the batch's own proportion of pairs
-        budget = int(1.0e9 / s.n_q_heads)
+        budget = int(2.0e9 / s.n_q_heads)
         q_host = res["q"].view(torch.int16).cpu().numpy().view(np.uint16)
         pairs = 0
         t_cpu = 0.0
@@ -262,6 +269,7 @@ def main() -> int:
             B.ps_destroy(rr.pop("ctx"))
             del rr
             torch.cuda.empty_cache()
+        extra["clock_under_load"] = clock_bench(B, W, torch, dev, args.workload)
         extra["swap"] = swap_bench(B, W, torch, np, dev)
         extra["reload_pipeline"] = reload_pipeline_bench(B, W, torch, np, dev)
         extra["closed_loop"] = closed_loop_bench(B, W, torch, np, dev, extra["swap"])
@@ -295,13 +303,49 @@ def roof_of(rl, workload):
         return dict(bound="hbm", kernel="attention_kernel", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=rl["attention_hbm_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get(workload),
                     traffic_source=TRAFFIC_SOURCE if workload in MEASURED_ATTENTION_TRAFFIC else None,
+                    shader_mhz=rl["shader_mhz"],
                     other_roof=dict(bound="mfma", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                                     frac=rl["attention_mfma_frac"]))
     return dict(bound="mfma", kernel="attention_kernel", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
                 unit="TFLOP/s", frac=rl["attention_mfma_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get(workload),
                 traffic_source=TRAFFIC_SOURCE if workload in MEASURED_ATTENTION_TRAFFIC else None,
+                shader_mhz=rl["shader_mhz"],
                 other_roof=dict(bound="hbm", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
                                 frac=rl["attention_hbm_frac"]))
+
+
+def clock_bench(B, W, torch, dev, workload):
+    """The same prefill launch (launched alone, profiling mode 2) on the workload's N(0,1) tensors and on all-zero
+    tensors: same instructions, same addresses, other operand bits.  The time and the shader clock of both, as the
+    kernel's own clock counters give it: the difference is the chip's power management, not the kernel's schedule."""
+    batch = W.make_workload(workload)
+    s = batch.shape
+    pool, q, kn, vn = W.device_inputs(batch, batch.seed, dev)
+    ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, 0)
+    nbytes = B.ps_workspace_bytes(ctx, batch.n_req, batch.n_tokens, len(batch.block_ids))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    out = torch.empty((batch.n_tokens, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+    cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
+    stream = torch.cuda.current_stream()
+    flops = 4 * s.head_dim * s.n_q_heads * batch.causal_pairs()
+    res = {}
+    B.ps_set_profiling(ctx, 2)
+    for name in ("normal_inputs", "zero_inputs"):
+        if name == "zero_inputs":
+            for t in (pool, q, kn, vn):
+                t.zero_()
+        for _ in range(3):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+        acc, n = {}, 10
+        for _ in range(n):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+            for k, v in B.ps_get_step_times(ctx).items():
+                acc[k] = acc.get(k, 0.0) + v / n
+        tf = flops / (acc["prefill_ms"] * 1e-3) / 1e12 if acc["prefill_ms"] > 0 else 0.0
+        res[name] = dict(prefill_alone_ms=acc["prefill_ms"], prefill_mhz=acc["prefill_mhz"], prefill_TFLOPs=tf,
+                         frac_of_peak=tf / MFMA_BF16_PEAK_TFLOPS, decode_alone_ms=acc["decode_ms"], decode_mhz=acc["decode_mhz"])
+    B.ps_destroy(ctx)
+    return res
 
 
 def swap_bench(B, W, torch, np, dev):

@@ -128,6 +128,11 @@ typedef struct {
  * launched one after the other (each with the whole chip) and attention_ms is their sum. */
 typedef struct {
   float upload_ms, append_ms, decode_ms, merge_ms, prefill_ms, total_ms, attention_ms;
+  /* Shader clock, in MHz, at which the decode and the prefill workgroups of the attention launch ran: the
+     median over the (first 2048) workgroups of each kind of their shader-clock ticks per tick of the
+     constant 100 MHz counter; 0 if the step had none.  The chip lowers this clock under load (2400 at
+     rest), and the matrix-pipe peak falls with it. */
+  float decode_mhz, prefill_mhz;
 } ps_step_times;
 
 const char* ps_last_error(void);

@@ -47,7 +47,7 @@ class ps_batch(C.Structure):
 
 class ps_step_times(C.Structure):
     _fields_ = [(n, C.c_float) for n in ("upload_ms", "append_ms", "decode_ms", "merge_ms", "prefill_ms", "total_ms",
-                                             "attention_ms")]
+                                             "attention_ms", "decode_mhz", "prefill_mhz")]
 
 
 class ps_sched_cfg(C.Structure):

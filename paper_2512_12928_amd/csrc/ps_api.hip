@@ -101,6 +101,8 @@ struct ps_ctx {
   int n_cus = 256;
   int profiling = 0;  // 0 off, 1 phases as they run, 2 decode and prefill roles in launches of their own
   hipEvent_t prof_ev[6];
+  unsigned long long* clocks_dev = nullptr;  // profiling: clock counters of the attention workgroups (ps_set_profiling allocates)
+  int prof_wgs[2] = {0, 0};                  // decode / prefill workgroups of the last profiled step
   bool prof_valid = false;
   int prof_mode = 0;
   DecodePlan plan;
@@ -566,6 +568,7 @@ void ps_destroy(ps_ctx* c) {
   for (auto& e : c->prof_ev)
     if (e) (void)hipEventDestroy(e);
   if (c->copy) (void)hipStreamDestroy(c->copy);
+  if (c->clocks_dev) (void)hipFree(c->clocks_dev);
   for (auto& st : c->staging) {
     if (st.dev) (void)hipFree(st.dev);
     if (st.done) (void)hipEventDestroy(st.done);
@@ -640,6 +643,11 @@ int ps_plan_decode(const ps_layer_cfg* cfg, const ps_batch* b, int32_t waves, in
 int ps_set_profiling(ps_ctx* c, int enabled) {
   if (!c) return fail(PS_EINVAL, "NULL ctx");
   if (enabled < 0 || enabled > 2) return fail(PS_EINVAL, "ps_set_profiling: mode must be 0, 1 or 2");
+  if (enabled && !c->clocks_dev) {
+    const size_t bytes = (size_t)2 * ps::kClockSlots * 4 * sizeof(unsigned long long);
+    PS_HIP(hipMalloc((void**)&c->clocks_dev, bytes));
+    PS_HIP(hipMemset(c->clocks_dev, 0, bytes));
+  }
   c->profiling = enabled;
   c->prof_valid = false;
   return PS_OK;
@@ -662,6 +670,26 @@ int ps_get_step_times(ps_ctx* c, ps_step_times* out) {
   }
   out->attention_ms = att + pre;
   PS_HIP(hipEventElapsedTime(&out->total_ms, c->prof_ev[0], c->prof_ev[5]));
+  // shader clock of each role's workgroups: the median over the recorded ones of (shader-clock ticks) / (100 MHz ticks)
+  if (c->clocks_dev) {
+    std::vector<unsigned long long> rec((size_t)2 * ps::kClockSlots * 4);
+    PS_HIP(hipMemcpy(rec.data(), c->clocks_dev, rec.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+    std::vector<float> mhz;
+    for (int role = 0; role < 2; ++role) {
+      mhz.clear();
+      const int n = std::min(c->prof_wgs[role], ps::kClockSlots);
+      for (int i = 0; i < n; ++i) {
+        const unsigned long long* r = &rec[((size_t)role * ps::kClockSlots + i) * 4];
+        if (r[3] > r[1] + 20 && r[2] > r[0]) mhz.push_back((float)((double)(r[2] - r[0]) / (double)(r[3] - r[1]) * 100.0));  // at least 0.2 us of life
+      }
+      float med = 0.f;
+      if (!mhz.empty()) {
+        std::nth_element(mhz.begin(), mhz.begin() + mhz.size() / 2, mhz.end());
+        med = mhz[mhz.size() / 2];
+      }
+      (role == 0 ? out->decode_mhz : out->prefill_mhz) = med;
+    }
+  }
   return PS_OK;
 }
 
@@ -790,6 +818,7 @@ static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps
   P.mitems = (const ps::MergeItem*)(w + off[7]);
   P.ptiles = (const ps::PrefillTile*)(w + off[8]);
   P.partials = (float*)workspace;
+  P.clocks = prof ? c->clocks_dev : nullptr;
   P.q = (const uint16_t*)q;
   P.k_new = (const uint16_t*)k_new;
   P.v_new = (const uint16_t*)v_new;
@@ -812,12 +841,12 @@ static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps
   // disjoint CUs).  Profiling mode 2 gives each its own launch instead.
   const int n_slots = (int)c->plan.dslots.size() - 1;
   if (prof == 2) {
-    PS_HIP(ps::launch_attention(P, n_slots, 0, stream));
+    PS_HIP(ps::launch_attention(P, n_slots, 0, stream, &c->prof_wgs[0], nullptr));
     PS_HIP(hipEventRecord(c->prof_ev[3], stream));
-    PS_HIP(ps::launch_attention(P, 0, (int)c->ptiles.size(), stream));
+    PS_HIP(ps::launch_attention(P, 0, (int)c->ptiles.size(), stream, nullptr, &c->prof_wgs[1]));
     PS_HIP(hipEventRecord(c->prof_ev[4], stream));
   } else {
-    PS_HIP(ps::launch_attention(P, n_slots, (int)c->ptiles.size(), stream));
+    PS_HIP(ps::launch_attention(P, n_slots, (int)c->ptiles.size(), stream, &c->prof_wgs[0], &c->prof_wgs[1]));
     if (prof) {
       PS_HIP(hipEventRecord(c->prof_ev[3], stream));
       PS_HIP(hipEventRecord(c->prof_ev[4], stream));

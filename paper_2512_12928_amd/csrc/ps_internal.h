@@ -12,6 +12,7 @@ constexpr int kBlockTokens = 16;
 constexpr int kSliceElems = kBlockTokens * kHeadDim;  // one (block, K|V, kv-head) slice: 4 KiB
 constexpr int kTileTokens = 32;                       // KV tokens per MFMA tile (two blocks)
 constexpr int kPartStride = 132;                      // fp32 per split-K partial: o[128], m, l, pad
+constexpr int kClockSlots = 2048;                     // workgroups per role whose clock counters a profiled step records
 
 // One split-K partition (segment) of one decode token: KV tokens [t0, t1) of its request, for all
 // G query heads of the kv-head that blockIdx.y selects.  A decode workgroup walks the segments
@@ -65,6 +66,7 @@ struct StepParams {
   const MergeItem* mitems;
   const PrefillTile* ptiles;
   float* partials;
+  unsigned long long* clocks;  // profiling: 2 * kClockSlots records of 4 counters (see clock_record), else NULL
   // tensors
   const uint16_t* q;
   const uint16_t* k_new;
@@ -85,7 +87,9 @@ hipError_t launch_prologue(const StepParams& p, const void* src_pinned, void* ds
 // merges items [first, first + n_merge) of the merge list
 hipError_t launch_merge(const StepParams& p, int first, int n_merge, hipStream_t s);
 // One launch for the decode slots and the prefill tiles of the batch (either may be 0).
-hipError_t launch_attention(const StepParams& p, int n_slots, int n_tiles, hipStream_t s);
+// n_decode_wgs_out / n_prefill_wgs_out (may be NULL): the workgroups of each role in the launch.
+hipError_t launch_attention(const StepParams& p, int n_slots, int n_tiles, hipStream_t s, int* n_decode_wgs_out,
+                            int* n_prefill_wgs_out);
 int decode_waves_per_wg();
 // tile_tokens: query tokens per workgroup tile as returned by prefill_tile_tokens(G).
 int prefill_tile_tokens(int G);

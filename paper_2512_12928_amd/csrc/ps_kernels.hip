@@ -117,6 +117,17 @@ __global__ __launch_bounds__(256) void prologue_kernel(StepParams P, const uint4
   }
 }
 
+// Profiling only (P.clocks != NULL): the first thread of workgroup `slot` notes the shader-clock counter and
+// the constant 100 MHz counter, at its start (at = 0) and at its end (at = 2); the host turns the two
+// differences into the shader clock the workgroup ran at.  Decode workgroups use slots [0, kClockSlots),
+// prefill workgroups [kClockSlots, 2 * kClockSlots); workgroups beyond that are not recorded.
+__device__ __forceinline__ void clock_record(const StepParams& P, int slot, int at) {
+  if (P.clocks != nullptr && threadIdx.x == 0 && slot < 2 * kClockSlots) {
+    P.clocks[slot * 4 + at] = __builtin_amdgcn_s_memtime();
+    P.clocks[slot * 4 + at + 1] = __builtin_amdgcn_s_memrealtime();
+  }
+}
+
 // ------------------------------------------------------------------------------------ decode
 // Split-K decode attention, HBM-bound.  grid (ceil(n_slots / 4), Hkv), 256 threads: four waves
 // that work independently (one slot each; a workgroup only pins them to the four SIMDs of one
@@ -345,6 +356,7 @@ __device__ __forceinline__ void decode_role(const StepParams& P, const DecodeIte
     }
     it = itn;
   }
+  if (wg < kClockSlots) clock_record(P, wg, 2);
 }
 
 // Combines the split-K partials of one token (decode, or a prefill row whose KV range was split).
@@ -689,6 +701,7 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
     }
   }
   __builtin_amdgcn_s_waitcnt(PS_VMCNT(0));  // no load may still be writing LDS when the wave ends
+  if (bid < kClockSlots) clock_record(P, kClockSlots + bid, 2);
 
   if (!active) return;
   const float ls = l + __shfl_xor(l, 32);
@@ -744,6 +757,10 @@ __global__ __launch_bounds__(kPrefillWaves * 64) void attention_kernel(StepParam
                                                                        int n_decode_wgs, int HW, int n_zsplit) {
   __shared__ __attribute__((aligned(16))) char lds[sizeof(PrefillStage) * kStages + kIdTiles * 4 * sizeof(int)];
   static_assert(sizeof(DecodeQ) * kDecodeWaves <= sizeof(PrefillStage) * kStages, "decode Q copies fit the prefill ring");
+  {
+    const int role_idx = (int)blockIdx.x < n_decode_wgs ? (int)blockIdx.x : (int)blockIdx.x - n_decode_wgs;
+    if (role_idx < kClockSlots) clock_record(P, ((int)blockIdx.x < n_decode_wgs ? 0 : kClockSlots) + role_idx, 0);
+  }
   if ((int)blockIdx.x < n_decode_wgs)
     decode_role(P, ditems, dslots, block_ids, n_slots, blockIdx.x, (DecodeQ*)lds);
   else
@@ -802,13 +819,16 @@ int prefill_tile_tokens(int G) { return (kPrefillWaves / prefill_heads_per_wg(G)
 
 int decode_waves_per_wg() { return kDecodeWaves; }
 
-hipError_t launch_attention(const StepParams& p, int n_slots, int n_tiles, hipStream_t s) {
+hipError_t launch_attention(const StepParams& p, int n_slots, int n_tiles, hipStream_t s, int* n_decode_wgs_out,
+                            int* n_prefill_wgs_out) {
   const int HW = prefill_heads_per_wg(p.G);
   const int nz = p.G / HW;
   const long long n_prefill_wgs = (long long)n_tiles * p.Hkv * nz;
   // decode workgroups: one per kDecodeWaves slots and kv-head, rounded up to a multiple of 8 (XCDs)
   const long long n_decode_wgs = n_slots > 0 ? (((long long)(n_slots + kDecodeWaves - 1) / kDecodeWaves * p.Hkv + 7) / 8 * 8) : 0;
   const long long grid = n_decode_wgs + n_prefill_wgs;
+  if (n_decode_wgs_out) *n_decode_wgs_out = (int)std::min<long long>(n_decode_wgs, 0x7fffffffLL);
+  if (n_prefill_wgs_out) *n_prefill_wgs_out = (int)std::min<long long>(n_prefill_wgs, 0x7fffffffLL);
   if (grid <= 0) return hipSuccess;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(attention_kernel, dim3((unsigned)grid), dim3(kPrefillWaves * 64), 0, s, p, p.ditems, p.dslots, p.block_ids,

@@ -305,11 +305,13 @@ def test_profiling_times_are_reported():
     got = lay.step(b, u16_to_dev(t.q), u16_to_dev(to_device_layout(cache.pool)))
     tm = B.ps_get_step_times(lay.ctx)
     assert tm["total_ms"] > 0 and tm["attention_ms"] > 0 and tm["decode_ms"] == 0 and tm["prefill_ms"] == 0
+    assert 500 < tm["decode_mhz"] < 2600 and 500 < tm["prefill_mhz"] < 2600      # the shader clock the roles ran at
     assert torch.equal(got, ref)
     B.ps_set_profiling(lay.ctx, 2)
     got = lay.step(b, u16_to_dev(t.q), u16_to_dev(to_device_layout(cache.pool)))
     tm = B.ps_get_step_times(lay.ctx)
     assert tm["decode_ms"] > 0 and tm["prefill_ms"] > 0
+    assert 500 < tm["decode_mhz"] < 2600 and 500 < tm["prefill_mhz"] < 2600
     assert abs(tm["attention_ms"] - tm["decode_ms"] - tm["prefill_ms"]) < 1e-3
     # the decode slots are cut differently in mode 2 (whole chip), so only closeness is asserted
     assert (got.float() - ref.float()).abs().max().item() < 2e-2
