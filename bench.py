@@ -371,18 +371,19 @@ def swap_bench(B, W, torch, np, dev):
     h1 = torch.empty(nbig, dtype=torch.uint8).pin_memory()
     h2 = torch.empty(nbig, dtype=torch.uint8).pin_memory()
 
-    def link(do_out, do_in, reps=6, own_streams=True):
+    def link(do_out, do_in, reps=6, own_streams=True, nbytes=nbig):
+        a1, a2, b1, b2 = h1[:nbytes], d1[:nbytes], d2[:nbytes], h2[:nbytes]
         torch.cuda.synchronize()
         t0 = _t.perf_counter()
         for _ in range(reps):
             if do_out:
                 with torch.cuda.stream(side_out if own_streams else torch.cuda.current_stream()):
-                    h1.copy_(d1, non_blocking=True)
+                    a1.copy_(a2, non_blocking=True)
             if do_in:
                 with torch.cuda.stream(side_in if own_streams else torch.cuda.current_stream()):
-                    d2.copy_(h2, non_blocking=True)
+                    b1.copy_(b2, non_blocking=True)
         torch.cuda.synchronize()
-        return reps * nbig / (_t.perf_counter() - t0) / 1e9
+        return reps * nbytes / (_t.perf_counter() - t0) / 1e9
 
     link(True, True, 1)
     link(True, True, 1, False)
@@ -391,6 +392,8 @@ def swap_bench(B, W, torch, np, dev):
     res["link_d2h_GBps"] = max(link(True, False), link(True, False, own_streams=False))
     res["link_h2d_GBps"] = max(link(False, True), link(False, True, own_streams=False))
     res["link_bidir_each_way_GBps"] = max(link(True, True) for _ in range(3))     # the best of three: this figure wanders from run to run
+    # the same with copies of the size a step moves (32 MiB each way per copy): what the copy engines reach at that grain
+    res["link_bidir_each_way_GBps_32MiB_copies"] = max(link(True, True, reps=48, nbytes=1 << 25) for _ in range(3))
     del d1, d2, h1, h2
     torch.cuda.empty_cache()
 
@@ -450,6 +453,7 @@ def swap_bench(B, W, torch, np, dev):
         r["overlap_in_GBps"] = step_bytes / t / 1e9
         r["overlap_in_step_ms"] = t * 1e3
         r["overlap_both_frac_of_bidir_link"] = r["overlap_both_each_way_GBps"] / res["link_bidir_each_way_GBps"]
+        r["overlap_both_frac_of_bidir_link_32MiB_copies"] = r["overlap_both_each_way_GBps"] / res["link_bidir_each_way_GBps_32MiB_copies"]
         r["overlap_out_frac_of_link"] = r["overlap_out_GBps"] / res["link_d2h_GBps"]
         r["overlap_in_frac_of_link"] = r["overlap_in_GBps"] / res["link_h2d_GBps"]
         # what the link alone needs for this step's bytes: the floor of a step that swaps 32 MiB each way

@@ -39,3 +39,22 @@ def test_profiling_batches_are_valid_and_seeded():
     for x, y in zip(a, b):
         assert np.array_equal(x.kv_len, y.kv_len) and np.array_equal(x.block_ids, y.block_ids)
         assert x.n_req >= 1 and len(set(x.block_ids.tolist())) == len(x.block_ids)
+
+
+def test_critical_path_form_recovers_a_planted_max():
+    """T = max(Eq. 7, t_c + w * longest walk): planted additive coefficients and w come back from the fit, and
+    the additive form alone cannot explain the same data."""
+    batches = E.profiling_batches(160, 11, W.LayerShape(32, 8), 60_000)
+    X = np.stack([E.features(b.q_start, b.kv_len) for b in batches])
+    walk = np.array([E.longest_walk(b.q_start, b.kv_len) for b in batches])
+    planted = np.array([3e-6, 2e-5, 6e-3, 5.5e-4, 0.016, 28.0])
+    y = np.maximum(X @ planted, planted[5] + 1.5 * walk)
+    assert (planted[5] + 1.5 * walk > X @ planted).sum() > 10          # the max binds on some batches
+    coef, w = E.fit_with_critical_path(X, walk, y)
+    err = np.abs(E.predict_max(coef, w, X, walk) - y) / y
+    assert abs(w - 1.5) <= 0.05 and err.mean() < 0.01
+    assert E.mape(E.fit(X, y), X, y) > 3 * err.mean()
+    b = W.build_batch(W.LayerShape(32, 8), [(1, 100), (64, 64 + 1000), (128, 128)], [1, 1, 1], np.random.default_rng(0), seed=0)
+    assert E.longest_walk(b.q_start, b.kv_len) == 17                    # ceil(1064 / 64)
+    b = W.build_batch(W.LayerShape(32, 8), [(1, 100)], [1], np.random.default_rng(0), seed=0)
+    assert E.longest_walk(b.q_start, b.kv_len) == 0
