@@ -565,7 +565,9 @@ def closed_loop_bench(B, W, torch, np, dev, swap, n_layers=4, steps=300):
     side (Sec. 5.3, block-management ablation): the copy budget as ps_form_batch sets it with the reload pipelined layer
     by layer; the same with everything reloaded whatever it costs (t_block tiny), pipelined, layer-synchronous, and all
     up front; and no host copies at all (evicted requests are recomputed).  pass_ms is GPU time of the forward passes
-    (from the first reload's issue to the last layer's end), summed over the rounds."""
+    (from the first reload's issue to the last layer's end), summed over the rounds.  The run's clock is the measured one:
+    every round advances it by the GPU time its pass took, and the tokens' delivery times on that clock are scored with
+    Eq. 3 (SLOs scaled to this 4-layer attention-only pass: first token 20 ms, 0.5 ms per later token)."""
     from paper_2512_12928_amd.closed_loop import ClosedLoop
     Hq, Hkv, M, Mh = 32, 8, 1200, 3000
     bb = 2 * Hkv * 16 * 128 * 2
@@ -573,8 +575,8 @@ def closed_loop_bench(B, W, torch, np, dev, swap, n_layers=4, steps=300):
     MS, US = 10 ** 9, 10 ** 6
     link = min(swap["link_h2d_GBps"], swap["link_d2h_GBps"])
     t_block = int(bb / (link * 1e9) * 1e12) * L
-    base = dict(n_classes=3, block_tokens=16, class_weight=[4, 2, 1], w_first=4, w_decode=1, ttft_slo_ps=2000 * MS,
-                tpot_slo_ps=100 * MS, a_p=3 * L, b_p=19 * L, c_p=5682 * L, a_d=554 * L, b_d=15784 * L, t_c=28 * US * L,
+    base = dict(n_classes=3, block_tokens=16, class_weight=[4, 2, 1], w_first=4, w_decode=1, ttft_slo_ps=20 * MS,
+                tpot_slo_ps=MS // 2, a_p=3 * L, b_p=19 * L, c_p=5682 * L, a_d=554 * L, b_d=15784 * L, t_c=28 * US * L,
                 eta_ps=2 * MS, tau_ps=30_000 * MS, gamma_num=9, gamma_den=10, beta_num=2, beta_den=1, rho_num=9, rho_den=10,
                 t_block_ps=t_block, n_off_base=8)
     trace = W.make_trace(3, 400, rate_per_s=4000.0, seed=21, prompt_mean=700, prompt_max=3000, out_mean=24, out_max=96)
@@ -595,12 +597,14 @@ def closed_loop_bench(B, W, torch, np, dev, swap, n_layers=4, steps=300):
     dev_order, host_order = rng.permutation(M), rng.permutation(Mh)
     for name, (cfg, mode) in arms.items():
         loop = ClosedLoop(Hq, Hkv, M, Mh, L, cfg, dev_order, host_order, rows, reload_mode=mode, out_dtype=B.PS_BF16, device=dev)
-        st = loop.run(trace, steps)
+        st = loop.run(trace, steps, clock="measured")
+        sc = loop.score(trace)
         loop.close()
         res[name] = dict(pass_ms=st["pass_ms"], ms_per_round=st["pass_ms"] / max(st["steps"], 1), tokens=st["tokens"],
                          evicted=st["evicted"], blocks_reloaded=st["blocks_reloaded"], blocks_offloaded=st["blocks_offloaded"],
                          recomputed_tokens=st["recomputed_tokens"],
-                         tokens_per_pass_ms=st["tokens"] / st["pass_ms"] if st["pass_ms"] else 0.0)
+                         tokens_per_pass_ms=st["tokens"] / st["pass_ms"] if st["pass_ms"] else 0.0,
+                         finished=sc["finished"], tdg_ratio=sc["tdg_ratio"], slo_attainment=sc["slo_attainment"])
         del loop
         torch.cuda.empty_cache()
     return res

@@ -46,6 +46,9 @@ class ClosedLoop:
         self.stats = dict(steps=0, evicted=0, blocks_reloaded=0, blocks_offloaded=0, tokens=0, prefill_tokens=0,
                           recomputed_tokens=0, pass_ms=0.0, dropped_in_flight=0)
         self.held: Dict[int, int] = {}    # rid -> tokens whose KV the engine has computed so far (to count recomputation)
+        self.sched_cfg = dict(sched_cfg)
+        self.last_pass_ms = 0.0
+        self.token_times: Dict[int, List[int]] = {}   # rid -> delivery times of its tokens (ps on the run's clock), in order
 
     def close(self):
         for _, tks in self.offloads:
@@ -134,7 +137,8 @@ class ClosedLoop:
         e1.record(self.compute)
         self.compute.synchronize()
         # the pass as an engine sees it: from the first reload's issue to the last layer's end (host waits included)
-        st["pass_ms"] += e0.elapsed_time(e1)
+        self.last_pass_ms = e0.elapsed_time(e1)
+        st["pass_ms"] += self.last_pass_ms
         if on_layer is not None:
             for ell in range(self.L):
                 on_layer(ell, fb, outs[ell])
@@ -149,8 +153,12 @@ class ClosedLoop:
             st["blocks_offloaded"] += len(fb["swap_out_dev_blocks"]) * self.L
         return fb
 
-    def run(self, trace, max_steps: int, on_layer: Optional[Callable] = None) -> Dict:
-        """Virtual clock as in ps_sched_simulate: advances by T_pd(B) of every round."""
+    def run(self, trace, max_steps: int, on_layer: Optional[Callable] = None, clock: str = "estimator") -> Dict:
+        """clock "estimator": the virtual clock of ps_sched_simulate, which advances by T_pd(B) of every round;
+        "measured": it advances by the GPU time the round's forward pass took (from the first reload's issue to the last
+        layer's end), so that the batch former sees the time an engine would.  Tokens are delivered when their pass
+        ends; score() applies Eq. 3 to the delivery times."""
+        assert clock in ("estimator", "measured")
         pending = sorted(trace, key=lambda x: (x.arrival_ps, x.rid))
         nxt = now = 0
         while self.stats["steps"] < max_steps:
@@ -164,5 +172,22 @@ class ClosedLoop:
                 now = pending[nxt].arrival_ps
                 continue
             fb = self.step(now, on_layer)
-            now += int(fb["t_batch"]) if fb["t_batch"] > 0 else self.eta
+            if fb["n_req"] == 0:
+                now += self.eta
+                continue
+            now += int(self.last_pass_ms * 1e9) if clock == "measured" else int(fb["t_batch"])
+            for rid in fb["emitted_req"].tolist():
+                self.token_times.setdefault(int(rid), []).append(now)
         return dict(self.stats)
+
+    def score(self, trace) -> Dict:
+        """Eq. 3 over the requests that finished in run(): token-level deadline-aware gain against the gain with every
+        token on time, and SLO attainment (ps_tdg_score does the arithmetic)."""
+        gain = ideal = ok = done = 0
+        for p in trace:
+            tt = self.token_times.get(p.rid, [])
+            if len(tt) < p.out_len:
+                continue
+            g, i, a = B.ps_tdg_score(self.sched_cfg, p.prio, p.out_len, np.asarray(tt, np.int64) - p.arrival_ps)
+            gain, ideal, ok, done = gain + g, ideal + i, ok + a, done + 1
+        return dict(finished=done, tdg_ratio=gain / ideal if ideal else 0.0, slo_attainment=ok / done if done else 0.0)

@@ -59,3 +59,30 @@ def test_closed_loop_every_layer_matches_oracle(mode, t_block):
         assert st["blocks_reloaded"] > 0
     else:
         assert st["recomputed_tokens"] > 0          # the slow link's budget leaves blocks behind: they are computed again
+
+
+def test_loop_clocks_and_scores():
+    """Without memory pressure (nothing is evicted, so offload reports cannot change a decision) the loop on the
+    estimator's clock delivers every token at the time ps_sched_simulate says, and its Eq. 3 score is the
+    simulation's.  On the measured clock (the GPU time of every pass) the same trace still finishes and scores."""
+    Hq, Hkv, M, Mh, L = 8, 2, 1500, 64, 2
+    _, lc = cfg_pair(tau=3000 * MS)
+    tr = W.make_trace(3, 30, rate_per_s=300.0, seed=9, prompt_mean=150, prompt_max=500, out_mean=10, out_max=30)
+    rng = np.random.default_rng(9)
+    dev_order, host_order = rng.permutation(M), rng.permutation(Mh)
+    sim = B.ps_sched_simulate(lc, dev_order, host_order, tr, 400)
+    assert sim["finished"] == len(tr)
+    loop = ClosedLoop(Hq, Hkv, M, Mh, L, lc, dev_order, host_order, rows)
+    st = loop.run(tr, 400)
+    got = loop.score(tr)
+    for i, p in enumerate(tr):
+        assert np.array_equal(np.asarray(loop.token_times[p.rid], np.int64) - p.arrival_ps, sim["token_times"][i]), p.rid
+    loop.close()
+    assert st["evicted"] == 0
+    assert got["finished"] == sim["finished"] and got["tdg_ratio"] == sim["gain"] / sim["ideal_gain"]
+    loop = ClosedLoop(Hq, Hkv, M, Mh, L, lc, dev_order, host_order, rows)
+    loop.run(tr, 400, clock="measured")
+    got_m = loop.score(tr)
+    loop.close()
+    print("estimator clock", got, "measured clock", got_m)
+    assert got_m["finished"] == len(tr) and 0.0 < got_m["tdg_ratio"] <= 1.0
