@@ -36,6 +36,27 @@ def build(verbose: bool = True) -> str:
     return LIB_PATH
 
 
+PROBE_PATH = os.path.join(HERE, "ps_machine_probe")
+
+
+def build_probe(verbose: bool = True) -> str:
+    """The stand-alone machine probe (csrc/ps_machine_probe.hip): matrix-pipe rate and shader clock against operand
+    bits, cache-streaming rate per CU, and both kinds of waves on one CU.  Run it on the GPU machine as
+    paper_2512_12928_amd/ps_machine_probe [mfma|stream|share]."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wall", os.path.join(CSRC, "ps_machine_probe.hip"), "-o", PROBE_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    if verbose and out.strip():
+        print(out)
+    return PROBE_PATH
+
+
 def build_host_checks(out_path: str, driver: str, verbose: bool = False) -> str:
     """CPU build of the whole library plus a driver program with AddressSanitizer and UndefinedBehaviorSanitizer on the
     host code (the device code is compiled as usual and never runs): for the host logic -- the batch former, the launch
@@ -56,4 +77,6 @@ def build_host_checks(out_path: str, driver: str, verbose: bool = False) -> str:
 if __name__ == "__main__":
     build()
     print("built", LIB_PATH)
+    build_probe()
+    print("built", PROBE_PATH)
     sys.exit(0)
