@@ -146,7 +146,9 @@ void ps_destroy(ps_ctx* ctx);
 
 /* Device workspace (split-K partial results of the decode kernels) needed by ps_step for any
  * batch with n_req <= max_req, n_tokens <= max_tokens and at most max_table_entries block-table
- * entries. */
+ * entries.  (Engine-internal: the paper describes no attention kernel, Sec. 4.1 only says that decode
+ * is memory-bound and prefill compute-bound; the same holds for ps_plan_decode, ps_plan_launch and the
+ * profiling calls below.) */
 int ps_workspace_bytes(const ps_ctx* ctx, int32_t max_req, int32_t max_tokens,
                        int64_t max_table_entries, size_t* out_bytes);
 
@@ -231,9 +233,12 @@ int ps_plan_decode(const ps_layer_cfg* cfg, const ps_batch* batch, int32_t waves
  * Errors as for ps_step's validation. */
 int ps_plan_launch(const ps_layer_cfg* cfg, const ps_batch* batch, int32_t n_cus, int32_t* out6);
 
-/* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds).
+/* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds), and the shader
+ * clock its attention workgroups ran at (clock counters read in the kernel).  The first call with a
+ * non-zero mode allocates 128 KiB of device memory for those counters; no step allocates for them.
  * mode 0: off; 1: the phases as they run; 2: the decode and the prefill work of the attention
- * phase in launches of their own, one after the other. PS_EINVAL for any other mode. */
+ * phase in launches of their own, one after the other. PS_EINVAL for any other mode; PS_EHIP if the
+ * allocation fails. */
 int ps_set_profiling(ps_ctx* ctx, int mode);
 /* Blocks until the last profiled step has finished, then fills *out. */
 int ps_get_step_times(ps_ctx* ctx, ps_step_times* out);
