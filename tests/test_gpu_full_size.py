@@ -63,14 +63,29 @@ def run_step(batch, pool, q, kn, vn, out_dtype):
     return out.float().cpu().numpy().astype(np.float64)
 
 
+REL_RMS = 0.03
+
+
 def assert_close(got, want, bf16_out, what):
+    """Two bounds on every element.  The absolute one is the stated tolerance.  The second scales with the row:
+    |err| <= REL_RMS * rms(o[token, head, :]) (+ half an ulp of a bf16 output).  The one rounding coarser than fp32
+    on the path is P to bf16 (nearest even) ahead of P.V, at most a relative 2^-9 per term, so an element's error
+    stays near 2^-9 |o| at worst and |o| reaches 4 to 5 times its row's rms: over the 10^7..10^8 elements of a
+    workload the worst element measures 0.009..0.012 of its row's rms, the same for every workload and recipe.
+    At a decode length of tens of thousands of tokens, where |o| itself is below the absolute tolerance, a dropped
+    KV partition or split-K partial moves elements by a good fraction of the row's rms and a dropped 32-token tile
+    by several hundredths at the row's worst element, so this bound sees them under the plain N(0,1) recipe too."""
     assert np.isfinite(got).all(), what + ": non-finite output"
     err = np.abs(got - want)
-    bound = 1e-2 + (2.0 ** -8) * np.abs(want) if bf16_out else 1e-2
-    bad = err > bound
+    half_ulp = (2.0 ** -8) * np.abs(want) if bf16_out else 0.0
+    bad = err > 1e-2 + half_ulp
     assert not bad.any(), "%s: %d elements off, max abs err %.4g at %s" % (
         what, int(bad.sum()), err.max(), np.unravel_index(err.argmax(), err.shape))
-    return float(err.max())
+    rms = np.sqrt((want ** 2).mean(axis=-1, keepdims=True))
+    rel = (err - half_ulp) / rms
+    assert (rel <= REL_RMS).all(), "%s: %d elements beyond %.3g of their row's rms, worst %.4g at %s" % (
+        what, int((rel > REL_RMS).sum()), REL_RMS, rel.max(), np.unravel_index(rel.argmax(), rel.shape))
+    return float(err.max()), float(rel.max())
 
 
 @pytest.mark.parametrize("recipe", ["normal", "needle"])
@@ -84,9 +99,9 @@ def test_full_size_all_rows(idx, recipe):
         batch.name, recipe, batch.n_req, batch.n_tokens, time.time() - t0, np.abs(want).max()), flush=True)
     for out_dtype, name in ((B.PS_F32, "f32"), (B.PS_BF16, "bf16")):
         got = run_step(batch, pool, q, kn, vn, out_dtype)
-        worst = assert_close(got, want, out_dtype == B.PS_BF16, "%s %s %s" % (batch.name, recipe, name))
-        print("   %s output: worst abs err %.4g over all %d x %d x 128 elements" % (name, worst, batch.n_tokens,
-                                                                                   batch.shape.n_q_heads), flush=True)
+        worst, rel = assert_close(got, want, out_dtype == B.PS_BF16, "%s %s %s" % (batch.name, recipe, name))
+        print("   %s output: worst abs err %.4g, worst err / row rms %.4g, over all %d x %d x 128 elements" % (
+            name, worst, rel, batch.n_tokens, batch.shape.n_q_heads), flush=True)
     # the append is a copy: after the step the cache holds the generated prefix plus the new rows, bit for bit
     for r in [int(x) for x in batch.prefill_reqs] + [int(x) for x in batch.decode_reqs[::16]]:
         k, v = logical_kv(batch, pool, kn, vn, r)
