@@ -105,6 +105,15 @@ typedef struct {
                               Measured on an MI355X with 512 blocks in 16 runs of 32: slower one way
                               (41 against 54 GB/s), faster when both directions run at once (36
                               against 32 GB/s each way), hence opt-in.  In [0, 65536]              */
+  int32_t mixed_launch;    /* how the attention launch of a batch with both decode tokens and prefill
+                              chunks is laid out.  1: the two kinds of work on disjoint compute units
+                              (decode workgroups first, the prefill workgroups take the rest).  2: every
+                              workgroup carries both (a prefill tile walk on eight waves, next to them two
+                              waves that fetch the walk's tiles and two that walk decode slots; needs
+                              decode_chunk and decode_waves 0, else as 1).  0 (default): the library picks:
+                              2 when the prefill work outweighs the decode work 2.2 times and there are at
+                              least two prefill workgroups per compute unit (measured 6 % faster on such
+                              a launch, no faster or slower otherwise), else 1.                       */
 } ps_layer_cfg;
 
 /* One mixed batch (the output of Alg. 1 as the attention layer sees it). HOST arrays. */
@@ -227,11 +236,23 @@ int ps_plan_decode(const ps_layer_cfg* cfg, const ps_batch* batch, int32_t waves
  * compute units (the decode work and the prefill work of a mixed batch share one launch; the decode
  * workgroups, one compute unit each, come first and the prefill workgroups take the rest and inherit the
  * decode units as those finish). For tests of that host logic.
- *   out6[0] decode waves     out6[1] decode slots (waves / Hkv)     out6[2] decode workgroups
+ *   out6[0] decode waves     out6[1] decode slots (waves / Hkv)
+ *   out6[2] decode workgroups; 0 for a mixed batch whose workgroups carry both kinds of work (cfg.mixed_launch):
+ *           then every prefill workgroup also walks up to two of the decode slots
  *   out6[3] prefill workgroups     out6[4] KV tiles (64 tokens) per partition of split prefill rows, 0 = no row split
  *   out6[5] split-K partial slots the step uses
  * Errors as for ps_step's validation. */
 int ps_plan_launch(const ps_layer_cfg* cfg, const ps_batch* batch, int32_t n_cus, int32_t* out6);
+
+/* Diagnostic of the launch whose workgroups carry both kinds of work (cfg.mixed_launch).  Its waves hand K/V tiles
+ * to one another through flags in LDS, and every wait for a flag is bounded: a wave that has waited about a tenth
+ * of a second for one stops waiting (its outputs are then wrong) and counts itself here, so that a mistake in the
+ * hand-over shows as a number and a failed comparison, never as a launch that does not end.  (Engine-internal, no
+ * counterpart in the paper.)
+ *   out   HOST: waves that gave up since the library was loaded, over all contexts of the current device; 0 unless
+ *         the library is broken.  The call synchronises the device.
+ * PS_EINVAL for a NULL argument, PS_EHIP if the counter cannot be read. */
+int ps_mixed_launch_faults(uint32_t* out);
 
 /* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds), and the shader
  * clock its attention workgroups ran at (clock counters read in the kernel).  The first call with a

@@ -25,7 +25,7 @@ EXPORTS = [
     "ps_last_error", "ps_create", "ps_destroy", "ps_workspace_bytes", "ps_step", "ps_step_next_layer", "ps_set_profiling",
     "ps_get_step_times", "ps_plan_decode", "ps_plan_launch", "ps_swap_out", "ps_swap_in", "ps_ticket_query", "ps_ticket_wait",
     "ps_sched_create", "ps_sched_destroy", "ps_sched_add_request", "ps_form_batch", "ps_sched_counts",
-    "ps_sched_offloads_done", "ps_tdg_score", "ps_sched_simulate", "ps_step_static",
+    "ps_sched_offloads_done", "ps_tdg_score", "ps_sched_simulate", "ps_step_static", "ps_mixed_launch_faults",
 ]
 
 
@@ -36,7 +36,7 @@ class ps_layer_cfg(C.Structure):
                 ("swap_workgroups", C.c_int32), ("own_streams", C.c_int32), ("prefill_split_tiles", C.c_int32),
                 ("decode_waves", C.c_int32), ("plan_stream_TBps", C.c_float), ("plan_tile_step_us", C.c_float),
                 ("plan_merge_launch_steps", C.c_float), ("plan_merge_row_steps", C.c_float), ("plan_decode_share", C.c_float),
-                ("plan_decode_knee_cus", C.c_int32), ("swap_dma_runs", C.c_int32)]
+                ("plan_decode_knee_cus", C.c_int32), ("swap_dma_runs", C.c_int32), ("mixed_launch", C.c_int32)]
 
 
 class ps_batch(C.Structure):
@@ -110,6 +110,7 @@ def lib():
         L.ps_step.argtypes = [C.c_void_p, C.POINTER(ps_batch)] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
         L.ps_step_static.argtypes = [C.c_void_p, C.POINTER(ps_batch)] + [C.c_void_p] * 5 + [C.c_void_p, C.c_uint64]
         L.ps_plan_launch.argtypes = [C.POINTER(ps_layer_cfg), C.POINTER(ps_batch), C.c_int32, C.POINTER(C.c_int32)]
+        L.ps_mixed_launch_faults.argtypes = [C.POINTER(C.c_uint32)]
         L.ps_step_next_layer.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p, C.c_uint64]
         L.ps_set_profiling.argtypes = [C.c_void_p, C.c_int]
         L.ps_get_step_times.argtypes = [C.c_void_p, C.POINTER(ps_step_times)]
@@ -174,12 +175,13 @@ def ps_create(n_q_heads: int, n_kv_heads: int, n_device_blocks: int, n_host_bloc
               softmax_scale: float = 0.0, out_dtype: int = PS_BF16, decode_chunk: int = 0,
               swap_workgroups: int = 0, head_dim: int = 128, block_tokens: int = 16,
               own_streams: int = 0, prefill_split_tiles: int = 0, decode_waves: int = 0, **plan) -> int:
-    """plan: the planner constants of ps_layer_cfg by name (plan_stream_TBps, ...); 0 or absent = default."""
+    """plan: the planner constants of ps_layer_cfg by name (plan_stream_TBps, ...), swap_dma_runs, mixed_launch;
+    0 or absent = default."""
     cfg = ps_layer_cfg(n_q_heads, n_kv_heads, head_dim, block_tokens, n_device_blocks, n_host_blocks,
                        softmax_scale, out_dtype, decode_chunk, swap_workgroups, own_streams, prefill_split_tiles,
                        decode_waves)
     for k, v in plan.items():
-        if not (k.startswith("plan_") or k == "swap_dma_runs"):
+        if not (k.startswith("plan_") or k in ("swap_dma_runs", "mixed_launch")):
             raise TypeError("unknown ps_layer_cfg field %r" % k)
         setattr(cfg, k, v)
     h = C.c_void_p()
@@ -253,6 +255,12 @@ def ps_plan_launch(n_q_heads: int, n_kv_heads: int, n_device_blocks: int, batch,
     del keep
     return dict(zip(("decode_waves", "decode_slots", "decode_workgroups", "prefill_workgroups", "prefill_split_tiles",
                      "partial_slots"), [int(x) for x in out]))
+
+
+def ps_mixed_launch_faults() -> int:
+    n = C.c_uint32()
+    _check(lib().ps_mixed_launch_faults(C.byref(n)))
+    return int(n.value)
 
 
 def ps_step_next_layer(ctx: int, q, k_new, v_new, kv_cache, out, workspace, workspace_bytes: int,

@@ -106,6 +106,7 @@ struct ps_ctx {
   bool prof_valid = false;
   int prof_mode = 0;
   DecodePlan plan;
+  bool plan_fused = false;  // the plan's decode slots are laid out for the launch whose workgroups carry both kinds of work
   std::vector<ps::PrefillTile> ptiles;
   std::vector<ps::AppendItem> aitems;
   // What ps_step_next_layer needs of the last ps_step: where its batch description sits on the device
@@ -462,6 +463,14 @@ const char* ps_last_error(void) { return g_err.c_str(); }
 // used by the host-only scheduler translation unit
 void ps_internal_set_error(const char* text) { g_err = text ? text : ""; }
 
+int ps_mixed_launch_faults(uint32_t* out) {
+  if (!out) return fail(PS_EINVAL, "ps_mixed_launch_faults: NULL argument");
+  unsigned int n = 0;
+  if (ps::fused_gave_up_count(&n) != 0) return fail(PS_EHIP, "ps_mixed_launch_faults: reading the device counter failed");
+  *out = n;
+  return PS_OK;
+}
+
 static int check_cfg(const ps_layer_cfg* cfg) {
   if (cfg->head_dim != ps::kHeadDim) return fail(PS_EINVAL, "head_dim must be 128 (got %d)", cfg->head_dim);
   if (cfg->block_tokens != ps::kBlockTokens)
@@ -493,6 +502,7 @@ static int check_cfg(const ps_layer_cfg* cfg) {
     if (!(v >= 0.f) || std::isinf(v)) return fail(PS_EINVAL, "planner constants must be finite and >= 0 (0 = default)");
   if (cfg->plan_decode_share > 1.f) return fail(PS_EINVAL, "plan_decode_share must be at most 1");
   if (cfg->plan_decode_knee_cus < 0) return fail(PS_EINVAL, "plan_decode_knee_cus must be >= 0");
+  if (cfg->mixed_launch < 0 || cfg->mixed_launch > 2) return fail(PS_EINVAL, "mixed_launch must be 0, 1 or 2");
   return PS_OK;
 }
 
@@ -590,8 +600,11 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
   // request of n table entries has at most (n + 1) / 2 tiles) and there are no more slots than one per
   // decode wave and kv-head.
   const size_t slots_by_tiles = (size_t)((max_table_entries + max_req) / (2 * kMinSlotTiles)) + 1;
-  const size_t slots_by_waves =
+  size_t slots_by_waves =
       (size_t)((c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus) / c->cfg.n_kv_heads) + 1;
+  if (c->cfg.mixed_launch == 2)  // three slots per prefill work item: a query tile, or one of its at most 8 partitions
+    slots_by_waves = std::max(slots_by_waves,
+                              (size_t)ps::fused_decode_slots(1, c->G) * 8 * ((size_t)max_tokens / ps::prefill_tile_tokens(c->G) + (size_t)max_req) + 1);
   const size_t max_parts = (size_t)max_req + (c->cfg.decode_chunk > 0
                                                  ? (size_t)(max_table_entries * ps::kBlockTokens / c->cfg.decode_chunk)
                                                  : std::min(slots_by_tiles, slots_by_waves));
@@ -746,7 +759,24 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
   // by 5 %: prefill workgroups inherit CUs that decode leaves early, never the other way round).
   {
     int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
-    if (c->cfg.decode_waves == 0 && c->profiling != 2 && !decode_reqs.empty() && !tiles.empty()) {
+    // Every workgroup carries both kinds of work (two decode slots per prefill work item and z-split).  Forced by
+    // cfg.mixed_launch = 2; picked by the library when the launch is dominated by prefill walks and has at least
+    // two prefill workgroups per compute unit: measured on an MI355X, 6 % faster than disjoint units with the
+    // prefill work priced at 2.6 times the decode work, no faster at 1.85 times, slower when decode dominates.
+    const bool fusable = c->cfg.decode_waves == 0 && c->cfg.decode_chunk == 0 && c->profiling != 2 && !decode_reqs.empty() &&
+                         !tiles.empty() && ps::fused_supports(c->G) &&
+                         (int64_t)ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads <= INT32_MAX;
+    c->plan_fused = fusable && c->cfg.mixed_launch == 2;
+    if (fusable && c->cfg.mixed_launch == 0) {
+      const PlanTuning tune = tuning_of(c->cfg);
+      const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / (tune.stream_TBps * 1e6);  // us
+      const double t_p = prefill_steps * tune.tile_step_us;
+      const int64_t wgs = (int64_t)tiles.size() * c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
+      c->plan_fused = t_p >= 2.2 * t_d && wgs >= 2 * (int64_t)c->n_cus;
+    }
+    if (c->plan_fused) {
+      waves = ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads;
+    } else if (c->cfg.decode_waves == 0 && c->profiling != 2 && !decode_reqs.empty() && !tiles.empty()) {
       const PlanTuning tune = tuning_of(c->cfg);
       const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / (tune.stream_TBps * 1e6);  // us
       const double t_p = prefill_steps * tune.tile_step_us;
@@ -846,7 +876,12 @@ static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps
     PS_HIP(ps::launch_attention(P, 0, (int)c->ptiles.size(), stream, nullptr, &c->prof_wgs[1]));
     PS_HIP(hipEventRecord(c->prof_ev[4], stream));
   } else {
-    PS_HIP(ps::launch_attention(P, n_slots, (int)c->ptiles.size(), stream, &c->prof_wgs[0], &c->prof_wgs[1]));
+    if (c->plan_fused) {
+      PS_HIP(ps::launch_fused(P, n_slots, (int)c->ptiles.size(), stream, &c->prof_wgs[1]));
+      c->prof_wgs[0] = c->prof_wgs[1];
+    } else {
+      PS_HIP(ps::launch_attention(P, n_slots, (int)c->ptiles.size(), stream, &c->prof_wgs[0], &c->prof_wgs[1]));
+    }
     if (prof) {
       PS_HIP(hipEventRecord(c->prof_ev[3], stream));
       PS_HIP(hipEventRecord(c->prof_ev[4], stream));
@@ -1113,7 +1148,7 @@ int ps_plan_launch(const ps_layer_cfg* cfg, const ps_batch* b, int32_t n_cus, in
   const int dw = ps::decode_waves_per_wg();
   out6[0] = n_slots * cfg->n_kv_heads;
   out6[1] = n_slots;
-  out6[2] = n_slots > 0 ? (n_slots + dw - 1) / dw * cfg->n_kv_heads : 0;
+  out6[2] = c.plan_fused ? 0 : (n_slots > 0 ? (n_slots + dw - 1) / dw * cfg->n_kv_heads : 0);
   out6[3] = (int32_t)c.ptiles.size() * cfg->n_kv_heads * (c.G / ps::prefill_heads_per_wg(c.G));
   out6[4] = (int32_t)split;
   out6[5] = n_parts;

@@ -90,6 +90,13 @@ hipError_t launch_merge(const StepParams& p, int first, int n_merge, hipStream_t
 // n_decode_wgs_out / n_prefill_wgs_out (may be NULL): the workgroups of each role in the launch.
 hipError_t launch_attention(const StepParams& p, int n_slots, int n_tiles, hipStream_t s, int* n_decode_wgs_out,
                             int* n_prefill_wgs_out);
+// The same batch with every workgroup carrying both kinds of work (ps_fused.hip): n_tiles prefill work items as
+// above, whose workgroup bid also walks the decode slots (bid / Hkv) * 3 + 0..2 for kv-head bid % Hkv, so
+// n_slots <= fused_decode_slots(n_tiles, G).  Needs fused_supports(G).
+hipError_t launch_fused(const StepParams& p, int n_slots, int n_tiles, hipStream_t s, int* n_wgs_out);
+int fused_decode_slots(int n_tiles, int G);
+bool fused_supports(int G);
+int fused_gave_up_count(unsigned int* out);
 int decode_waves_per_wg();
 // tile_tokens: query tokens per workgroup tile as returned by prefill_tile_tokens(G).
 int prefill_tile_tokens(int G);

@@ -12,42 +12,9 @@
 // load and the lanes of one load instruction cover runs of 256 bytes or more.
 #include <type_traits>
 
-#include "ps_internal.h"
+#include "ps_device.h"
 
 namespace ps {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-#define PS_NEG_INF (-__builtin_inff())
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  f32x2 v = {a, b};
-  bf16x2 r = __builtin_convertvector(v, bf16x2);  // round to nearest even
-  return __builtin_bit_cast(uint32_t, r);
-}
-
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-// Zero the 16-bit elements e (0..3) of v whose token index first+e is >= limit.
-__device__ __forceinline__ uint2 zero_from(uint2 v, int first, int limit) {
-  uint32_t m0 = (first + 0 < limit ? 0x0000FFFFu : 0u) | (first + 1 < limit ? 0xFFFF0000u : 0u);
-  uint32_t m1 = (first + 2 < limit ? 0x0000FFFFu : 0u) | (first + 3 < limit ? 0xFFFF0000u : 0u);
-  v.x &= m0;
-  v.y &= m1;
-  return v;
-}
-
-__device__ __forceinline__ const uint16_t* k_slice(const uint16_t* cache, int block, int Hkv, int g) {
-  return cache + ((size_t)(block * 2 + 0) * Hkv + g) * kSliceElems;
-}
-__device__ __forceinline__ const uint16_t* v_slice(const uint16_t* cache, int block, int Hkv, int g) {
-  return cache + ((size_t)(block * 2 + 1) * Hkv + g) * kSliceElems;
-}
 
 // ------------------------------------------------------------------------------------ prologue
 // One launch, 256 threads per workgroup, two kinds of workgroup:
@@ -117,17 +84,6 @@ __global__ __launch_bounds__(256) void prologue_kernel(StepParams P, const uint4
   }
 }
 
-// Profiling only (P.clocks != NULL): the first thread of workgroup `slot` notes the shader-clock counter and
-// the constant 100 MHz counter, at its start (at = 0) and at its end (at = 2); the host turns the two
-// differences into the shader clock the workgroup ran at.  Decode workgroups use slots [0, kClockSlots),
-// prefill workgroups [kClockSlots, 2 * kClockSlots); workgroups beyond that are not recorded.
-__device__ __forceinline__ void clock_record(const StepParams& P, int slot, int at) {
-  if (P.clocks != nullptr && threadIdx.x == 0 && slot < 2 * kClockSlots) {
-    P.clocks[slot * 4 + at] = __builtin_amdgcn_s_memtime();
-    P.clocks[slot * 4 + at + 1] = __builtin_amdgcn_s_memrealtime();
-  }
-}
-
 // ------------------------------------------------------------------------------------ decode
 // Split-K decode attention, HBM-bound.  grid (ceil(n_slots / 4), Hkv), 256 threads: four waves
 // that work independently (one slot each; a workgroup only pins them to the four SIMDs of one
@@ -150,28 +106,6 @@ __device__ __forceinline__ void clock_record(const StepParams& P, int slot, int 
 // covers, per 8-dim group, all 16 slots of a block: runs of 256 bytes.  In the 32x32 result
 // layout lane (head j, k-group h2) holds, for MFMA step u, the 8 consecutive tokens
 // 16u + 8*h2 .. +7: its V operand is one 16-byte run of the dim-major V block.
-
-__device__ __forceinline__ bf16x8 load_stream16(const uint16_t* p) {
-  return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4*)p));
-}
-
-// Zero the 16-bit elements e (0..7) of v whose token index first+e is >= limit.
-__device__ __forceinline__ bf16x8 zero_from8(bf16x8 v, int first, int limit) {
-  u32x4 w = __builtin_bit_cast(u32x4, v);
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    w[i] &= (first + 2 * i < limit ? 0x0000FFFFu : 0u) | (first + 2 * i + 1 < limit ? 0xFFFF0000u : 0u);
-  return __builtin_bit_cast(bf16x8, w);
-}
-
-// max over lanes l and l ^ 32 (both lanes get it), on the VALU: v_permlane32_swap exchanges the upper
-// half of its first operand with the lower half of its second.
-__device__ __forceinline__ float xor32_max(float x) {
-  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
-  asm volatile("" : "+v"(b));  // two distinct registers for the swap
-  auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
-  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
-}
 
 // The work lists and the block tables come as separate restrict-qualified kernel parameters: only
 // then does the compiler know that the kernel's own stores cannot change them, and fetches them
@@ -442,20 +376,6 @@ constexpr int kStages = 4;
 constexpr int kLoadsPerTile = 4;
 constexpr int kIdTiles = 512;       // block ids of up to this many KV tiles (32k tokens) are kept in LDS    // global->LDS loads each wave issues per tile
 
-// s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding)
-#define PS_VMCNT(n) (((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
-
-// One lane's 16 bytes at `gptr` -> LDS at lds_base + lane*16 (lds_base wave-uniform).  The LDS
-// base travels in M0, which is saved and restored around the load.
-__device__ __forceinline__ void load_to_lds16(const void* gptr, uint32_t lds_base) {
-  uint32_t saved;
-  asm volatile(
-      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
-      : "=&s"(saved)
-      : "v"(gptr), "s"(lds_base)
-      : "memory");
-}
-
 // Four block-table entries through the scalar cache.  Written as asm because the compiler will
 // not use scalar loads next to the memory-clobbering LDS loads above, and its vector-load
 // fallback would wait for vmcnt(0), i.e. for every tile still in flight.
@@ -465,14 +385,6 @@ __device__ __forceinline__ void load_ids(const int* p0, const int* p1, const int
       "s_load_dword %3, %7, 0x0\n\ts_waitcnt lgkmcnt(0)"
       : "=&s"(id[0]), "=&s"(id[1]), "=&s"(id[2]), "=&s"(id[3])
       : "s"(p0), "s"(p1), "s"(p2), "s"(p3));
-}
-
-// max of three without the NaN-quieting moves the compiler wraps around fmaxf of MFMA results
-// (the inputs here are never NaN: finite scores or -inf)
-__device__ __forceinline__ float max3(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
 }
 
 struct PrefillHalf {

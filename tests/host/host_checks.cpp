@@ -129,6 +129,7 @@ static int run_planners() {
     cfg.n_device_blocks = 200000;
     if (iter % 7 == 3) cfg.decode_chunk = 512;
     if (iter % 5 == 2) cfg.prefill_split_tiles = (int32_t)rnd_in(-1, 9);
+    cfg.mixed_launch = iter % 3;
     const int n_dec = (int)rnd_in(0, 300), n_pre = (int)rnd_in(n_dec ? 0 : 1, 4);
     std::vector<int32_t> q_start(1, 0), kv_len, bt_start(1, 0), ids;
     for (int r = 0; r < n_dec + n_pre; ++r) {

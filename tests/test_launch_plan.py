@@ -41,13 +41,37 @@ def test_shares_of_the_benchmark_workloads():
     of the chip.  One long chunk of equally long workgroups that outweighs the decode work: decode gets most
     of the chip first and leaves it to the prefill workgroups.  Many prefill workgroups of all lengths next to
     moderate decode work: the proportional share again."""
-    p2, p4, p5 = plan(W.make_workload(2)), plan(W.make_workload(4)), plan(W.make_workload(5))
+    p2, p4, p5 = (plan(W.make_workload(i), mixed_launch=1) for i in (2, 4, 5))
     assert 170 <= p2["decode_workgroups"] <= 200 and p2["prefill_split_tiles"] > 0      # 64-tile rows cut in two
     assert 160 <= p4["decode_workgroups"] <= 248 and p4["prefill_workgroups"] == 512 and p4["prefill_split_tiles"] == 0
     assert 64 <= p5["decode_workgroups"] <= 128 and p5["prefill_workgroups"] == 2048
     for p in (p2, p4, p5):
         assert p["decode_waves"] == p["decode_slots"] * 8
         assert p["decode_workgroups"] == -(-p["decode_slots"] // 4) * 8
+
+
+def test_which_mixed_batches_get_workgroups_that_carry_both_kinds_of_work():
+    """Left to the library (mixed_launch = 0), only the launch dominated by prefill walks (workload 4: the prefill
+    work priced at 2.6 times the decode work, two prefill workgroups per compute unit) is laid out that way; forced
+    (2), any mixed batch is, and every prefill workgroup then walks at most two decode slots of its kv-head."""
+    p2, p4, p5 = (plan(W.make_workload(i)) for i in (2, 4, 5))
+    assert p2["decode_workgroups"] > 0 and p5["decode_workgroups"] > 0
+    assert p2 == plan(W.make_workload(2), mixed_launch=1) and p5 == plan(W.make_workload(5), mixed_launch=1)
+    assert p4["decode_workgroups"] == 0 and p4["prefill_workgroups"] == 512 and p4 == plan(W.make_workload(4), mixed_launch=2)
+    for i in (2, 4, 5):
+        b = W.make_workload(i)
+        p = plan(b, mixed_launch=2)
+        assert p["decode_workgroups"] == 0 and p["decode_waves"] == p["decode_slots"] * 8
+        assert 0 < p["decode_slots"] <= min(2 * p["prefill_workgroups"] // 8, decode_tiles(b) // 4)
+        assert p["prefill_workgroups"] == plan(b, mixed_launch=1)["prefill_workgroups"]
+    # decode-only and prefill-only batches are not affected, nor is a batch with fixed decode partitions or wave count
+    b = W.build_batch(W.LayerShape(32, 8), [(1, 4000)] * 300, [1] * 300, np.random.default_rng(1), seed=1)
+    assert plan(b, mixed_launch=2) == plan(b)
+    b = W.make_workload(4)
+    assert plan(b, mixed_launch=2, decode_chunk=256)["decode_workgroups"] > 0
+    assert plan(b, mixed_launch=2, decode_waves=512)["decode_workgroups"] > 0
+    with pytest.raises(B.PsError):
+        plan(b, mixed_launch=3)
 
 
 @pytest.mark.parametrize("seed", range(12))
@@ -61,7 +85,7 @@ def test_random_batches_keep_the_launch_within_bounds(seed):
         lq = int(rng.integers(2, 3000))
         items.append((lq, lq + int(rng.integers(0, 20000))))
     b = W.build_batch(W.LayerShape(Hq, Hkv), items, [1] * len(items), rng, seed=seed)
-    p = plan(b, n_cus)
+    p = plan(b, n_cus, mixed_launch=1)
     n_dec, T = len(b.decode_reqs), decode_tiles(b)
     assert (p["decode_slots"] > 0) == (n_dec > 0)
     if n_dec:
@@ -80,7 +104,17 @@ def test_random_batches_keep_the_launch_within_bounds(seed):
     if p["prefill_split_tiles"] == 0:
         assert p["partial_slots"] <= 2 * max(0, p["decode_slots"] - 1)
     # the plan is a function of the batch alone
-    assert plan(b, n_cus) == p
+    assert plan(b, n_cus, mixed_launch=1) == p
+    # every workgroup carrying both kinds of work: same prefill work items, at most two decode slots for each
+    f = plan(b, n_cus, mixed_launch=2)
+    if n_dec and n_pre:
+        assert f["decode_workgroups"] == 0 and f["prefill_workgroups"] == p["prefill_workgroups"]
+        assert 0 < f["decode_slots"] <= max(1, min(2 * f["prefill_workgroups"] // Hkv, T // 4))
+        if f["prefill_split_tiles"] == 0:
+            assert f["partial_slots"] <= 2 * max(0, f["decode_slots"] - 1)
+    else:
+        assert f == p
+    assert plan(b, n_cus) in (p, f)
 
 
 def test_bad_arguments():
