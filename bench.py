@@ -21,10 +21,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of attention_kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in runs of
-# their own (scaled by a plain 1 GiB copy; summary in profiles/attention_kernel_hbm_traffic_pmc.md), by workload
-# index.  Not measured in this run: counters need the profiler.
-MEASURED_ATTENTION_TRAFFIC = {2: 1.607e9, 4: 3.382e9, 5: 4.690e9}
+# HBM bytes per launch of the attention kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in runs of
+# their own (scaled by a plain 1 GiB copy; summary in profiles/attention_kernel_hbm_traffic_pmc.md), by kernel and
+# workload index.  Not measured in this run: counters need the profiler.
+MEASURED_ATTENTION_TRAFFIC = {("attention_kernel", 2): 1.607e9, ("attention_kernel", 4): 3.382e9,
+                              ("attention_kernel", 5): 4.690e9, ("fused_kernel", 4): 3.258e9}
 TRAFFIC_SOURCE = "profiles/attention_kernel_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; runs of their own)"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
@@ -38,6 +39,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=5, help="workload index 1..5 (5 = headline)")
     ap.add_argument("--decode-chunk", type=int, default=0)
+    ap.add_argument("--mixed-launch", type=int, default=0,
+                    help="cfg.mixed_launch: 0 the library picks, 1 decode and prefill work on disjoint compute units, "
+                         "2 every workgroup carries both")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads / swap figures")
     ap.add_argument("--swap-only", action="store_true",
@@ -84,7 +88,7 @@ def main() -> int:
         s = batch.shape
         pool, q, kn, vn = device_inputs(batch, batch.seed)
         ctx = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, 0, out_dtype=B.PS_BF16,
-                          decode_chunk=decode_chunk)
+                          decode_chunk=decode_chunk, mixed_launch=args.mixed_launch)
         nbytes = B.ps_workspace_bytes(ctx, batch.n_req, batch.n_tokens, len(batch.block_ids))
         ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         out = torch.empty((batch.n_tokens, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
@@ -145,7 +149,12 @@ def main() -> int:
         att_tf = flops_pre / att_s / 1e12 if att_s > 0 else 0.0
         dec_gbs = bytes_dec / dec_s / 1e9 if dec_s > 0 else 0.0
         pre_tf = flops_pre / pre_s / 1e12 if pre_s > 0 else 0.0
-        return dict(attention_ms=run_["attention_ms"], attention_GBps=att_gbs, attention_hbm_frac=att_gbs / HBM_PEAK_GBS,
+        sh = batch.shape
+        plan = B.ps_plan_launch(sh.n_q_heads, sh.n_kv_heads, batch.n_device_blocks, batch, mixed_launch=args.mixed_launch,
+                                decode_chunk=args.decode_chunk)
+        both = plan["decode_slots"] > 0 and plan["prefill_workgroups"] > 0
+        return dict(kernel="fused_kernel" if both and plan["decode_workgroups"] == 0 else "attention_kernel",
+                    attention_ms=run_["attention_ms"], attention_GBps=att_gbs, attention_hbm_frac=att_gbs / HBM_PEAK_GBS,
                     attention_TFLOPs=att_tf, attention_mfma_frac=att_tf / MFMA_BF16_PEAK_TFLOPS,
                     attention_bytes=bytes_dec + bytes_pre, prefill_flops=flops_pre,
                     append_ms=run_["append_ms"], merge_ms=run_["merge_ms"],
@@ -269,6 +278,7 @@ def main() -> int:
             B.ps_destroy(rr.pop("ctx"))
             del rr
             torch.cuda.empty_cache()
+        extra["mixed_launch_layouts"] = layout_bench(B, W, torch, dev)
         extra["clock_under_load"] = clock_bench(B, W, torch, dev, args.workload)
         extra["swap"] = swap_bench(B, W, torch, np, dev)
         extra["reload_pipeline"] = reload_pipeline_bench(B, W, torch, np, dev)
@@ -300,18 +310,57 @@ def roof_of(rl, workload):
     t_hbm = rl["attention_bytes"] / (HBM_PEAK_GBS * 1e9)
     t_mfma = rl["prefill_flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if t_hbm >= t_mfma:
-        return dict(bound="hbm", kernel="attention_kernel", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=rl["attention_hbm_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get(workload),
-                    traffic_source=TRAFFIC_SOURCE if workload in MEASURED_ATTENTION_TRAFFIC else None,
+        return dict(bound="hbm", kernel=rl["kernel"], achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=rl["attention_hbm_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get((rl["kernel"], workload)),
+                    traffic_source=TRAFFIC_SOURCE if (rl["kernel"], workload) in MEASURED_ATTENTION_TRAFFIC else None,
                     shader_mhz=rl["shader_mhz"],
                     other_roof=dict(bound="mfma", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                                     frac=rl["attention_mfma_frac"]))
-    return dict(bound="mfma", kernel="attention_kernel", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
-                unit="TFLOP/s", frac=rl["attention_mfma_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get(workload),
-                traffic_source=TRAFFIC_SOURCE if workload in MEASURED_ATTENTION_TRAFFIC else None,
+    return dict(bound="mfma", kernel=rl["kernel"], achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
+                unit="TFLOP/s", frac=rl["attention_mfma_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get((rl["kernel"], workload)),
+                traffic_source=TRAFFIC_SOURCE if (rl["kernel"], workload) in MEASURED_ATTENTION_TRAFFIC else None,
                 shader_mhz=rl["shader_mhz"],
                 other_roof=dict(bound="hbm", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
                                 frac=rl["attention_hbm_frac"]))
+
+
+def layout_bench(B, W, torch, dev):
+    """The attention launch of workloads 4 and 5 in both layouts, interleaved on one box: decode and prefill work on
+    disjoint compute units (cfg.mixed_launch = 1) against workgroups that carry both (2); GPU time of the launch from
+    the library's events, median of 5 rounds of 10 steps, and which of the two the library picks by itself."""
+    out = {}
+    for idx in (4, 5):
+        batch = W.make_workload(idx)
+        s = batch.shape
+        pool, q, kn, vn = W.device_inputs(batch, batch.seed, dev)
+        o = torch.empty((batch.n_tokens, s.n_q_heads, s.head_dim), dtype=torch.bfloat16, device=dev)
+        cb = B.make_batch(batch.q_start, batch.kv_len, batch.bt_start, batch.block_ids, batch.prio)
+        stream = torch.cuda.current_stream()
+        ctxs, ws = {}, {}
+        for mode in (1, 2):
+            ctxs[mode] = B.ps_create(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, 0, mixed_launch=mode)
+            n = B.ps_workspace_bytes(ctxs[mode], batch.n_req, batch.n_tokens, len(batch.block_ids))
+            ws[mode] = torch.empty(n, dtype=torch.uint8, device=dev)
+            B.ps_set_profiling(ctxs[mode], 1)
+            for _ in range(3):
+                B.ps_step(ctxs[mode], cb, q, kn, vn, pool, o, ws[mode], ws[mode].numel(), stream)
+        times = {1: [], 2: []}
+        for _ in range(5):
+            for mode in (1, 2):
+                acc = 0.0
+                for _ in range(10):
+                    B.ps_step(ctxs[mode], cb, q, kn, vn, pool, o, ws[mode], ws[mode].numel(), stream)
+                    acc += B.ps_get_step_times(ctxs[mode])["attention_ms"] / 10
+                times[mode].append(acc)
+        for mode in (1, 2):
+            B.ps_destroy(ctxs[mode])
+        picked = B.ps_plan_launch(s.n_q_heads, s.n_kv_heads, batch.n_device_blocks, batch)["decode_workgroups"] == 0
+        out["workload_%d" % idx] = dict(attention_ms_disjoint_units=sorted(times[1])[2], attention_ms_both_in_every_workgroup=sorted(times[2])[2],
+                                        library_picks="both_in_every_workgroup" if picked else "disjoint_units")
+        del pool, q, kn, vn, o, ws
+        torch.cuda.empty_cache()
+    out["faults"] = B.ps_mixed_launch_faults()
+    return out
 
 
 def clock_bench(B, W, torch, dev, workload):
