@@ -6,6 +6,7 @@
 //   ps_machine_probe mfma       matrix-pipe rate and shader clock against the operand bits
 //   ps_machine_probe stream     cache-streaming rate of one CU and of the chip against the waves per CU
 //   ps_machine_probe share      an MFMA wave set and a streaming wave set in one workgroup, alone and together
+//   ps_machine_probe loads      what a 16-byte-per-lane load costs the wave that issues it, by destination and source
 //
 // Sections
 //  mfma    two waves per SIMD issue v_mfma_f32_32x32x16_bf16 back to back, four independent accumulators each,
@@ -19,6 +20,11 @@
 //          reused; 4 or 8 waves per CU, on 32 CUs (HBM far from its limit: what one CU can take) and on all CUs.
 //  share   workgroups of 12 waves, one per CU: 8 waves as in `mfma` (random operands, softmax arithmetic), 4
 //          waves as in `stream` over 4 GiB.  Timed with only the first kind active, only the second, and both.
+//  loads   one workgroup per CU of 1, 2, 4 or 8 waves; a wave issues rounds of 16 loads of 16 bytes per lane (1 KiB
+//          per instruction) and waits for each round.  Destination LDS (global_load_lds_dwordx4, M0 written before
+//          every load) or registers; source a region every workgroup shares (1 MiB: served by the L2s) or 128 KiB of
+//          its own per wave out of 256 MiB (served by HBM and the memory-side cache).  Reported: shader cycles per
+//          load the wave spends issuing, cycles per load overall, and the rate per CU.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -180,6 +186,89 @@ Result launch(int grid, int roles, int zero_operands, int iters, const u32x4* sr
   return Result{best, mhz.empty() ? 0.0 : mhz[mhz.size() / 2]};
 }
 
+// `loads` section.  DST 0: to LDS, 1: to registers.  shared != 0: every workgroup reads the same 1 MiB.
+template <int DST>
+__global__ __launch_bounds__(512) void loads_kernel(const char* __restrict__ src, int shared, int rounds, unsigned long long* out,
+                                                    float* sink) {
+  __shared__ __attribute__((aligned(16))) char lds[128 * 1024];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nw = blockDim.x >> 6;
+  const char* p = src + (size_t)(shared ? wave : blockIdx.x * nw + wave) * (8 * 16384) + lane * 16;
+  const unsigned base = (unsigned)(uintptr_t)lds + wave * 16384;
+  unsigned long long t_issue = 0, t_all = __builtin_amdgcn_s_memtime();
+  u32x4 acc = {0, 0, 0, 0};
+  for (int r = 0; r < rounds; ++r) {
+    const char* q = p + (size_t)(r & 7) * 16384;
+    const unsigned long long t0 = __builtin_amdgcn_s_memtime();
+    if (DST == 0) {
+#pragma unroll
+      for (int f = 0; f < 16; ++f) {
+        unsigned saved;
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved)
+                     : "v"(q + f * 1024), "s"(base + f * 1024)
+                     : "memory");
+      }
+      t_issue += __builtin_amdgcn_s_memtime() - t0;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+      u32x4 v[16];
+#pragma unroll
+      for (int f = 0; f < 16; ++f) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v[f]) : "v"(q + f * 1024) : "memory");
+      t_issue += __builtin_amdgcn_s_memtime() - t0;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int f = 0; f < 16; ++f) {
+        asm volatile("" : "+v"(v[f]));
+        acc += v[f];
+      }
+    }
+  }
+  t_all = __builtin_amdgcn_s_memtime() - t_all;
+  if (lane == 0) {
+    atomicAdd(&out[0], t_issue);
+    atomicAdd(&out[1], t_all);
+  }
+  if (acc.x == 0x12345u) sink[0] = (float)acc.y;
+  if (lds[threadIdx.x] == 77) sink[1] = 1.f;
+}
+
+void section_loads(int n_cus, const u32x4* buf, float* sink, Clocks* clocks) {
+  printf("== loads: one workgroup per CU, rounds of 16 loads of 16 bytes per lane, each round waited for (%d CUs)\n", n_cus);
+  unsigned long long* out = (unsigned long long*)clocks;  // two counters; the clock records are not used here
+  for (int shared = 1; shared >= 0; --shared)
+    for (int dst = 0; dst < 2; ++dst)
+      for (int waves : {1, 2, 4, 8}) {
+        const int rounds = shared ? 256 : 64;
+        unsigned long long z[2] = {0, 0}, o[2];
+        hipEvent_t a, b;
+        CK(hipEventCreate(&a));
+        CK(hipEventCreate(&b));
+        for (int pass = 0; pass < 2; ++pass) {  // the first pass warms the caches
+          CK(hipMemcpy(out, z, sizeof(z), hipMemcpyHostToDevice));
+          CK(hipEventRecord(a));
+          if (dst == 0)
+            hipLaunchKernelGGL(loads_kernel<0>, dim3(n_cus), dim3(waves * 64), 0, 0, (const char*)buf, shared, pass ? rounds : 8, out, sink);
+          else
+            hipLaunchKernelGGL(loads_kernel<1>, dim3(n_cus), dim3(waves * 64), 0, 0, (const char*)buf, shared, pass ? rounds : 8, out, sink);
+          CK(hipGetLastError());
+          CK(hipEventRecord(b));
+          CK(hipDeviceSynchronize());
+        }
+        float ms = 0.f;
+        CK(hipEventElapsedTime(&ms, a, b));
+        CK(hipMemcpy(o, out, sizeof(o), hipMemcpyDeviceToHost));
+        CK(hipEventDestroy(a));
+        CK(hipEventDestroy(b));
+        const double loads = (double)n_cus * waves * rounds * 16;
+        printf("  %-30s %-12s %d waves per CU: %4.0f cycles per load issuing, %4.0f overall, %6.1f GB/s per CU\n",
+               shared ? "1 MiB shared by all (L2):" : "128 KiB per wave of 256 MiB:", dst ? "to registers," : "to LDS,", waves, o[0] / loads,
+               o[1] / loads, loads * 1024 / n_cus / (ms * 1e6));
+        fflush(stdout);
+      }
+  CK(hipMemset(clocks, 0, sizeof(Clocks) * 1024));
+}
+
 void section_mfma(int n_cus, const u32x4* buf, float* sink, Clocks* clocks) {
   printf("== mfma: 8 waves per CU (two per SIMD), one LDS operand fragment per MFMA, %d CUs\n", n_cus);
   const int iters = 6000;
@@ -247,6 +336,7 @@ int main(int argc, char** argv) {
   if (all || !strcmp(what, "mfma")) section_mfma(n_cus, buf, sink, clocks);
   if (all || !strcmp(what, "stream")) section_stream(n_cus, buf, buf_bytes, sink, clocks);
   if (all || !strcmp(what, "share")) section_share(n_cus, buf, buf_bytes, sink, clocks);
+  if (all || !strcmp(what, "loads")) section_loads(n_cus, buf, sink, clocks);
   CK(hipFree(buf));
   CK(hipFree(sink));
   CK(hipFree(clocks));
