@@ -94,6 +94,20 @@ __device__ __forceinline__ void load_to_lds16(const void* gptr, uint32_t lds_bas
       : "memory");
 }
 
+// The same with an instruction offset OFF (0 .. 4095 bytes), which the hardware adds to the global address AND to the
+// LDS address: lane's 16 bytes at gptr + OFF -> LDS at lds_base + OFF + lane*16.  Several loads off one address
+// register pair then cost no vector arithmetic between them.
+template <int OFF>
+__device__ __forceinline__ void load_to_lds16_off(const void* gptr, uint32_t lds_base) {
+  static_assert(OFF >= 0 && OFF < 4096, "13-bit signed instruction offset, used unsigned");
+  uint32_t saved;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off offset:%3\n\ts_mov_b32 m0, %0"
+      : "=&s"(saved)
+      : "v"(gptr), "s"(lds_base), "n"(OFF)
+      : "memory");
+}
+
 // max of three without the NaN-quieting moves the compiler wraps around fmaxf of MFMA results
 // (the inputs here are never NaN: finite scores or -inf)
 __device__ __forceinline__ float max3(float a, float b, float c) {

@@ -303,15 +303,27 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         idB = id[1];
       }
       const uint32_t st = ring_base + (uint32_t)(ti & (kFusedRing - 1)) * (uint32_t)sizeof(FusedStage);
+      // Three address register pairs per tile; the fragments differ by instruction offsets only (fragment f of K is
+      // 512 bytes further on in the cache and 1024 in LDS, and the offset counts on both sides: M0 makes up the rest).
       const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + kslot * 8 + h2 * (kBlockTokens * 8);
-#pragma unroll
-      for (int f = 0; f < 8; ++f) load_to_lds16(krow + f * 2 * (kBlockTokens * 8), st + (uint32_t)f * 1024u);
       const uint16_t* vA = v_slice(P.cache, idA, Hkv, g) + j * kBlockTokens + 8 * h2;
       const uint16_t* vB = v_slice(P.cache, idB, Hkv, g) + j * kBlockTokens + 8 * h2;
-#pragma unroll
-      for (int n = 0; n < 4; ++n) load_to_lds16(vA + n * 32 * kBlockTokens, st + 8192u + (uint32_t)n * 1024u);
-#pragma unroll
-      for (int n = 0; n < 4; ++n) load_to_lds16(vB + n * 32 * kBlockTokens, st + 8192u + (uint32_t)(4 + n) * 1024u);
+      load_to_lds16_off<0 * 512>(krow, st + 0 * 512u);
+      load_to_lds16_off<1 * 512>(krow, st + 1 * 512u);
+      load_to_lds16_off<2 * 512>(krow, st + 2 * 512u);
+      load_to_lds16_off<3 * 512>(krow, st + 3 * 512u);
+      load_to_lds16_off<4 * 512>(krow, st + 4 * 512u);
+      load_to_lds16_off<5 * 512>(krow, st + 5 * 512u);
+      load_to_lds16_off<6 * 512>(krow, st + 6 * 512u);
+      load_to_lds16_off<7 * 512>(krow, st + 7 * 512u);
+      load_to_lds16_off<0 * 1024>(vA, st + 8192u);
+      load_to_lds16_off<1 * 1024>(vA, st + 8192u);
+      load_to_lds16_off<2 * 1024>(vA, st + 8192u);
+      load_to_lds16_off<3 * 1024>(vA, st + 8192u);
+      load_to_lds16_off<0 * 1024>(vB, st + 12288u);
+      load_to_lds16_off<1 * 1024>(vB, st + 12288u);
+      load_to_lds16_off<2 * 1024>(vB, st + 12288u);
+      load_to_lds16_off<3 * 1024>(vB, st + 12288u);
     };
     // Tile ti has landed (the caller has waited for its loads): hand it to the MFMA waves.
     auto publish = [&](int ti) {
