@@ -47,8 +47,8 @@ constexpr int kFusedIdTiles = 1024; // block ids of up to this many ring tiles (
 constexpr int kHostTileKV = 64;     // unit of PrefillTile::tile_begin / tile_end
 
 struct FusedStage {
-  uint4 k[8][64];  // fragment c: dims 16c..16c+15 of the tile's 32 tokens, in MFMA A-operand lane order
-  uint4 v[8][64];  // fragment 4u+n: dims 32n..32n+31 of block u
+  uint4 k[2][256]; // block u of the tile as it lies in the cache: [dim/8][token][8 dims], 16 bytes per (dim group, token)
+  uint4 v[8][64];  // fragment 4u+n: dims 32n..32n+31 of block u, in MFMA A-operand lane order
 };
 struct FusedLds {
   FusedStage ring[kFusedRing];
@@ -146,6 +146,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
       for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
     const int my_last = p + (q0 + kFusedRows < lq ? q0 + kFusedRows : lq) - 1;  // last visible key
     const int qpos = p + q0 + j;
+    // K row j of a score tile is token pi(j) of the ring tile: block j>>4, slot 8*bit2(j) + 4*bit3(j) + (j&3)
+    const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
 
     bool gave_up = false;
     for (int it = 0; it < ntiles; ++it) {
@@ -168,9 +170,11 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         // all 8 K fragments are requested from LDS before the first MFMA needs one, the first 4 V fragments
         // right behind the score MFMAs and the other 4 behind the softmax arithmetic, so that LDS latency is
         // paid once per tile and no more than 8 fragments are held at a time
+        // K operand of dim chunk c: row j is token pi(j) of the tile (block j>>4, slot kslot), this lane's 8 dims are dim
+        // group 2c + h2; the 16 lanes of a quarter wave read 16 consecutive slots of one group: no bank conflict
         bf16x8 kf[8], vf[8];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) kf[c] = as_bf16x8(S.k[c][lane]);
+        for (int c = 0; c < 8; ++c) kf[c] = as_bf16x8(S.k[j >> 4][(2 * c + h2) * 16 + kslot]);
         __builtin_amdgcn_sched_barrier(0);
         f32x16 s;
 #pragma unroll
@@ -281,9 +285,9 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
   if (mw < kFusedFeeders) {
     // ---- a feeder: fetches the tiles t = mw (mod kFusedFeeders) of the walk in order, up to three in flight, as
     // their ring slots come free
-    // K row j of a fragment is token pi(j) of the tile: block j>>4, slot 8*bit2(j) + 4*bit3(j) + (j&3)
-    const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
     const uint32_t ring_base = (uint32_t)(uintptr_t)(&sm.ring[0]);  // LDS byte address of the ring
+    const uint32_t k_voff = (uint32_t)lane * 16u;                       // K slice: straight copy
+    const uint32_t v_voff = (uint32_t)(j * kBlockTokens + 8 * h2) * 2u;  // V slice: dim row j of a 32-dim group, tokens 8*h2..
     // Tile ti's previous occupant of its ring slot has been read by all eight MFMA waves.
     auto slot_free = [&](int ti) {
       return ti < kFusedRing || lds_peek(&sm.consumed[ti & (kFusedRing - 1)]) >= (uint32_t)(kFusedMfmaWaves * (ti >> 3));
@@ -303,27 +307,28 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         idB = id[1];
       }
       const uint32_t st = ring_base + (uint32_t)(ti & (kFusedRing - 1)) * (uint32_t)sizeof(FusedStage);
-      // Three address register pairs per tile; the fragments differ by instruction offsets only (fragment f of K is
-      // 512 bytes further on in the cache and 1024 in LDS, and the offset counts on both sides: M0 makes up the rest).
-      const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + kslot * 8 + h2 * (kBlockTokens * 8);
-      const uint16_t* vA = v_slice(P.cache, idA, Hkv, g) + j * kBlockTokens + 8 * h2;
-      const uint16_t* vB = v_slice(P.cache, idB, Hkv, g) + j * kBlockTokens + 8 * h2;
-      load_to_lds16_off<0 * 512>(krow, st + 0 * 512u);
-      load_to_lds16_off<1 * 512>(krow, st + 1 * 512u);
-      load_to_lds16_off<2 * 512>(krow, st + 2 * 512u);
-      load_to_lds16_off<3 * 512>(krow, st + 3 * 512u);
-      load_to_lds16_off<4 * 512>(krow, st + 4 * 512u);
-      load_to_lds16_off<5 * 512>(krow, st + 5 * 512u);
-      load_to_lds16_off<6 * 512>(krow, st + 6 * 512u);
-      load_to_lds16_off<7 * 512>(krow, st + 7 * 512u);
-      load_to_lds16_off<0 * 1024>(vA, st + 8192u);
-      load_to_lds16_off<1 * 1024>(vA, st + 8192u);
-      load_to_lds16_off<2 * 1024>(vA, st + 8192u);
-      load_to_lds16_off<3 * 1024>(vA, st + 8192u);
-      load_to_lds16_off<0 * 1024>(vB, st + 12288u);
-      load_to_lds16_off<1 * 1024>(vB, st + 12288u);
-      load_to_lds16_off<2 * 1024>(vB, st + 12288u);
-      load_to_lds16_off<3 * 1024>(vB, st + 12288u);
+      // Every load is one contiguous KiB of one block's K or V slice: a wave-uniform base (scalar arithmetic only), a
+      // per-lane offset that never changes, and an instruction offset that counts on the LDS side as well.
+      const uint16_t* kA = k_slice(P.cache, idA, Hkv, g);
+      const uint16_t* kB = k_slice(P.cache, idB, Hkv, g);
+      const uint16_t* vA = v_slice(P.cache, idA, Hkv, g);
+      const uint16_t* vB = v_slice(P.cache, idB, Hkv, g);
+      load_to_lds16_sbase<0>(kA, k_voff, st);
+      load_to_lds16_sbase<1024>(kA, k_voff, st);
+      load_to_lds16_sbase<2048>(kA, k_voff, st);
+      load_to_lds16_sbase<3072>(kA, k_voff, st);
+      load_to_lds16_sbase<0>(kB, k_voff, st + 4096u);
+      load_to_lds16_sbase<1024>(kB, k_voff, st + 4096u);
+      load_to_lds16_sbase<2048>(kB, k_voff, st + 4096u);
+      load_to_lds16_sbase<3072>(kB, k_voff, st + 4096u);
+      load_to_lds16_sbase<0>(vA, v_voff, st + 8192u);
+      load_to_lds16_sbase<1024>(vA, v_voff, st + 8192u);
+      load_to_lds16_sbase<2048>(vA, v_voff, st + 8192u);
+      load_to_lds16_sbase<3072>(vA, v_voff, st + 8192u);
+      load_to_lds16_sbase<0>(vB, v_voff, st + 12288u);
+      load_to_lds16_sbase<1024>(vB, v_voff, st + 12288u);
+      load_to_lds16_sbase<2048>(vB, v_voff, st + 12288u);
+      load_to_lds16_sbase<3072>(vB, v_voff, st + 12288u);
     };
     // Tile ti has landed (the caller has waited for its loads): hand it to the MFMA waves.
     auto publish = [&](int ti) {
