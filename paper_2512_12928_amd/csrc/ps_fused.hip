@@ -43,6 +43,7 @@ constexpr int kFusedThreads = (kFusedMfmaWaves + kFusedMemWaves) * 64;
 constexpr int kFusedRows = 32;      // query tokens per MFMA wave
 constexpr int kFusedKV = 32;        // KV tokens per ring tile
 constexpr int kFusedRing = 8;       // tiles in the LDS ring
+constexpr int kFusedPairs = kFusedRing / 2;  // handed over in pairs: tiles 2p and 2p + 1 in ring slots (2p) % 8 and (2p + 1) % 8
 constexpr int kFusedIdTiles = 1024; // block ids of up to this many ring tiles (32k tokens) are kept in LDS
 constexpr int kHostTileKV = 64;     // unit of PrefillTile::tile_begin / tile_end
 
@@ -53,8 +54,8 @@ struct FusedStage {
 struct FusedLds {
   FusedStage ring[kFusedRing];
   int ids[kFusedIdTiles * 2];
-  uint32_t ready[kFusedRing];     // ready[s] = 1 + index of the last tile that landed in slot s
-  uint32_t consumed[kFusedRing];  // MFMA waves that are through with slot s, counted over the whole walk
+  uint32_t ready[kFusedRing];     // ready[p % 4] = 1 + index of the last pair that landed in pair slot p % 4 (entries 4.. unused)
+  uint32_t consumed[kFusedRing];  // MFMA waves that are through with pair slot p % 4, counted over the whole walk
 };
 static_assert(sizeof(FusedLds) <= 160 * 1024, "one workgroup's LDS");
 
@@ -150,12 +151,16 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
     const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
 
     bool gave_up = false;
+    // The walk is handed over in pairs of tiles (64 tokens): one wait for the pair's flag ahead of its first tile, one
+    // count behind the wave's last read of its second (or only) tile.
     for (int it = 0; it < ntiles; ++it) {
       const int slot = it & (kFusedRing - 1);
+      const int pslot = (it >> 1) & (kFusedPairs - 1);
       const int ts = (tile0 + it) * kFusedKV;
-      if (!gave_up) {
+      const bool last_of_pair = (it & 1) || it + 1 == ntiles;
+      if (!(it & 1) && !gave_up) {
         int spins = 0;
-        while (lds_peek(&sm.ready[slot]) < (uint32_t)(it + 1)) {
+        while (lds_peek(&sm.ready[pslot]) < (uint32_t)((it >> 1) + 1)) {
           __builtin_amdgcn_s_sleep(1);
           if (++spins > kFusedSpinLimit) {
             gave_up = true;
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
           }
         }
       }
-      asm volatile("" ::: "memory");  // no read of the tile moves above the flag
+      asm volatile("" ::: "memory");  // no read of the pair moves above the flag
       if (active && ts <= my_last) {
         const FusedStage& S = sm.ring[slot];
         // all 8 K fragments are requested from LDS before the first MFMA needs one, the first 4 V fragments
@@ -229,15 +234,17 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         // the wave's last read of the tile is issued: LDS serves a wave's instructions in order, so the count
         // may follow at once
         asm volatile("" ::: "memory");
-        if (lane == 0) __hip_atomic_fetch_add(&sm.consumed[slot], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (last_of_pair && lane == 0)
+          __hip_atomic_fetch_add(&sm.consumed[pslot], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
           for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u * 4 + n], pop[u], acc[n], 0, 0, 0);
-      } else {
-        if (lane == 0) __hip_atomic_fetch_add(&sm.consumed[slot], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      } else if (last_of_pair) {
+        asm volatile("" ::: "memory");
+        if (lane == 0) __hip_atomic_fetch_add(&sm.consumed[pslot], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     }
     if (bid < kClockSlots) clock_record(P, kClockSlots + bid, 2);
@@ -283,14 +290,14 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
   // ---------------------------------------------------------------------------------- memory waves
   const int mw = wave - kFusedMfmaWaves;
   if (mw < kFusedFeeders) {
-    // ---- a feeder: fetches the tiles t = mw (mod kFusedFeeders) of the walk in order, up to three in flight, as
-    // their ring slots come free
+    // ---- a feeder: fetches the pairs of tiles p = mw (mod kFusedFeeders) of the walk in order, up to three tiles in
+    // flight, as their ring slots come free
     const uint32_t ring_base = (uint32_t)(uintptr_t)(&sm.ring[0]);  // LDS byte address of the ring
     const uint32_t k_voff = (uint32_t)lane * 16u;                       // K slice: straight copy
     const uint32_t v_voff = (uint32_t)(j * kBlockTokens + 8 * h2) * 2u;  // V slice: dim row j of a 32-dim group, tokens 8*h2..
-    // Tile ti's previous occupant of its ring slot has been read by all eight MFMA waves.
-    auto slot_free = [&](int ti) {
-      return ti < kFusedRing || lds_peek(&sm.consumed[ti & (kFusedRing - 1)]) >= (uint32_t)(kFusedMfmaWaves * (ti >> 3));
+    // The previous occupants of pair pr's two ring slots have been read by all eight MFMA waves.
+    auto pair_free = [&](int pr) {
+      return pr < kFusedPairs || lds_peek(&sm.consumed[pr & (kFusedPairs - 1)]) >= (uint32_t)(kFusedMfmaWaves * (pr >> 2));
     };
     // The 16 loads of tile ti: K fragments 0..7 (dim chunks), V fragments 0..7 (block f/4, dims 32*(f%4)..).
     auto issue_tile = [&](int ti) {
@@ -330,8 +337,9 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
       load_to_lds16_sbase<2048>(vB, v_voff, st + 12288u);
       load_to_lds16_sbase<3072>(vB, v_voff, st + 12288u);
     };
-    // Tile ti has landed (the caller has waited for its loads): hand it to the MFMA waves.
-    auto publish = [&](int ti) {
+    // Tile ti has landed (the caller has waited for its loads): zero what must not be read, and with the last tile of
+    // a pair hand the pair to the MFMA waves.
+    auto landed = [&](int ti) {
       const int slot = ti & (kFusedRing - 1);
       const int ts = (tile0 + ti) * kFusedKV;
       if (ts + kFusedKV > L) {
@@ -345,18 +353,22 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
           sm.ring[slot].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
         }
       }
-      asm volatile("" ::: "memory");  // the flag is written after the tile, in program order (LDS keeps it)
-      if (lane == 0) *(volatile uint32_t*)&sm.ready[slot] = (uint32_t)(ti + 1);
+      if ((ti & 1) || ti + 1 >= ntiles) {
+        asm volatile("" ::: "memory");  // the flag is written after the tiles, in program order (LDS keeps it)
+        if (lane == 0) *(volatile uint32_t*)&sm.ready[(ti >> 1) & (kFusedPairs - 1)] = (uint32_t)((ti >> 1) + 1);
+      }
     };
-    int tp = mw, spins = 0;
-    // Issue whenever a slot is free and fewer than kFusedInFlight tiles are out; otherwise wait for the oldest
-    // tile in flight (loads return in issue order: with at most 16 * k still out, all but the youngest k tiles have
-    // landed) and hand it over.
-    int tail = mw, nfl = 0;  // oldest tile in flight, tiles in flight
-    while (tail < ntiles) {
-      if (nfl < kFusedInFlight && tp < ntiles && slot_free(tp)) {
-        issue_tile(tp);
-        tp += kFusedFeeders;
+    // This feeder's q-th tile: the two tiles of its pair q / 2.
+    auto tile_of = [&](int q) { return 2 * (mw + kFusedFeeders * (q >> 1)) + (q & 1); };
+    // Issue whenever the next tile has room (a pair's first tile asks whether the pair's slots are free) and fewer
+    // than kFusedInFlight tiles are out; otherwise wait for the oldest tile in flight (loads return in issue order:
+    // with at most 16 * k still out, all but the youngest k tiles have landed).
+    int qh = 0, qt = 0, nfl = 0, spins = 0;  // next tile to issue, oldest tile in flight, tiles in flight
+    while (tile_of(qt) < ntiles) {
+      const int th = tile_of(qh);
+      if (nfl < kFusedInFlight && th < ntiles && ((qh & 1) || pair_free(th >> 1))) {
+        issue_tile(th);
+        ++qh;
         ++nfl;
         spins = 0;
         continue;
@@ -368,8 +380,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
           asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
         else
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        publish(tail);
-        tail += kFusedFeeders;
+        landed(tile_of(qt));
+        ++qt;
         --nfl;
         continue;
       }
