@@ -760,9 +760,10 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
   {
     int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
     // Every workgroup carries both kinds of work (two decode slots per prefill work item and z-split).  Forced by
-    // cfg.mixed_launch = 2; picked by the library when the launch is dominated by prefill walks and has at least
-    // two prefill workgroups per compute unit: measured on an MI355X, 6 % faster than disjoint units with the
-    // prefill work priced at 2.6 times the decode work, no faster at 1.85 times, slower when decode dominates.
+    // cfg.mixed_launch = 2; picked by the library when neither kind of work dwarfs the other (the prefill work priced
+    // at 0.75 to 4 times the decode work) and there are at least two prefill workgroups per compute unit.  Measured on
+    // an MI355X against disjoint units, by that ratio: 6 and more, the same; 3.4, -2 %; 2.6, -8 %; 1.9, -3 to -4 %;
+    // 1.2 and 1.0, -6 %; 0.64, the same; 0.45 and less, 4 to 6 % slower.
     const bool fusable = c->cfg.decode_waves == 0 && c->cfg.decode_chunk == 0 && c->profiling != 2 && !decode_reqs.empty() &&
                          !tiles.empty() && ps::fused_supports(c->G) &&
                          (int64_t)ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads <= INT32_MAX;
@@ -772,7 +773,7 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
       const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / (tune.stream_TBps * 1e6);  // us
       const double t_p = prefill_steps * tune.tile_step_us;
       const int64_t wgs = (int64_t)tiles.size() * c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
-      c->plan_fused = t_p >= 2.2 * t_d && wgs >= 2 * (int64_t)c->n_cus;
+      c->plan_fused = t_p >= 0.75 * t_d && t_p <= 4.0 * t_d && wgs >= 2 * (int64_t)c->n_cus;
     }
     if (c->plan_fused) {
       waves = ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads;

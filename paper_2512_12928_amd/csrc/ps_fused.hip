@@ -11,22 +11,26 @@
 //
 // Workgroup = 12 waves, three per SIMD (168 registers each), one workgroup per compute unit (LDS).
 //   waves 0..7   MFMA waves: the prefill role on 32-token KV tiles (v_mfma_f32_32x32x16_bf16), operands
-//                from the LDS ring; they wait for a tile's `ready` flag and count themselves into its
-//                `consumed` counter once their last read of it has been issued.
-//   waves 8, 9   feeders: wave 8 + f fetches the tiles t = f (mod 2) of the walk in order, up to three in
-//                flight (16 global->LDS loads each), each into its ring slot once all eight MFMA waves have
-//                consumed the slot's previous tile; when a tile's loads are back it zeroes V slots past the
-//                end of the request and sets `ready`.
+//                from an LDS ring of eight tiles that is handed over in pairs of tiles (64 tokens): a wave
+//                waits for the pair's `ready` flag ahead of its first tile and counts itself into the
+//                pair's `consumed` counter once its last read of the second tile has been issued.
+//   waves 8, 9   feeders: wave 8 + f fetches the pairs p = f (mod 2) of the walk in order, up to three tiles in
+//                flight (16 global->LDS loads each: every load one contiguous KiB of a block's K or V slice,
+//                addressed by a scalar base and a per-lane offset that never changes), a pair's first tile
+//                once all eight MFMA waves have consumed the previous pair in those slots; when a tile's loads
+//                are back it zeroes V slots past the end of the request, and behind a pair's last tile it sets
+//                `ready`.
 //   waves 10, 11 decode waves: wave 10 + k walks decode slot (bid / Hkv) * 2 + k of the launch for the
 //                workgroup's kv-head, one 32-token tile at a time (16x16x32 MFMA, the G query heads of the
 //                kv-head in 16 columns, no LDS), and ends when the slot does.
 // Nobody waits at a barrier after the start: MFMA waves wait only for `ready`, feeders only for memory
-// and for `consumed`, decode waves only for memory; tile t's `ready` needs `consumed` of tile t - 8 only,
-// which needs `ready` of t - 8: every wait is for something earlier in that order, so the walk drains.
-// What it buys (MI355X): a launch dominated by long prefill walks ends 6 % sooner than with the two kinds
-// of work on disjoint compute units; with more decode work the two layouts take the same time, because a
-// load issued next to MFMA waves costs its wave about 150 cycles and every load on the unit, hit or miss,
-// returns at the pace of the misses in front of it.
+// and for `consumed`, decode waves only for memory; pair p's `ready` needs `consumed` of pair p - 4 only,
+// which needs `ready` of p - 4: every wait is for something earlier in that order, so the walk drains.
+// What it buys (MI355X), against the two kinds of work on disjoint compute units: 2 to 8 % off a launch in
+// which neither kind dwarfs the other (the prefill work 0.75 to 4 times the decode work); outside that
+// range the two layouts take the same time or this one more.  It stops there because every load on a
+// unit, hit or miss, returns at the pace of the misses in front of it, and because a load issued next to
+// MFMA waves costs its wave some 90 cycles (160 with a 64-bit address per lane).
 #include <type_traits>
 
 #include "ps_device.h"

@@ -51,13 +51,19 @@ def test_shares_of_the_benchmark_workloads():
 
 
 def test_which_mixed_batches_get_workgroups_that_carry_both_kinds_of_work():
-    """Left to the library (mixed_launch = 0), only the launch dominated by prefill walks (workload 4: the prefill
-    work priced at 2.6 times the decode work, two prefill workgroups per compute unit) is laid out that way; forced
-    (2), any mixed batch is, and every prefill workgroup then walks at most two decode slots of its kv-head."""
+    """Left to the library (mixed_launch = 0), a launch in which neither kind of work dwarfs the other and which has at
+    least two prefill workgroups per compute unit is laid out that way (workloads 4 and 5: the prefill work priced at 2.6
+    and 1.9 times the decode work; not workload 2, a quarter of a prefill workgroup per unit and mostly decode work, nor
+    workload 5 with an eighth of its decode requests); forced (2), any mixed batch is, and every prefill workgroup then
+    walks at most two decode slots of its kv-head."""
     p2, p4, p5 = (plan(W.make_workload(i)) for i in (2, 4, 5))
-    assert p2["decode_workgroups"] > 0 and p5["decode_workgroups"] > 0
-    assert p2 == plan(W.make_workload(2), mixed_launch=1) and p5 == plan(W.make_workload(5), mixed_launch=1)
+    assert p2["decode_workgroups"] > 0 and p2 == plan(W.make_workload(2), mixed_launch=1)
     assert p4["decode_workgroups"] == 0 and p4["prefill_workgroups"] == 512 and p4 == plan(W.make_workload(4), mixed_launch=2)
+    assert p5["decode_workgroups"] == 0 and p5["prefill_workgroups"] == 2048 and p5 == plan(W.make_workload(5), mixed_launch=2)
+    b5 = W.make_workload(5)
+    few = [(1, int(b5.kv_len[r])) for r in b5.decode_reqs[:64]] + [(b5.l_q(int(r)), int(b5.kv_len[r])) for r in b5.prefill_reqs]
+    bf = W.build_batch(b5.shape, few, [1] * len(few), np.random.default_rng(3), seed=3)
+    assert plan(bf)["decode_workgroups"] > 0 and plan(bf, mixed_launch=2)["decode_workgroups"] == 0
     for i in (2, 4, 5):
         b = W.make_workload(i)
         p = plan(b, mixed_launch=2)
