@@ -111,9 +111,9 @@ typedef struct {
                               workgroup carries both (a prefill tile walk on eight waves, next to them two
                               waves that fetch the walk's tiles and two that walk decode slots; needs
                               decode_chunk and decode_waves 0, else as 1).  0 (default): the library picks:
-                              2 when neither kind of work dwarfs the other (the prefill work priced at 0.75
-                              to 4 times the decode work) and there are at least two prefill workgroups per
-                              compute unit (measured 2 to 8 % faster on such launches, the same or slower
+                              2 when neither kind of work dwarfs the other (the prefill work priced at 0.6
+                              to 5 times the decode work) and there are at least two prefill workgroups per
+                              compute unit (measured 1 to 14 % faster on such launches, the same or slower
                               outside that range), else 1.                                            */
 } ps_layer_cfg;
 

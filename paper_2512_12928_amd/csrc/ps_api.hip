@@ -384,15 +384,84 @@ void build_decode_slots(DecodePlan* c, int n_kv_heads, int decode_chunk, const p
   close_slot();
 }
 
+// Decode work list for the launch whose workgroups carry both kinds of work.  Slot x is walked by a decode wave of
+// the prefill workgroups of work item x / slots_per_item, and lasts as long as they do if its share of the decode
+// tiles is that of its work item in the prefill work: weight[x] = length of that item's tile walk.  The requests'
+// 32-token tiles, laid end to end in batch order, are cut at the cumulative weights (rounded up to kMinSlotTiles
+// tiles: short slots are latency-bound); a slot may come out empty, and is kept as an empty range so that slot
+// numbers still name their workgroups.  Requests cut by a boundary get one partials slot per segment and a merge item.
+void build_weighted_decode_slots(DecodePlan* c, const ps_batch* b, const std::vector<int>& reqs, int& n_parts,
+                                 const std::vector<int64_t>& weight) {
+  c->ditems.clear();
+  c->dslots.assign(1, 0);
+  const size_t S = weight.size();
+  int64_t T = 0, wtot = 0;
+  for (int r : reqs) T += (b->kv_len[r] + ps::kTileTokens - 1) / ps::kTileTokens;
+  for (int64_t w : weight) wtot += std::max<int64_t>(w, 0);
+  if (wtot < 1) wtot = 1;
+  std::vector<int64_t> end(S);  // one past the last tile of slot x, non-decreasing
+  {
+    int64_t wc = 0;
+    for (size_t x = 0; x < S; ++x) {
+      wc += std::max<int64_t>(weight[x], 0);
+      const int64_t e = (int64_t)(((__int128)T * wc + wtot - 1) / wtot);
+      end[x] = x + 1 == S ? T : std::min<int64_t>((e + kMinSlotTiles - 1) / kMinSlotTiles * kMinSlotTiles, T);
+    }
+  }
+  auto item = [&](int r, int t0, int t1, int part) {
+    const int L = b->kv_len[r];
+    return ps::DecodeItem{b->bt_start[r], b->q_start[r], t0, t1, part, (L + ps::kBlockTokens - 1) / ps::kBlockTokens, {0, 0}};
+  };
+  auto close_slot = [&]() { c->dslots.push_back((int32_t)c->ditems.size()); };
+  int64_t off = 0;  // tiles before the current request
+  size_t x = 0;     // the slot the next tile falls into
+  for (int r : reqs) {
+    const int L = b->kv_len[r];
+    const int64_t n = (L + ps::kTileTokens - 1) / ps::kTileTokens;
+    while (x + 1 < S && end[x] <= off) {  // slots that end at or before the start of this request (some of them empty)
+      close_slot();
+      ++x;
+    }
+    int nseg = 1;
+    {
+      int64_t pos = off;
+      for (size_t y = x; y + 1 < S && end[y] < off + n; ++y)
+        if (end[y] > pos) {
+          ++nseg;
+          pos = end[y];
+        }
+    }
+    if (nseg == 1) {
+      c->ditems.push_back(item(r, 0, L, -1));
+      // slots that end inside the request without taking a tile of it (their end is its start) were closed above
+    } else {
+      c->mitems.push_back(ps::MergeItem{b->q_start[r], n_parts, nseg, 0});
+      int64_t pos = off;
+      while (x + 1 < S && end[x] < off + n) {
+        if (end[x] > pos) {
+          c->ditems.push_back(item(r, (int)((pos - off) * ps::kTileTokens), (int)((end[x] - off) * ps::kTileTokens), n_parts++));
+          pos = end[x];
+        }
+        close_slot();
+        ++x;
+      }
+      c->ditems.push_back(item(r, (int)((pos - off) * ps::kTileTokens), L, n_parts++));
+    }
+    off += n;
+  }
+  while (c->dslots.size() < S + 1) close_slot();
+}
+
 // Host-side check of the decode work list before anything is launched from it: every slot a
-// non-empty range of items, every item inside its request, the segments of a request tiling
+// non-empty range of items (an empty one only where empty_ok says so), every item inside its request, the segments of a request tiling
 // [0, kv_len) exactly.  A mistake here would otherwise become an out-of-bounds access on the GPU.
-bool decode_slots_ok(const DecodePlan* c, const ps_batch* b, const std::vector<int>& reqs, std::vector<int64_t>& cover) {
+bool decode_slots_ok(const DecodePlan* c, const ps_batch* b, const std::vector<int>& reqs, std::vector<int64_t>& cover,
+                     bool empty_ok = false) {
   const size_t n = c->ditems.size();
   if (c->dslots.empty() || c->dslots.front() != 0 || (size_t)c->dslots.back() != n) return false;
   for (size_t i = 1; i < c->dslots.size(); ++i)
-    if (c->dslots[i] <= c->dslots[i - 1]) return false;
-  if (reqs.empty()) return n == 0 && c->dslots.size() == 1;
+    if (c->dslots[i] < c->dslots[i - 1] || (!empty_ok && c->dslots[i] == c->dslots[i - 1])) return false;
+  if (reqs.empty()) return n == 0 && (empty_ok || c->dslots.size() == 1);
   cover.assign((size_t)b->n_tokens, 0);
   std::vector<int> req_of((size_t)b->n_tokens, -1);
   for (int r : reqs) req_of[(size_t)b->q_start[r]] = r;
@@ -752,6 +821,8 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
     }
   }
   const double prefill_steps = plan_prefill(c, b, tiles, TT, workspace_bytes, n_parts);
+  // launch order of the prefill work items: heaviest partitions first, so the tail of the launch is made of short ones
+  std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
 
   // Decode slots.  With prefill work in the same launch the decode workgroups get the share of the
   // CUs that makes both kinds of work end together (each priced at its full-chip speed: 6.3 TB/s
@@ -761,9 +832,9 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
     int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
     // Every workgroup carries both kinds of work (two decode slots per prefill work item and z-split).  Forced by
     // cfg.mixed_launch = 2; picked by the library when neither kind of work dwarfs the other (the prefill work priced
-    // at 0.75 to 4 times the decode work) and there are at least two prefill workgroups per compute unit.  Measured on
-    // an MI355X against disjoint units, by that ratio: 6 and more, the same; 3.4, -2 %; 2.6, -8 %; 1.9, -3 to -4 %;
-    // 1.2 and 1.0, -6 %; 0.64, the same; 0.45 and less, 4 to 6 % slower.
+    // at 0.6 to 5 times the decode work) and there are at least two prefill workgroups per compute unit.  Measured on
+    // an MI355X against disjoint units, by that ratio: 6.4, the same; 3.6, -2.5 %; 2.6, -8 %; 1.95, -7 %; 1.3, -14 %;
+    // 1.0, -12 to -13 %; 0.65 and 0.48, -1 %; 0.46 with half the prefill workgroups, 4 % slower.
     const bool fusable = c->cfg.decode_waves == 0 && c->cfg.decode_chunk == 0 && c->profiling != 2 && !decode_reqs.empty() &&
                          !tiles.empty() && ps::fused_supports(c->G) &&
                          (int64_t)ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads <= INT32_MAX;
@@ -773,7 +844,7 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
       const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / (tune.stream_TBps * 1e6);  // us
       const double t_p = prefill_steps * tune.tile_step_us;
       const int64_t wgs = (int64_t)tiles.size() * c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
-      c->plan_fused = t_p >= 0.75 * t_d && t_p <= 4.0 * t_d && wgs >= 2 * (int64_t)c->n_cus;
+      c->plan_fused = t_p >= 0.6 * t_d && t_p <= 5.0 * t_d && wgs >= 2 * (int64_t)c->n_cus;
     }
     if (c->plan_fused) {
       waves = ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads;
@@ -811,13 +882,19 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
       }
       waves = ps::decode_waves_per_wg() * cus;
     }
-    build_decode_slots(&c->plan, c->cfg.n_kv_heads, c->cfg.decode_chunk, b, decode_reqs, n_parts, waves);
-    if (!decode_slots_ok(&c->plan, b, decode_reqs, c->cover))
+    if (c->plan_fused) {
+      // slot x goes with the workgroups of work item (x / slots per item) of the launch order fixed above
+      const int per_item = ps::fused_decode_slots(1, c->G);
+      std::vector<int64_t> weight((size_t)per_item * tiles.size());
+      for (size_t x = 0; x < weight.size(); ++x) weight[x] = tiles[x / (size_t)per_item].reach;
+      build_weighted_decode_slots(&c->plan, b, decode_reqs, n_parts, weight);
+    } else {
+      build_decode_slots(&c->plan, c->cfg.n_kv_heads, c->cfg.decode_chunk, b, decode_reqs, n_parts, waves);
+    }
+    if (!decode_slots_ok(&c->plan, b, decode_reqs, c->cover, c->plan_fused))
       return fail(PS_ESTATE, "ps_step: inconsistent decode work list (library bug)");
   }
 
-  // heaviest partitions first, so the tail of the launch is made of short ones
-  std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& a, const TileKey& b2) { return a.reach > b2.reach; });
   for (auto& t : tiles) c->ptiles.push_back(t.t);
   n_parts_out = n_parts;
   if (prefill_split_out) {

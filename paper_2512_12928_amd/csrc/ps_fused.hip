@@ -427,6 +427,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
     };
     const int seg_end = dslots[dslot + 1];
     int seg = dslots[dslot];
+    if (seg >= seg_end) return;  // a slot may be empty (its workgroup's share of the decode tiles rounded to nothing)
     DecodeItem it = ditems[seg];
     int nextA, nextB;
     tile_ids(it, it.t0, nextA, nextB);
