@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 # their own (scaled by a plain 1 GiB copy; summary in profiles/attention_kernel_hbm_traffic_pmc.md), by kernel and
 # workload index.  Not measured in this run: counters need the profiler.
 MEASURED_ATTENTION_TRAFFIC = {("attention_kernel", 2): 1.607e9, ("attention_kernel", 4): 3.382e9,
-                              ("attention_kernel", 5): 4.690e9, ("fused_kernel", 4): 3.260e9, ("fused_kernel", 5): 4.605e9}
+                              ("attention_kernel", 5): 4.690e9, ("fused_kernel", 4): 3.258e9, ("fused_kernel", 5): 4.598e9}
 TRAFFIC_SOURCE = "profiles/attention_kernel_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; runs of their own)"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16

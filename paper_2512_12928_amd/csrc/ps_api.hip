@@ -671,7 +671,7 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
   const size_t slots_by_tiles = (size_t)((max_table_entries + max_req) / (2 * kMinSlotTiles)) + 1;
   size_t slots_by_waves =
       (size_t)((c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus) / c->cfg.n_kv_heads) + 1;
-  if (c->cfg.mixed_launch == 2)  // three slots per prefill work item: a query tile, or one of its at most 8 partitions
+  if (c->cfg.mixed_launch != 1)  // the layout with two decode slots per prefill work item (a query tile, or one of its at most 8 partitions) may be picked
     slots_by_waves = std::max(slots_by_waves,
                               (size_t)ps::fused_decode_slots(1, c->G) * 8 * ((size_t)max_tokens / ps::prefill_tile_tokens(c->G) + (size_t)max_req) + 1);
   const size_t max_parts = (size_t)max_req + (c->cfg.decode_chunk > 0
