@@ -353,15 +353,17 @@ __global__ __launch_bounds__(256) void merge_kernel(StepParams P, int first) {
 // its G query heads; wave w owns 32 consecutive query tokens (one 32-column B tile) of head
 // z*HW + w % HW, token sub-tile w / HW.  All eight waves walk the same 64-token KV tiles.
 //
-// KV tiles go from the cache straight into LDS (global_load_lds_dwordx4, no VGPR round trip),
-// in MFMA operand order: a fragment is the 1 KiB that the 64 lanes of a wave feed to one MFMA as
-// its A operand, lane after lane, so it is read back with one conflict-free 16-byte ds_read per
-// lane.  A 64-token tile is two halves of 32 tokens (two blocks each); a half is 8 K fragments
-// (dim chunks) + 8 V fragments (block u, 32 dims).  Wave w fetches K and V fragment w of both
-// halves.  The LDS ring holds kStages tiles; loads run kStages-1 tiles ahead of the compute,
-// one barrier per tile.
+// KV tiles go from the cache straight into LDS (global_load_lds_dwordx4, no VGPR round trip), every load one
+// contiguous KiB of one block's K or V slice (scalar base, fixed per-lane offset, instruction offset).  A 64-token
+// tile is two halves of 32 tokens (two blocks each).  The K of a block lies in LDS as it lies in the cache,
+// [dim/8][token][8 dims]; a wave gathers its A operand of dim chunk c from it with one 16-byte ds_read per lane
+// (row j of the operand = slot kslot(j) of block j>>4, dim group 2c + h2: the 16 lanes of a quarter wave read the 16
+// consecutive slots of one group, so no bank conflict).  V arrives in MFMA operand order: a fragment is the 1 KiB
+// that the 64 lanes feed to one MFMA, lane after lane (fragment 4u+n = dims 32n.. of block u), read back with one
+// conflict-free 16-byte ds_read per lane.  Wave w fetches two KiB of K and two of V of block w >> 1 of the tile.
+// The LDS ring holds kStages tiles; loads run kStages-1 tiles ahead of the compute, one barrier per tile.
 //
-// Row i of a K fragment is token pi(i) of its half (bits 2 and 3 of i swapped).  With the
+// Row j of a K operand is token pi(j) of its half (bits 2 and 3 of j swapped).  With the
 // 32x32 result layout this makes the 8 probabilities a lane holds for MFMA step u the 8
 // consecutive tokens 16u + 8*h2 .. +7, so its V operand is one contiguous 16-byte run of the
 // dim-major V block.
@@ -388,8 +390,8 @@ __device__ __forceinline__ void load_ids(const int* p0, const int* p1, const int
 }
 
 struct PrefillHalf {
-  uint4 k[8][64];
-  uint4 v[8][64];
+  uint4 k[2][256];  // block u of the half as it lies in the cache: [dim/8][token][8 dims], 16 bytes per (dim group, token)
+  uint4 v[8][64];   // fragment 4u+n: dims 32n..32n+31 of block u, in MFMA A-operand lane order
 };
 struct PrefillStage {
   PrefillHalf h[2];
@@ -465,23 +467,29 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
       idv = make_int4(id[0], id[1], id[2], id[3]);
     }
   };
-  // Issues this wave's loads of one tile into ring slot `stage`: K fragment `wave` (dim chunk) and
-  // V fragment `wave` (block wave/4, dims 32*(wave%4)..) of each half.  Every call issues exactly
-  // kLoadsPerTile loads (past the end the last tile is fetched again): the vmcnt bookkeeping
-  // below counts on it.
+  // Issues this wave's loads of one tile into ring slot `stage`.  Wave w fetches from block (w >> 1) of the tile's
+  // four (half w >> 2, block u = (w >> 1) & 1 of the half) the two KiB 2(w & 1), 2(w & 1) + 1 of its K slice (dim
+  // groups 8(w & 1) .. +7, a straight copy) and of its V slice (dims 64(w & 1) .. +63, as two operand fragments).
+  // Every load is one contiguous KiB addressed by a wave-uniform base, a per-lane offset that never changes and an
+  // instruction offset (which counts on the LDS side too): next to busy MFMA waves this form is taken far faster than
+  // one with a 64-bit address per lane.  Every call issues exactly kLoadsPerTile loads (past the end the last tile
+  // is fetched again): the vmcnt bookkeeping below counts on it.
+  const int my_hf = wave >> 2, my_u = (wave >> 1) & 1, my_qp = wave & 1;
+  const uint32_t k_voff = (uint32_t)lane * 16u;
+  const uint32_t v_voff = (uint32_t)(j * kBlockTokens + 8 * h2) * 2u;
   auto issue = [&](int stage, const int4& idv) {
     const int id[4] = {__builtin_amdgcn_readfirstlane(idv.x), __builtin_amdgcn_readfirstlane(idv.y),
                        __builtin_amdgcn_readfirstlane(idv.z), __builtin_amdgcn_readfirstlane(idv.w)};
-    const uint32_t st = sm_base + (uint32_t)stage * (uint32_t)sizeof(PrefillStage);
-    const int f = wave, u = f >> 2, n = f & 3;
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      const int idA = id[2 * hf], idB = id[2 * hf + 1];
-      const uint16_t* krow = k_slice(P.cache, j < 16 ? idA : idB, Hkv, g) + kslot * 8;
-      load_to_lds16(krow + (f * 2 + h2) * (kBlockTokens * 8), st + (uint32_t)hf * 16384u + (uint32_t)f * 1024u);
-      const uint16_t* vs = v_slice(P.cache, u == 0 ? idA : idB, Hkv, g) + (n * 32 + j) * kBlockTokens + 8 * h2;
-      load_to_lds16(vs, st + (uint32_t)hf * 16384u + 8192u + (uint32_t)f * 1024u);
-    }
+    const int blk = my_hf ? (my_u ? id[3] : id[2]) : (my_u ? id[1] : id[0]);
+    const uint32_t st = sm_base + (uint32_t)stage * (uint32_t)sizeof(PrefillStage) + (uint32_t)my_hf * 16384u;
+    const char* kb = (const char*)k_slice(P.cache, blk, Hkv, g) + my_qp * 2048;
+    const char* vb = (const char*)v_slice(P.cache, blk, Hkv, g) + my_qp * 2048;
+    const uint32_t kd = st + (uint32_t)my_u * 4096u + (uint32_t)my_qp * 2048u;
+    const uint32_t vd = st + 8192u + (uint32_t)(my_u * 4 + my_qp * 2) * 1024u;
+    load_to_lds16_sbase<0>(kb, k_voff, kd);
+    load_to_lds16_sbase<1024>(kb, k_voff, kd);
+    load_to_lds16_sbase<0>(vb, v_voff, vd);
+    load_to_lds16_sbase<1024>(vb, v_voff, vd);
   };
 
   if (ids_in_lds) {
@@ -522,14 +530,14 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
     if (ts + kPrefillKV > L) {
       // Last tile of the request: slots past kv_len may hold anything.  The wave that fetched a V
       // fragment zeroes those slots in LDS before anyone multiplies by them (0 * NaN is NaN).
-      const int f = wave, u = f >> 2;
+      const int first = ts + 32 * my_hf + 16 * my_u + 8 * h2;
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        const int first = ts + 32 * hf + 16 * u + 8 * h2;
-        const uint4 vv = sm[stage].h[hf].v[f][lane];
+      for (int k = 0; k < 2; ++k) {
+        const int f = my_u * 4 + my_qp * 2 + k;
+        const uint4 vv = sm[stage].h[my_hf].v[f][lane];
         const uint2 lo = zero_from(make_uint2(vv.x, vv.y), first, L);
         const uint2 hi = zero_from(make_uint2(vv.z, vv.w), first + 4, L);
-        sm[stage].h[hf].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        sm[stage].h[my_hf].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
       }
       __syncthreads();  // workgroup-uniform branch
     }
@@ -543,7 +551,7 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) kf[hf][c] = as_bf16x8(S.h[hf].k[c][lane]);
+        for (int c = 0; c < 8; ++c) kf[hf][c] = as_bf16x8(S.h[hf].k[j >> 4][(2 * c + h2) * 16 + kslot]);
       __builtin_amdgcn_sched_barrier(0);
       f32x16 s[2];
 #pragma unroll
