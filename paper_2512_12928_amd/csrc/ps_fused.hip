@@ -26,8 +26,8 @@
 // Nobody waits at a barrier after the start: MFMA waves wait only for `ready`, feeders only for memory
 // and for `consumed`, decode waves only for memory; pair p's `ready` needs `consumed` of pair p - 4 only,
 // which needs `ready` of p - 4: every wait is for something earlier in that order, so the walk drains.
-// What it buys (MI355X), against the two kinds of work on disjoint compute units: 2 to 8 % off a launch in
-// which neither kind dwarfs the other (the prefill work 0.75 to 4 times the decode work); outside that
+// What it buys (MI355X), against the two kinds of work on disjoint compute units: 6 to 14 % off a launch in
+// which neither kind dwarfs the other (the prefill work 0.6 to 5 times the decode work); outside that
 // range the two layouts take the same time or this one more.  It stops there because every load on a
 // unit, hit or miss, returns at the pace of the misses in front of it, and because a load issued next to
 // MFMA waves costs its wave some 90 cycles (160 with a 64-bit address per lane).
@@ -41,14 +41,11 @@ constexpr int kFusedMfmaWaves = 8;
 constexpr int kFusedMemWaves = 4;     // kFusedFeeders feeders and kFusedDecodeWaves decode waves
 constexpr int kFusedFeeders = 2;
 constexpr int kFusedDecodeWaves = kFusedMemWaves - kFusedFeeders;
-constexpr int kFusedInFlight = 3;   // tiles a feeder keeps in flight at most (16 loads each; the load counter holds 63)
-static_assert(kFusedInFlight <= 3, "the feeder's waits are written for at most three tiles in flight");
 constexpr int kFusedThreads = (kFusedMfmaWaves + kFusedMemWaves) * 64;
 constexpr int kFusedRows = 32;      // query tokens per MFMA wave
 constexpr int kFusedKV = 32;        // KV tokens per ring tile
 constexpr int kFusedRing = 8;       // tiles in the LDS ring
 constexpr int kFusedPairs = kFusedRing / 2;  // handed over in pairs: tiles 2p and 2p + 1 in ring slots (2p) % 8 and (2p + 1) % 8
-constexpr int kFusedIdTiles = 1024; // block ids of up to this many ring tiles (32k tokens) are kept in LDS
 constexpr int kHostTileKV = 64;     // unit of PrefillTile::tile_begin / tile_end
 
 struct FusedStage {
@@ -57,7 +54,6 @@ struct FusedStage {
 };
 struct FusedLds {
   FusedStage ring[kFusedRing];
-  int ids[kFusedIdTiles * 2];
   uint32_t ready[kFusedRing];     // ready[p % 4] = 1 + index of the last pair that landed in pair slot p % 4 (entries 4.. unused)
   uint32_t consumed[kFusedRing];  // MFMA waves that are through with pair slot p % 4, counted over the whole walk
 };
@@ -74,7 +70,7 @@ __device__ __forceinline__ uint32_t lds_peek(const uint32_t* f) {
 constexpr int kFusedSpinLimit = 1 << 18;
 __device__ unsigned int g_fused_gave_up;
 
-// Two block-table entries through the scalar cache (for walks longer than the LDS id table).
+// Two block-table entries through the scalar cache.
 __device__ __forceinline__ void load_ids2(const int* p0, const int* p1, int (&id)[2]) {
   asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
                : "=&s"(id[0]), "=&s"(id[1])
@@ -107,20 +103,12 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
   const int tile0 = t.tile_begin * (kHostTileKV / kFusedKV);  // this partition: tiles [tile0, tile1)
   const int tile1 = t.tile_end * (kHostTileKV / kFusedKV) < reach ? t.tile_end * (kHostTileKV / kFusedKV) : reach;
   const int ntiles = tile1 - tile0;  // workgroup-uniform; the host never makes it < 1
-  const bool ids_in_lds = ntiles <= kFusedIdTiles;
 
   if (bid < kClockSlots) {
     clock_record(P, kClockSlots + bid, 0);
     if (P.clocks != nullptr && threadIdx.x == (kFusedMfmaWaves + kFusedFeeders) * 64) {
       P.clocks[bid * 4 + 0] = __builtin_amdgcn_s_memtime();
       P.clocks[bid * 4 + 1] = __builtin_amdgcn_s_memrealtime();
-    }
-  }
-  if (ids_in_lds) {
-    const int last = nblk - 1;
-    for (int e = threadIdx.x; e < ntiles * 2; e += kFusedThreads) {
-      const int bi = tile0 * (kFusedKV / kBlockTokens) + e;
-      sm.ids[e] = table[bi < last ? bi : last];
     }
   }
   if (threadIdx.x < kFusedRing) {
@@ -305,18 +293,13 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
     };
     // The 16 loads of tile ti: K fragments 0..7 (dim chunks), V fragments 0..7 (block f/4, dims 32*(f%4)..).
     auto issue_tile = [&](int ti) {
-      int idA, idB;
-      if (ids_in_lds) {
-        idA = __builtin_amdgcn_readfirstlane(*(const volatile int*)&sm.ids[ti * 2]);
-        idB = __builtin_amdgcn_readfirstlane(*(const volatile int*)&sm.ids[ti * 2 + 1]);
-      } else {
-        const int b0 = (tile0 + ti) * (kFusedKV / kBlockTokens);
-        const int last = nblk - 1;
-        int id[2];
-        load_ids2(table + b0, table + (b0 + 1 < last ? b0 + 1 : last), id);
-        idA = id[0];
-        idB = id[1];
-      }
+      // the tile's two block ids come through the scalar cache (an absent second block repeats the first and is
+      // fully masked): a feeder keeps away from the LDS, which the MFMA waves' operand reads keep busy
+      const int b0 = (tile0 + ti) * (kFusedKV / kBlockTokens);
+      const int last = nblk - 1;
+      int id[2];
+      load_ids2(table + (b0 < last ? b0 : last), table + (b0 + 1 < last ? b0 + 1 : last), id);
+      const int idA = id[0], idB = id[1];
       const uint32_t st = ring_base + (uint32_t)(ti & (kFusedRing - 1)) * (uint32_t)sizeof(FusedStage);
       // Every load is one contiguous KiB of one block's K or V slice: a wave-uniform base (scalar arithmetic only), a
       // per-lane offset that never changes, and an instruction offset that counts on the LDS side as well.
@@ -341,59 +324,58 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
       load_to_lds16_sbase<2048>(vB, v_voff, st + 12288u);
       load_to_lds16_sbase<3072>(vB, v_voff, st + 12288u);
     };
-    // Tile ti has landed (the caller has waited for its loads): zero what must not be read, and with the last tile of
-    // a pair hand the pair to the MFMA waves.
-    auto landed = [&](int ti) {
-      const int slot = ti & (kFusedRing - 1);
-      const int ts = (tile0 + ti) * kFusedKV;
-      if (ts + kFusedKV > L) {
-        // Last tile of the request: slots past kv_len may hold anything, and 0 * NaN is NaN: zero them in V.
+    // Pair pr has landed (the caller has waited for its loads): zero what must not be read and hand it to the MFMA waves.
+    auto publish = [&](int pr) {
 #pragma unroll
-        for (int f = 0; f < 8; ++f) {
-          const int first = ts + 16 * (f >> 2) + 8 * h2;
-          const uint4 vv = sm.ring[slot].v[f][lane];
-          const uint2 lo = zero_from(make_uint2(vv.x, vv.y), first, L);
-          const uint2 hi = zero_from(make_uint2(vv.z, vv.w), first + 4, L);
-          sm.ring[slot].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      for (int h = 0; h < 2; ++h) {
+        const int ti = 2 * pr + h;
+        const int ts = (tile0 + ti) * kFusedKV;
+        if (ti < ntiles && ts + kFusedKV > L) {
+          // Last tile of the request: slots past kv_len may hold anything, and 0 * NaN is NaN: zero them in V.
+          const int slot = ti & (kFusedRing - 1);
+#pragma unroll
+          for (int f = 0; f < 8; ++f) {
+            const int first = ts + 16 * (f >> 2) + 8 * h2;
+            const uint4 vv = sm.ring[slot].v[f][lane];
+            const uint2 lo = zero_from(make_uint2(vv.x, vv.y), first, L);
+            const uint2 hi = zero_from(make_uint2(vv.z, vv.w), first + 4, L);
+            sm.ring[slot].v[f][lane] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          }
         }
       }
-      if ((ti & 1) || ti + 1 >= ntiles) {
-        asm volatile("" ::: "memory");  // the flag is written after the tiles, in program order (LDS keeps it)
-        if (lane == 0) *(volatile uint32_t*)&sm.ready[(ti >> 1) & (kFusedPairs - 1)] = (uint32_t)((ti >> 1) + 1);
-      }
+      asm volatile("" ::: "memory");  // the flag is written after the tiles, in program order (LDS keeps it)
+      if (lane == 0) *(volatile uint32_t*)&sm.ready[pr & (kFusedPairs - 1)] = (uint32_t)(pr + 1);
     };
-    // This feeder's q-th tile: the two tiles of its pair q / 2.
-    auto tile_of = [&](int q) { return 2 * (mw + kFusedFeeders * (q >> 1)) + (q & 1); };
-    // Issue whenever the next tile has room (a pair's first tile asks whether the pair's slots are free) and fewer
-    // than kFusedInFlight tiles are out; otherwise wait for the oldest tile in flight (loads return in issue order:
-    // with at most 16 * k still out, all but the youngest k tiles have landed).
-    int qh = 0, qt = 0, nfl = 0, spins = 0;  // next tile to issue, oldest tile in flight, tiles in flight
-    while (tile_of(qt) < ntiles) {
-      const int th = tile_of(qh);
-      if (nfl < kFusedInFlight && th < ntiles && ((qh & 1) || pair_free(th >> 1))) {
-        issue_tile(th);
-        ++qh;
-        ++nfl;
-        spins = 0;
-        continue;
-      }
-      if (nfl > 0) {
-        if (nfl >= 3)
-          asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
-        else if (nfl == 2)
-          asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-        else
+    // One pass per pair, and one look at the LDS per pass: wait until the pair's slots are free, issue its first tile,
+    // hand over the pair before (loads return in issue order: with at most the 16 loads just issued still out, it has
+    // landed), issue the second tile.  At most three tiles are in flight (the load counter holds 63).
+    int prev = -1;  // the pair in flight
+    for (int pr = mw; 2 * pr < ntiles; pr += kFusedFeeders) {
+      int spins = 0;
+      while (!pair_free(pr)) {
+        if (prev >= 0) {  // do not sit on a pair that has landed meanwhile
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        landed(tile_of(qt));
-        ++qt;
-        --nfl;
-        continue;
+          publish(prev);
+          prev = -1;
+          continue;
+        }
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > kFusedSpinLimit) {  // nothing of this wave is in flight here: prev was handed over above
+          if (lane == 0) atomicAdd(&g_fused_gave_up, 1u);
+          return;
+        }
       }
-      __builtin_amdgcn_s_sleep(1);
-      if (++spins > kFusedSpinLimit) {
-        if (lane == 0) atomicAdd(&g_fused_gave_up, 1u);
-        break;
+      issue_tile(2 * pr);
+      if (prev >= 0) {
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        publish(prev);
       }
+      if (2 * pr + 1 < ntiles) issue_tile(2 * pr + 1);
+      prev = pr;
+    }
+    if (prev >= 0) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      publish(prev);
     }
     return;
   }

@@ -83,8 +83,8 @@ def test_scaled_workloads(idx, scale):
 
 
 def test_walk_longer_than_the_id_table():
-    """A chunk over a 36 000-token prefix, unsplit: more tiles than the LDS table of block ids holds, so the feeders
-    read the ids through the scalar cache; next to a 70 000-token decode request."""
+    """A chunk over a 36 000-token prefix, unsplit (a walk of more than a thousand ring tiles by one workgroup), next
+    to a 70 000-token decode request."""
     check(*custom_batch(2, 1, [(40, 40 + 36_000), (1, 70_000), (1, 5)], seed=31), prefill_split_tiles=-1)
 
 
