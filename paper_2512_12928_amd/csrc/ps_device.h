@@ -13,6 +13,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define PS_NEG_INF (-__builtin_inff())
+// Online softmax with a lazy running maximum (prefill role): the accumulators are rescaled only when some row's
+// tile maximum exceeds the row's reference m by more than this many powers of two.  Until then m stays below the true
+// maximum, the probabilities of a row are at most 2^kRescaleSlack instead of at most 1, and the row sum and the
+// accumulators carry the same factor, which the final division (or the merge, which is handed this m) takes out:
+// the result is the same up to rounding, fp32 has the range, and bf16 has fp32's exponent.  Each rescale it saves is
+// 64 multiplications per lane that stand between the output MFMAs of one tile and those of the next.
+#define PS_RESCALE_SLACK 8.f
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   f32x2 v = {a, b};

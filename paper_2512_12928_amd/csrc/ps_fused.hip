@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         for (int e = 3; e < 15; e += 2) tmax = max3(tmax, s[e], s[e + 1]);
         tmax = fmaxf(tmax, s[15]);
         tmax = xor32_max(tmax) * P.scale_log2;
-        if (__builtin_amdgcn_ballot_w64(tmax > m) != 0) {  // rescale only when some row's max grew
+        if (__builtin_amdgcn_ballot_w64(tmax > m + PS_RESCALE_SLACK) != 0) {  // some row outgrew its reference
           const float m_new = fmaxf(m, tmax);
           const float alpha = m_new == PS_NEG_INF ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
           l *= alpha;

@@ -590,7 +590,7 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
       tmax = xor32_max(tmax) * P.scale_log2;
       // a row that sees nothing in this tile keeps its m; a row that has seen nothing yet in this
       // partition has m = -inf, l = 0 and all-zero accumulators
-      if (__builtin_amdgcn_ballot_w64(tmax > m) != 0) {  // rescale only when some row's max grew
+      if (__builtin_amdgcn_ballot_w64(tmax > m + PS_RESCALE_SLACK) != 0) {  // some row outgrew its reference
         const float m_new = fmaxf(m, tmax);
         const float alpha = m_new == PS_NEG_INF ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
         l *= alpha;
