@@ -124,20 +124,31 @@ def main() -> int:
                     B.ps_step_next_layer(ctx, q, kn, vn, pool, out, ws, nbytes, stream)
             host_us[name] = (time.perf_counter() - t0) / 3 * 1e6
             torch.cuda.synchronize()
-        # per-launch durations: HIP events recorded by the library on the launch stream.  Mode 1: the
-        # phases as they run; mode 2: the decode and the prefill work in launches of their own
+        # per-launch durations: HIP events recorded by the library on the launch stream, one set per step, read once
+        # after the last step.  Mode 1: the timed region again, the same `steps` calls back to back, with the events
+        # on (the library averages over the last 64 steps; the region's own ms_per_step is reported beside the
+        # headline one).  Mode 2: the decode and the prefill work in launches of their own, `profile_steps` steps
+        # back to back.
         phases = {}
-        for mode in (1, 2):
-            B.ps_set_profiling(ctx, mode)
-            acc = {}
-            for _ in range(profile_steps):
-                B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
-                for k, v in B.ps_get_step_times(ctx).items():
-                    acc[k] = acc.get(k, 0.0) + v / profile_steps
-            phases[mode] = acc
+        B.ps_set_profiling(ctx, 1)
+        for _ in range(warmup):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+        torch.cuda.synchronize()
+        if warmup > 0:
+            B.ps_get_step_times(ctx)                      # the warm-up steps are not part of the mean
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+        torch.cuda.synchronize()
+        dt_events = time.perf_counter() - t0
+        phases[1] = B.ps_get_step_times(ctx)
+        B.ps_set_profiling(ctx, 2)
+        for _ in range(profile_steps):
+            B.ps_step(ctx, cb, q, kn, vn, pool, out, ws, nbytes, stream)
+        phases[2] = B.ps_get_step_times(ctx)
         B.ps_set_profiling(ctx, 0)
-        res = dict(ms_per_step=dt / steps * 1e3, phases_ms=phases, ctx=ctx, pool=pool, q=q, out=out, kn=kn, vn=vn,
-                   ms_per_layer_plan_reused=dt_pass * 1e3, host_us_per_call=host_us)
+        res = dict(ms_per_step=dt / steps * 1e3, ms_per_step_with_events=dt_events / steps * 1e3, phases_ms=phases, ctx=ctx,
+                   pool=pool, q=q, out=out, kn=kn, vn=vn, ms_per_layer_plan_reused=dt_pass * 1e3, host_us_per_call=host_us)
         return res
 
     def rooflines(batch, res):
@@ -154,7 +165,8 @@ def main() -> int:
                                 decode_chunk=args.decode_chunk)
         both = plan["decode_slots"] > 0 and plan["prefill_workgroups"] > 0
         return dict(kernel="fused_kernel" if both and plan["decode_workgroups"] == 0 else "attention_kernel",
-                    attention_ms=run_["attention_ms"], attention_GBps=att_gbs, attention_hbm_frac=att_gbs / HBM_PEAK_GBS,
+                    attention_ms=run_["attention_ms"], ms_per_step_with_events=res["ms_per_step_with_events"],
+                    attention_GBps=att_gbs, attention_hbm_frac=att_gbs / HBM_PEAK_GBS,
                     attention_TFLOPs=att_tf, attention_mfma_frac=att_tf / MFMA_BF16_PEAK_TFLOPS,
                     attention_bytes=bytes_dec + bytes_pre, prefill_flops=flops_pre,
                     append_ms=run_["append_ms"], merge_ms=run_["merge_ms"],
@@ -309,15 +321,19 @@ def roof_of(rl, workload):
     HBM peak, or all prefill FLOPs at the bf16 MFMA peak."""
     t_hbm = rl["attention_bytes"] / (HBM_PEAK_GBS * 1e9)
     t_mfma = rl["prefill_flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    how = dict(launch_us=rl["attention_ms"] * 1e3,
+               launch_us_from="HIP events of the library on the launch stream around every launch of the timed steps run again "
+                              "back to back with those events on (mean over the last 64 launches; ms_per_step of that region: "
+                              "%.4f)" % rl["ms_per_step_with_events"])
     if t_hbm >= t_mfma:
         return dict(bound="hbm", kernel=rl["kernel"], achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=rl["attention_hbm_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get((rl["kernel"], workload)),
+                    frac=rl["attention_hbm_frac"], **how, traffic=MEASURED_ATTENTION_TRAFFIC.get((rl["kernel"], workload)),
                     traffic_source=TRAFFIC_SOURCE if (rl["kernel"], workload) in MEASURED_ATTENTION_TRAFFIC else None,
                     shader_mhz=rl["shader_mhz"],
                     other_roof=dict(bound="mfma", achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                                     frac=rl["attention_mfma_frac"]))
     return dict(bound="mfma", kernel=rl["kernel"], achieved=rl["attention_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS,
-                unit="TFLOP/s", frac=rl["attention_mfma_frac"], traffic=MEASURED_ATTENTION_TRAFFIC.get((rl["kernel"], workload)),
+                unit="TFLOP/s", frac=rl["attention_mfma_frac"], **how, traffic=MEASURED_ATTENTION_TRAFFIC.get((rl["kernel"], workload)),
                 traffic_source=TRAFFIC_SOURCE if (rl["kernel"], workload) in MEASURED_ATTENTION_TRAFFIC else None,
                 shader_mhz=rl["shader_mhz"],
                 other_roof=dict(bound="hbm", achieved=rl["attention_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",

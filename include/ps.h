@@ -88,7 +88,7 @@ typedef struct {
      another part, clock or power limit wants its own (time two probe launches: a decode-only and a
      prefill-only batch with ps_set_profiling(ctx, 2)).                                            */
   float plan_stream_TBps;      /* rate at which decode waves on the whole chip stream the cache [6.3]  */
-  float plan_tile_step_us;     /* one 64-token KV tile step of a prefill workgroup [1.92]              */
+  float plan_tile_step_us;     /* one 64-token KV tile step of a prefill workgroup [1.78]              */
   float plan_merge_launch_steps; /* a merge launch, in tile steps [4.0]                                */
   float plan_merge_row_steps;  /* merging one split row of 32 heads, in tile steps [0.0047]            */
   float plan_decode_share;     /* fraction of the balanced decode share actually given to decode: the
@@ -111,10 +111,10 @@ typedef struct {
                               workgroup carries both (a prefill tile walk on eight waves, next to them two
                               waves that fetch the walk's tiles and two that walk decode slots; needs
                               decode_chunk and decode_waves 0, else as 1).  0 (default): the library picks:
-                              2 when neither kind of work dwarfs the other (the prefill work priced at 0.6
-                              to 5 times the decode work) and there are at least two prefill workgroups per
-                              compute unit (measured 1 to 14 % faster on such launches, the same or slower
-                              outside that range), else 1.                                            */
+                              2 when neither kind of work dwarfs the other (the prefill work priced at 0.65
+                              to 4.5 times the decode work) and there are at least two prefill workgroups
+                              per compute unit (measured 3 to 15 % faster on such launches, the same or
+                              slower outside that range), else 1.                                     */
 } ps_layer_cfg;
 
 /* One mixed batch (the output of Alg. 1 as the attention layer sees it). HOST arrays. */
@@ -257,12 +257,17 @@ int ps_mixed_launch_faults(uint32_t* out);
 
 /* Per-phase GPU timing of ps_step with events on its stream (adds a few microseconds), and the shader
  * clock its attention workgroups ran at (clock counters read in the kernel).  The first call with a
- * non-zero mode allocates 128 KiB of device memory for those counters; no step allocates for them.
+ * non-zero mode allocates 128 KiB of device memory for those counters and creates the events; no step
+ * allocates for them.  Every call restarts the series that ps_get_step_times averages.
  * mode 0: off; 1: the phases as they run; 2: the decode and the prefill work of the attention
  * phase in launches of their own, one after the other. PS_EINVAL for any other mode; PS_EHIP if the
  * allocation fails. */
 int ps_set_profiling(ps_ctx* ctx, int mode);
-/* Blocks until the last profiled step has finished, then fills *out. */
+/* Blocks until the last profiled step has finished, then fills *out with the mean over the profiled steps
+ * enqueued since the previous call (the most recent 64 of them; events are kept per step, so many steps can
+ * run back to back with no host synchronisation between them and be read once); the clocks are those of the
+ * last step.  With no profiled step since the previous call, that call's figures again.  PS_ESTATE before the
+ * first profiled step. */
 int ps_get_step_times(ps_ctx* ctx, ps_step_times* out);
 
 /* Asynchronous offload (Sec. 4.3): host_pool[host_slot_ids[k]] <- cache[dev_block_ids[k]] for

@@ -100,7 +100,14 @@ struct ps_ctx {
   hipStream_t copy = nullptr;
   int n_cus = 256;
   int profiling = 0;  // 0 off, 1 phases as they run, 2 decode and prefill roles in launches of their own
-  hipEvent_t prof_ev[6];
+  // profiling: the events of the last kProfRing profiled steps; step number prof_n records into slot prof_n % kProfRing
+  // (slot 0 exists from ps_create on, the others from the first ps_set_profiling that switches profiling on)
+  static constexpr int kProfRing = 64;
+  hipEvent_t prof_ring[kProfRing][6];
+  uint64_t prof_n = 0;       // profiled steps enqueued since ps_set_profiling
+  uint64_t prof_read = 0;    // of which ps_get_step_times has reported
+  ps_step_times prof_last;   // its last report
+  hipEvent_t* prof_ev_now() { return prof_ring[prof_n % kProfRing]; }
   unsigned long long* clocks_dev = nullptr;  // profiling: clock counters of the attention workgroups (ps_set_profiling allocates)
   int prof_wgs[2] = {0, 0};                  // decode / prefill workgroups of the last profiled step
   bool prof_valid = false;
@@ -143,7 +150,7 @@ struct PlanTuning {
 PlanTuning tuning_of(const ps_layer_cfg& c) {
   PlanTuning t;
   t.stream_TBps = c.plan_stream_TBps > 0.f ? c.plan_stream_TBps : 6.3;
-  t.tile_step_us = c.plan_tile_step_us > 0.f ? c.plan_tile_step_us : 1.92;
+  t.tile_step_us = c.plan_tile_step_us > 0.f ? c.plan_tile_step_us : 1.78;
   t.merge_launch_steps = c.plan_merge_launch_steps > 0.f ? c.plan_merge_launch_steps : 4.0;
   t.merge_row_steps = c.plan_merge_row_steps > 0.f ? c.plan_merge_row_steps : 0.0047;
   t.decode_share = c.plan_decode_share > 0.f ? c.plan_decode_share : 0.95;
@@ -590,7 +597,8 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
   const float scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   c->scale_log2 = scale * 1.4426950408889634f;
   for (auto& e : c->ticket_ev) e = nullptr;
-  for (auto& e : c->prof_ev) e = nullptr;
+  for (auto& slot_ev : c->prof_ring)
+    for (auto& e : slot_ev) e = nullptr;
   for (auto& t : c->ticket_id) t = 0;
   hipError_t e = hipGetDevice(&c->device);
   if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, c->device);
@@ -606,7 +614,7 @@ int ps_create(const ps_layer_cfg* cfg, ps_ctx** out) {
     e = hipEventCreateWithFlags(&c->swap_slot[i].ev, hipEventDisableTiming);
   for (int i = 0; i < kTicketRing && e == hipSuccess; ++i)
     e = hipEventCreateWithFlags(&c->ticket_ev[i], hipEventDisableTiming);
-  for (int i = 0; i < 6 && e == hipSuccess; ++i) e = hipEventCreate(&c->prof_ev[i]);
+  for (int i = 0; i < 6 && e == hipSuccess; ++i) e = hipEventCreate(&c->prof_ring[0][i]);
   if (cfg->own_streams) {
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking);
   }
@@ -644,8 +652,9 @@ void ps_destroy(ps_ctx* c) {
   }
   for (auto& e : c->ticket_ev)
     if (e) (void)hipEventDestroy(e);
-  for (auto& e : c->prof_ev)
-    if (e) (void)hipEventDestroy(e);
+  for (auto& slot_ev : c->prof_ring)
+    for (auto& e : slot_ev)
+      if (e) (void)hipEventDestroy(e);
   if (c->copy) (void)hipStreamDestroy(c->copy);
   if (c->clocks_dev) (void)hipFree(c->clocks_dev);
   for (auto& st : c->staging) {
@@ -730,8 +739,13 @@ int ps_set_profiling(ps_ctx* c, int enabled) {
     PS_HIP(hipMalloc((void**)&c->clocks_dev, bytes));
     PS_HIP(hipMemset(c->clocks_dev, 0, bytes));
   }
+  if (enabled)
+    for (auto& slot_ev : c->prof_ring)
+      for (auto& e : slot_ev)
+        if (!e) PS_HIP(hipEventCreate(&e));
   c->profiling = enabled;
   c->prof_valid = false;
+  c->prof_n = c->prof_read = 0;
   return PS_OK;
 }
 
@@ -739,19 +753,38 @@ int ps_get_step_times(ps_ctx* c, ps_step_times* out) {
   if (!c || !out) return fail(PS_EINVAL, "NULL argument");
   std::memset(out, 0, sizeof *out);
   if (!c->prof_valid) return fail(PS_ESTATE, "no profiled step");
-  PS_HIP(hipEventSynchronize(c->prof_ev[5]));
-  float att = 0.f, pre = 0.f;
-  PS_HIP(hipEventElapsedTime(&out->upload_ms, c->prof_ev[0], c->prof_ev[1]));
-  PS_HIP(hipEventElapsedTime(&out->append_ms, c->prof_ev[1], c->prof_ev[2]));
-  PS_HIP(hipEventElapsedTime(&att, c->prof_ev[2], c->prof_ev[3]));
-  PS_HIP(hipEventElapsedTime(&pre, c->prof_ev[3], c->prof_ev[4]));
-  PS_HIP(hipEventElapsedTime(&out->merge_ms, c->prof_ev[4], c->prof_ev[5]));
+  // the mean over the profiled steps enqueued since the last report (the most recent kProfRing of them): a caller
+  // that asks after every step gets that step, one that runs many steps back to back and asks once gets their mean
+  // with no host synchronisation in between
+  const uint64_t fresh = std::min<uint64_t>(c->prof_n - c->prof_read, ps_ctx::kProfRing);
+  if (fresh == 0) {
+    *out = c->prof_last;
+    return PS_OK;
+  }
+  double sum[6] = {0, 0, 0, 0, 0, 0};
+  for (uint64_t k = c->prof_n - fresh; k < c->prof_n; ++k) {
+    hipEvent_t* ev = c->prof_ring[k % ps_ctx::kProfRing];
+    PS_HIP(hipEventSynchronize(ev[5]));
+    float t = 0.f;
+    for (int i = 0; i < 5; ++i) {
+      PS_HIP(hipEventElapsedTime(&t, ev[i], ev[i + 1]));
+      sum[i] += t;
+    }
+    PS_HIP(hipEventElapsedTime(&t, ev[0], ev[5]));
+    sum[5] += t;
+  }
+  c->prof_read = c->prof_n;
+  const double inv = 1.0 / (double)fresh;
+  out->upload_ms = (float)(sum[0] * inv);
+  out->append_ms = (float)(sum[1] * inv);
+  const float att = (float)(sum[2] * inv), pre = (float)(sum[3] * inv);
+  out->merge_ms = (float)(sum[4] * inv);
   if (c->prof_mode == 2) {
     out->decode_ms = att;
     out->prefill_ms = pre;
   }
   out->attention_ms = att + pre;
-  PS_HIP(hipEventElapsedTime(&out->total_ms, c->prof_ev[0], c->prof_ev[5]));
+  out->total_ms = (float)(sum[5] * inv);
   // shader clock of each role's workgroups: the median over the recorded ones of (shader-clock ticks) / (100 MHz ticks)
   if (c->clocks_dev) {
     std::vector<unsigned long long> rec((size_t)2 * ps::kClockSlots * 4);
@@ -772,6 +805,7 @@ int ps_get_step_times(ps_ctx* c, ps_step_times* out) {
       (role == 0 ? out->decode_mhz : out->prefill_mhz) = med;
     }
   }
+  c->prof_last = *out;
   return PS_OK;
 }
 
@@ -826,15 +860,16 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
 
   // Decode slots.  With prefill work in the same launch the decode workgroups get the share of the
   // CUs that makes both kinds of work end together (each priced at its full-chip speed: 6.3 TB/s
-  // for the cache stream, 1.92 us per KV tile step of a prefill workgroup; the decode share is cut
+  // for the cache stream, 1.78 us per KV tile step of a prefill workgroup; the decode share is cut
   // by 5 %: prefill workgroups inherit CUs that decode leaves early, never the other way round).
   {
     int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
     // Every workgroup carries both kinds of work (two decode slots per prefill work item and z-split).  Forced by
     // cfg.mixed_launch = 2; picked by the library when neither kind of work dwarfs the other (the prefill work priced
-    // at 0.6 to 5 times the decode work) and there are at least two prefill workgroups per compute unit.  Measured on
-    // an MI355X against disjoint units, by that ratio: 6.4, the same; 3.6, -2.5 %; 2.6, -8 %; 1.95, -7 %; 1.3, -14 %;
-    // 1.0, -12 to -13 %; 0.65 and 0.48, -1 %; 0.46 with half the prefill workgroups, 4 % slower.
+    // at 0.65 to 4.5 times the decode work) and there are at least two prefill workgroups per compute unit.  Measured on
+    // an MI355X against disjoint units, by that ratio: 10, 4 % slower; 5.6, 1 % slower; 3.2, -2.6 %; 1.8, -10 %;
+    // 1.2, -15 %; 0.9, -10 %; 0.58 and 0.44, 1 to 2 % slower; 0.29, 7 % slower; with fewer prefill workgroups 0.92,
+    // -10 %; 0.43, 6 % slower.
     const bool fusable = c->cfg.decode_waves == 0 && c->cfg.decode_chunk == 0 && c->profiling != 2 && !decode_reqs.empty() &&
                          !tiles.empty() && ps::fused_supports(c->G) &&
                          (int64_t)ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads <= INT32_MAX;
@@ -844,7 +879,7 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
       const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / (tune.stream_TBps * 1e6);  // us
       const double t_p = prefill_steps * tune.tile_step_us;
       const int64_t wgs = (int64_t)tiles.size() * c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
-      c->plan_fused = t_p >= 0.6 * t_d && t_p <= 5.0 * t_d && wgs >= 2 * (int64_t)c->n_cus;
+      c->plan_fused = t_p >= 0.65 * t_d && t_p <= 4.5 * t_d && wgs >= 2 * (int64_t)c->n_cus;
     }
     if (c->plan_fused) {
       waves = ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads;
@@ -943,16 +978,16 @@ static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps
   // over the host link (a third of the latency of a DMA copy).
   PS_HIP(ps::launch_prologue(P, h, w, upload_bytes, aitems_src, k_new ? (int)c->aitems.size() : 0, stream));
   if (h && (upload_bytes > 0 || k_new)) PS_HIP(hipEventRecord(slot.ev, stream));  // last reader of the pinned slot
-  if (prof) PS_HIP(hipEventRecord(c->prof_ev[2], stream));
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev_now()[2], stream));
   // Attention: one launch for the decode slots and the prefill tiles (decode streams the cache at
   // HBM speed and leaves the matrix pipes idle, prefill is the opposite: they run side by side on
   // disjoint CUs).  Profiling mode 2 gives each its own launch instead.
   const int n_slots = (int)c->plan.dslots.size() - 1;
   if (prof == 2) {
     PS_HIP(ps::launch_attention(P, n_slots, 0, stream, &c->prof_wgs[0], nullptr));
-    PS_HIP(hipEventRecord(c->prof_ev[3], stream));
+    PS_HIP(hipEventRecord(c->prof_ev_now()[3], stream));
     PS_HIP(ps::launch_attention(P, 0, (int)c->ptiles.size(), stream, nullptr, &c->prof_wgs[1]));
-    PS_HIP(hipEventRecord(c->prof_ev[4], stream));
+    PS_HIP(hipEventRecord(c->prof_ev_now()[4], stream));
   } else {
     if (c->plan_fused) {
       PS_HIP(ps::launch_fused(P, n_slots, (int)c->ptiles.size(), stream, &c->prof_wgs[1]));
@@ -961,13 +996,14 @@ static int launch_phases(ps_ctx* c, const char* h, size_t upload_bytes, const ps
       PS_HIP(ps::launch_attention(P, n_slots, (int)c->ptiles.size(), stream, &c->prof_wgs[0], &c->prof_wgs[1]));
     }
     if (prof) {
-      PS_HIP(hipEventRecord(c->prof_ev[3], stream));
-      PS_HIP(hipEventRecord(c->prof_ev[4], stream));
+      PS_HIP(hipEventRecord(c->prof_ev_now()[3], stream));
+      PS_HIP(hipEventRecord(c->prof_ev_now()[4], stream));
     }
   }
   PS_HIP(ps::launch_merge(P, 0, (int)c->plan.mitems.size(), stream));
   if (prof) {
-    PS_HIP(hipEventRecord(c->prof_ev[5], stream));
+    PS_HIP(hipEventRecord(c->prof_ev_now()[5], stream));
+    ++c->prof_n;
     c->prof_valid = true;
     c->prof_mode = prof;
   }
@@ -1090,8 +1126,8 @@ static int step_impl(ps_ctx* c, const ps_batch* b, const void* q, const void* k_
     if (ss->used[which] && ss->last_stream[which] != stream) PS_HIP(hipStreamWaitEvent(stream, ss->done[which], 0));
     ss->used[which] = true;
     if (prof) {
-      PS_HIP(hipEventRecord(c->prof_ev[0], stream));
-      PS_HIP(hipEventRecord(c->prof_ev[1], stream));
+      PS_HIP(hipEventRecord(c->prof_ev_now()[0], stream));
+      PS_HIP(hipEventRecord(c->prof_ev_now()[1], stream));
     }
     slot.in_flight = true;
     c->last.valid = false;
@@ -1126,19 +1162,19 @@ static int step_impl(ps_ctx* c, const ps_batch* b, const void* q, const void* k_
     PS_HIP(hipEventRecord(slot.ev, c->copy));
     PS_HIP(hipEventRecord(mb.uploaded, c->copy));
     if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
-    if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
+    if (prof) PS_HIP(hipEventRecord(c->prof_ev_now()[0], stream));
     PS_HIP(hipStreamWaitEvent(stream, mb.uploaded, 0));
   } else {  // everything on the caller's stream (the two buffers still alternate)
     if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
     // the step before last read this copy of the description; on the same stream it is over by order, on another
     // stream this one waits for it before the prologue overwrites the lists
     if (mb.used && mb.last_stream != stream) PS_HIP(hipStreamWaitEvent(stream, mb.done, 0));
-    if (prof) PS_HIP(hipEventRecord(c->prof_ev[0], stream));
+    if (prof) PS_HIP(hipEventRecord(c->prof_ev_now()[0], stream));
     // the upload is part of the prologue kernel launched below
   }
   slot.in_flight = true;
   mb.used = true;
-  if (prof) PS_HIP(hipEventRecord(c->prof_ev[1], stream));
+  if (prof) PS_HIP(hipEventRecord(c->prof_ev_now()[1], stream));
   c->last.valid = false;
   c->last.meta_dev = mb.dev;
   c->last.mb = &mb;
@@ -1186,8 +1222,8 @@ int ps_step_next_layer(ps_ctx* c, const void* q, const void* k_new, const void* 
     return fail(PS_ENOMEM, "workspace too small: need %zu bytes, have %zu", c->last.part_bytes, workspace_bytes);
   if (wait_ev) PS_HIP(hipStreamWaitEvent(stream, wait_ev, 0));
   if (c->profiling) {
-    PS_HIP(hipEventRecord(c->prof_ev[0], stream));
-    PS_HIP(hipEventRecord(c->prof_ev[1], stream));
+    PS_HIP(hipEventRecord(c->prof_ev_now()[0], stream));
+    PS_HIP(hipEventRecord(c->prof_ev_now()[1], stream));
   }
   // the append items are taken from the device copy of the batch description this time
   const char* w = c->last.meta_dev;

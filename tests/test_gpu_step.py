@@ -345,4 +345,23 @@ def test_profiling_times_are_reported():
     with pytest.raises(B.PsError) as e:
         B.ps_set_profiling(lay.ctx, 3)
     assert e.value.code == B.PS_EINVAL
+    # Many steps back to back, read once: the mean over the steps since the last read (the library keeps the events
+    # of the last 64).  It lies between the fastest and the slowest step read one at a time, give or take what running
+    # back to back changes; a second read with no step in between repeats the first.
+    B.ps_set_profiling(lay.ctx, 1)
+    q_dev, c_dev = u16_to_dev(t.q), u16_to_dev(to_device_layout(cache.pool))
+    singles = []
+    for _ in range(5):
+        lay.step(b, q_dev, c_dev)
+        singles.append(B.ps_get_step_times(lay.ctx)["attention_ms"])
+    for _ in range(70):
+        lay.step(b, q_dev, c_dev)
+    mean = B.ps_get_step_times(lay.ctx)
+    assert 0.5 * min(singles) < mean["attention_ms"] < 2.0 * max(singles)
+    assert mean["total_ms"] >= mean["attention_ms"] > 0
+    assert B.ps_get_step_times(lay.ctx) == mean
+    with pytest.raises(B.PsError) as e:          # switching the mode restarts the series
+        B.ps_set_profiling(lay.ctx, 1)
+        B.ps_get_step_times(lay.ctx)
+    assert e.value.code == B.PS_ESTATE
     lay.close()

@@ -142,7 +142,7 @@ def test_planner_constants_move_the_share_and_the_split():
     out give the default plan, a dear merge forbids the row split."""
     b = W.make_workload(2)
     base = plan(b)
-    same = plan(b, plan_stream_TBps=6.3, plan_tile_step_us=1.92, plan_merge_launch_steps=4.0, plan_merge_row_steps=0.0047,
+    same = plan(b, plan_stream_TBps=6.3, plan_tile_step_us=1.78, plan_merge_launch_steps=4.0, plan_merge_row_steps=0.0047,
                 plan_decode_share=0.95, plan_decode_knee_cus=176)
     assert same == base
     assert plan(b, plan_stream_TBps=12.6)["decode_workgroups"] < base["decode_workgroups"]
