@@ -129,11 +129,35 @@ __device__ __forceinline__ void load_to_lds16_sbase(const void* sbase, uint32_t 
       : "memory");
 }
 
-// max of three without the NaN-quieting moves the compiler wraps around fmaxf of MFMA results
-// (the inputs here are never NaN: finite scores or -inf)
-__device__ __forceinline__ float max3(float a, float b, float c) {
+// Largest of the 16 elements a lane holds of a 32x32 MFMA result, without the NaN-quieting moves the compiler wraps
+// around fmaxf (the inputs are never NaN: finite scores or -inf).  The ISA asks for 11 wait states between an 8-pass
+// MFMA and a vector instruction that reads its result, and the compiler counts none for instructions inside inline asm
+// (nor does it keep a separate NOP statement in front of them): with NOPS the block starts with those wait states, so
+// it may follow the MFMA at once.
+template <bool NOPS>
+__device__ __forceinline__ float max16(const f32x16& s) {
   float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  if (NOPS)
+    asm("s_nop 7\n\ts_nop 3\n\t"
+        "v_max3_f32 %0, %1, %2, %3\n\tv_max3_f32 %0, %0, %4, %5\n\tv_max3_f32 %0, %0, %6, %7\n\t"
+        "v_max3_f32 %0, %0, %8, %9\n\tv_max3_f32 %0, %0, %10, %11\n\tv_max3_f32 %0, %0, %12, %13\n\t"
+        "v_max3_f32 %0, %0, %14, %15\n\tv_max_f32 %0, %0, %16"
+        : "=&v"(r)
+        : "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]), "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]), "v"(s[8]), "v"(s[9]),
+          "v"(s[10]), "v"(s[11]), "v"(s[12]), "v"(s[13]), "v"(s[14]), "v"(s[15]));
+  else
+    asm("v_max3_f32 %0, %1, %2, %3\n\tv_max3_f32 %0, %0, %4, %5\n\tv_max3_f32 %0, %0, %6, %7\n\t"
+        "v_max3_f32 %0, %0, %8, %9\n\tv_max3_f32 %0, %0, %10, %11\n\tv_max3_f32 %0, %0, %12, %13\n\t"
+        "v_max3_f32 %0, %0, %14, %15\n\tv_max_f32 %0, %0, %16"
+        : "=&v"(r)
+        : "v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]), "v"(s[4]), "v"(s[5]), "v"(s[6]), "v"(s[7]), "v"(s[8]), "v"(s[9]),
+          "v"(s[10]), "v"(s[11]), "v"(s[12]), "v"(s[13]), "v"(s[14]), "v"(s[15]));
+  return r;
+}
+// max of two that are never NaN
+__device__ __forceinline__ float max2(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
   return r;
 }
 

@@ -196,13 +196,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
             if (tok > qpos) s[e] = PS_NEG_INF;
           }
         }
-        // max3 is inline asm, so the compiler does not count the wait states the ISA requires between an
-        // MFMA and a VALU read of its result; the NOPs make that independent of instruction scheduling
-        asm volatile("s_nop 7\n\ts_nop 3" ::: "memory");
-        float tmax = max3(s[0], s[1], s[2]);
-#pragma unroll
-        for (int e = 3; e < 15; e += 2) tmax = max3(tmax, s[e], s[e + 1]);
-        tmax = fmaxf(tmax, s[15]);
+        float tmax = max16<true>(s);  // starts with the wait states an MFMA result needs
         tmax = xor32_max(tmax) * P.scale_log2;
         if (__builtin_amdgcn_ballot_w64(tmax > m + PS_RESCALE_SLACK) != 0) {  // some row outgrew its reference
           const float m_new = fmaxf(m, tmax);

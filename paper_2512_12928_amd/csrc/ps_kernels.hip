@@ -577,16 +577,8 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
             if (tok > qpos) s[hf][e] = PS_NEG_INF;
           }
       }
-      // max3 is inline asm, so the compiler does not count the wait states the ISA requires between an
-      // MFMA and a VALU read of its result (11 for these 8-pass MFMAs); the 16 V-fragment reads above
-      // already separate them, the NOPs make it independent of instruction scheduling
-      asm volatile("s_nop 7\n\ts_nop 3" ::: "memory");
-      float tmax = max3(s[0][0], s[0][1], s[1][0]);
-#pragma unroll
-      for (int e = 2; e < 16; e += 2) tmax = max3(tmax, s[0][e], s[0][e + 1]);
-#pragma unroll
-      for (int e = 1; e < 15; e += 2) tmax = max3(tmax, s[1][e], s[1][e + 1]);
-      tmax = fmaxf(tmax, s[1][15]);
+      // max16 starts with the wait states an MFMA result needs before a vector instruction may read it
+      float tmax = max2(max16<true>(s[0]), max16<false>(s[1]));
       tmax = xor32_max(tmax) * P.scale_log2;
       // a row that sees nothing in this tile keeps its m; a row that has seen nothing yet in this
       // partition has m = -inf, l = 0 and all-zero accumulators
