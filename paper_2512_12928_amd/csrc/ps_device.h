@@ -13,13 +13,17 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define PS_NEG_INF (-__builtin_inff())
-// Online softmax with a lazy running maximum (prefill role): the accumulators are rescaled only when some row's
-// tile maximum exceeds the row's reference m by more than this many powers of two.  Until then m stays below the true
-// maximum, the probabilities of a row are at most 2^kRescaleSlack instead of at most 1, and the row sum and the
-// accumulators carry the same factor, which the final division (or the merge, which is handed this m) takes out:
-// the result is the same up to rounding, fp32 has the range, and bf16 has fp32's exponent.  Each rescale it saves is
-// 64 multiplications per lane that stand between the output MFMAs of one tile and those of the next.
+// Online softmax with a lazy reference maximum (prefill role).  Softmax does not care which reference m the exponentials
+// are taken against as long as the row sum and the accumulators use the same one: the final division (or the merge, which
+// is handed this m) takes the factor out, fp32 has the range, and bf16 has fp32's exponent.  So a wave takes the maximum
+// of a tile only when it has to: on its first tile, while some row has seen no key yet (m = -inf), and on a tile whose
+// row sums say that the reference has fallen too far behind (a row sum beyond PS_ROWSUM_LIMIT, or not a number: the tile
+// is then redone with its maximum taken, before anything of it has been accumulated).  When the maximum is taken, the
+// accumulators are rescaled only if some row's tile maximum exceeds its reference by more than PS_RESCALE_SLACK powers
+// of two.  In between, a row's probabilities are bounded by the limit instead of by 1, and a tile costs 8 three-way
+// maxima, a cross-lane exchange and (when a maximum grew) 64 multiplications per lane less.
 #define PS_RESCALE_SLACK 8.f
+#define PS_ROWSUM_LIMIT 0x1p40f
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   f32x2 v = {a, b};
@@ -69,22 +73,30 @@ __device__ __forceinline__ bf16x8 zero_from8(bf16x8 v, int first, int limit) {
   return __builtin_bit_cast(bf16x8, w);
 }
 
-// max over lanes l and l ^ 32 (both lanes get it), on the VALU: v_permlane32_swap exchanges the upper
-// half of its first operand with the lower half of its second.
-__device__ __forceinline__ float xor32_max(float x) {
-  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
-  asm volatile("" : "+v"(b));  // two distinct registers for the swap
-  auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
-  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+// max of two that are never NaN (fmaxf wraps NaN-quieting moves around its operands)
+__device__ __forceinline__ float max2(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
 }
 
-// max over lanes l and l ^ 16: v_permlane16_swap exchanges the odd rows (of 16 lanes) of its first
-// operand with the even rows of its second.
+// max over lanes l and l ^ 32 (both lanes get it), on the VALU: v_permlane32_swap exchanges the upper half of its
+// first operand with the lower half of its second, so with x in both, one register comes back holding the lower
+// half's values in both halves and the other the upper half's.  Written as asm with both registers as outputs: the
+// compiler's builtin hands back the first register for either element of its result here, which silently made this
+// the lower half's value instead of the maximum.  The swap needs two wait states behind a vector write of its operands.
+__device__ __forceinline__ float xor32_max(float x) {
+  float a = x, b = x;
+  asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return max2(a, b);
+}
+
+// max over lanes l and l ^ 16: v_permlane16_swap exchanges the odd rows (of 16 lanes) of its first operand with the
+// even rows of its second.
 __device__ __forceinline__ float xor16_max(float x) {
-  unsigned a = __builtin_bit_cast(unsigned, x), b = a;
-  asm volatile("" : "+v"(b));
-  auto r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
-  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+  float a = x, b = x;
+  asm("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return max2(a, b);
 }
 
 // s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding)
@@ -154,11 +166,4 @@ __device__ __forceinline__ float max16(const f32x16& s) {
           "v"(s[10]), "v"(s[11]), "v"(s[12]), "v"(s[13]), "v"(s[14]), "v"(s[15]));
   return r;
 }
-// max of two that are never NaN
-__device__ __forceinline__ float max2(float a, float b) {
-  float r;
-  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-  return r;
-}
-
 }  // namespace ps

@@ -141,8 +141,15 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
     const int qpos = p + q0 + j;
     // K row j of a score tile is token pi(j) of the ring tile: block j>>4, slot 8*bit2(j) + 4*bit3(j) + (j&3)
     const int kslot = 8 * ((j >> 2) & 1) + 4 * ((j >> 3) & 1) + (j & 3);
+    // byte offsets of this lane's first K fragment and of its V fragments inside a ring slot (the chunks follow at 512 B,
+    // the V fragments at 1 KiB): one addition per tile instead of the index arithmetic
+    uint32_t k_lane = (uint32_t)((j >> 4) * sizeof(uint4) * 256 + (h2 * 16 + kslot) * sizeof(uint4));
+    uint32_t v_lane = (uint32_t)(sizeof(uint4) * 512 + lane * sizeof(uint4));
+    asm("" : "+v"(k_lane), "+v"(v_lane));  // kept in a register each: left alone, the compiler rebuilds them from j and h2 every tile
+    static_assert(offsetof(FusedStage, v) == sizeof(uint4) * 512 && sizeof(FusedStage::k[0]) == sizeof(uint4) * 256, "ring slot layout");
 
     bool gave_up = false;
+    bool track = true;  // wave-uniform: the next tile's maximum is taken (see PS_RESCALE_SLACK)
     // The walk is handed over in pairs of tiles (64 tokens): one wait for the pair's flag ahead of its first tile, one
     // count behind the wave's last read of its second (or only) tile.
     for (int it = 0; it < ntiles; ++it) {
@@ -178,7 +185,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         // group 2c + h2; the 16 lanes of a quarter wave read 16 consecutive slots of one group: no bank conflict
         bf16x8 kf[8], vf[8];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) kf[c] = as_bf16x8(S.k[j >> 4][(2 * c + h2) * 16 + kslot]);
+        for (int c = 0; c < 8; ++c) kf[c] = as_bf16x8(*(const uint4*)((const char*)&S + k_lane + c * 512));
         __builtin_amdgcn_sched_barrier(0);
         f32x16 s;
 #pragma unroll
@@ -186,7 +193,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
 #pragma unroll
         for (int c = 0; c < 8; ++c) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[c], qop[c], s, 0, 0, 0);
 #pragma unroll
-        for (int f = 0; f < 4; ++f) vf[f] = as_bf16x8(S.v[f][lane]);
+        for (int f = 0; f < 4; ++f) vf[f] = as_bf16x8(*(const uint4*)((const char*)&S + v_lane + f * 1024));
         __builtin_amdgcn_sched_barrier(0);
         // s[e]: token ts + 16*(e/8) + 8*h2 + e%8, query q0 + j (raw dot products)
         if (ts + kFusedKV - 1 > p + q0) {  // diagonal tile (wave-uniform test)
@@ -196,15 +203,19 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
             if (tok > qpos) s[e] = PS_NEG_INF;
           }
         }
-        float tmax = max16<true>(s);  // starts with the wait states an MFMA result needs
-        tmax = xor32_max(tmax) * P.scale_log2;
-        if (__builtin_amdgcn_ballot_w64(tmax > m + PS_RESCALE_SLACK) != 0) {  // some row outgrew its reference
-          const float m_new = fmaxf(m, tmax);
-          const float alpha = m_new == PS_NEG_INF ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
-          l *= alpha;
-          m = m_new;
+        const bool tracked = track;
+        if (tracked) {
+          float tmax = max16<true>(s);  // starts with the wait states an MFMA result needs
+          tmax = xor32_max(tmax) * P.scale_log2;
+          if (__builtin_amdgcn_ballot_w64(tmax > m + PS_RESCALE_SLACK) != 0) {  // some row outgrew its reference
+            const float m_new = fmaxf(m, tmax);
+            const float alpha = m_new == PS_NEG_INF ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
+            l *= alpha;
+            m = m_new;
 #pragma unroll
-          for (int n = 0; n < 4; ++n) acc[n] *= alpha;
+            for (int n = 0; n < 4; ++n) acc[n] *= alpha;
+          }
+          track = __builtin_amdgcn_ballot_w64(m == PS_NEG_INF) != 0;  // rows that have seen nothing yet have no reference
         }
         const float m_use = m == PS_NEG_INF ? 0.f : m;  // all scores of such a row are -inf: exp2 gives 0
         float psum = 0.f;
@@ -212,6 +223,15 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         for (int e = 0; e < 16; ++e) {
           s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], P.scale_log2, -m_use));
           psum += s[e];
+        }
+        // Without the maximum nothing bounds the probabilities but the row sum itself: one beyond 2^40 (or infinite)
+        // says that a row's scores have left the range its reference covers, and the tile is done once more, this time
+        // with its maximum taken.  Nothing of the tile has gone into l or the accumulators yet, and the pair's count
+        // has not been touched; at the pair's first tile the flag is looked at again, which costs a read.
+        if (!tracked && __builtin_amdgcn_ballot_w64(!(psum <= PS_ROWSUM_LIMIT)) != 0) {
+          track = true;
+          --it;
+          continue;
         }
         l += psum;
         bf16x8 pop[2];
@@ -223,7 +243,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int f = 4; f < 8; ++f) vf[f] = as_bf16x8(S.v[f][lane]);
+        for (int f = 4; f < 8; ++f) vf[f] = as_bf16x8(*(const uint4*)((const char*)&S + v_lane + f * 1024));
         // the wave's last read of the tile is issued: LDS serves a wave's instructions in order, so the count
         // may follow at once
         asm volatile("" ::: "memory");

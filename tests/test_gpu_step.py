@@ -208,13 +208,14 @@ def test_very_long_contexts(split):
 
 
 @pytest.mark.parametrize("mixed_launch", [1, 2])
-@pytest.mark.parametrize("shape", ["rising", "falling", "steps"])
+@pytest.mark.parametrize("shape", ["rising", "falling", "steps", "leaps"])
 def test_row_maxima_that_drift_along_the_context(shape, mixed_launch):
     """Scores whose row maximum keeps moving along the KV walk: every request's queries and keys share a +-1
     direction, the keys with a gain that rises (0 to 2), falls (2 to 0) or jumps every 100 tokens, which moves
     the scaled score by up to 32 powers of two over the walk, by a fraction of one per tile on the long rows and
-    by several per tile on the short ones.  The online softmax has to follow that whatever its policy for
-    renewing the reference maximum (a kernel may let the reference lag behind by a bounded amount)."""
+    by several per tile on the short ones; "leaps" jumps between gains 0, 4 and 10, 65 to 163 powers of two at
+    once, more than fp32 holds.  The online softmax has to follow that whatever its policy for renewing the
+    reference maximum (a kernel may let the reference lag behind, and has to notice when it lags too far)."""
     items = [(1, 90), (1, 700), (1, 4000), (40, 140), (200, 900), (64, 64 + 3000), (33, 33)]
     b, t = custom_batch(8, 2, items, seed=77)
     rng = np.random.default_rng(78)
@@ -225,7 +226,8 @@ def test_row_maxima_that_drift_along_the_context(shape, mixed_launch):
         L = int(b.kv_len[r])
         pos = np.arange(L, dtype=np.float32) / max(L - 1, 1)
         gain = {"rising": 2 * pos, "falling": 2 - 2 * pos,
-                "steps": rng.choice(np.array([0.0, 0.5, 1.0, 2.0], dtype=np.float32), size=L // 100 + 1)[np.arange(L) // 100]}[shape]
+                "steps": rng.choice(np.array([0.0, 0.5, 1.0, 2.0], dtype=np.float32), size=L // 100 + 1)[np.arange(L) // 100],
+                "leaps": rng.choice(np.array([0.0, 4.0, 10.0], dtype=np.float32), size=L // 100 + 1)[np.arange(L) // 100]}[shape]
         t.k[r] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(t.k[r]) + gain[:, None, None] * u[None])
         a, e = int(b.q_start[r]), int(b.q_start[r + 1])
         q[a:e] += np.repeat(u, s.group, axis=0)[None]
