@@ -13,15 +13,18 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define PS_NEG_INF (-__builtin_inff())
-// Online softmax with a lazy reference maximum (prefill role).  Softmax does not care which reference m the exponentials
+// Online softmax with a lazy reference maximum (prefill work).  Softmax does not care which reference m the exponentials
 // are taken against as long as the row sum and the accumulators use the same one: the final division (or the merge, which
-// is handed this m) takes the factor out, fp32 has the range, and bf16 has fp32's exponent.  So a wave takes the maximum
-// of a tile only when it has to: on its first tile, while some row has seen no key yet (m = -inf), and on a tile whose
-// row sums say that the reference has fallen too far behind (a row sum beyond PS_ROWSUM_LIMIT, or not a number: the tile
-// is then redone with its maximum taken, before anything of it has been accumulated).  When the maximum is taken, the
-// accumulators are rescaled only if some row's tile maximum exceeds its reference by more than PS_RESCALE_SLACK powers
-// of two.  In between, a row's probabilities are bounded by the limit instead of by 1, and a tile costs 8 three-way
-// maxima, a cross-lane exchange and (when a maximum grew) 64 multiplications per lane less.
+// is handed this m) takes the factor out, fp32 has the range, and bf16 has fp32's exponent.  Two uses:
+//  * both prefill roles rescale the accumulators (64 multiplications per lane that stand between the output MFMAs of one
+//    tile and those of the next) only when some row's tile maximum exceeds its reference by more than PS_RESCALE_SLACK
+//    powers of two; until then a row's probabilities are at most 2^PS_RESCALE_SLACK instead of at most 1;
+//  * the MFMA waves of fused_kernel do not even take the maximum of a tile unless they have to: on their first tile,
+//    while some row has seen no key yet (m = -inf), and on a tile whose row sums say that the reference has fallen too
+//    far behind (a row sum beyond PS_ROWSUM_LIMIT, or not a number: the tile is then done once more with its maximum
+//    taken, before anything of it has been accumulated).  In between the probabilities are bounded by that limit, and
+//    a tile costs 8 three-way maxima and a cross-lane exchange less.  (In the prefill role of attention_kernel the same
+//    check, once per half tile, cost what the maxima had: it takes the maximum of every tile.)
 #define PS_RESCALE_SLACK 8.f
 #define PS_ROWSUM_LIMIT 0x1p40f
 
