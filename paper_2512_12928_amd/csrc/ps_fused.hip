@@ -132,6 +132,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
       for (int c = 0; c < 8; ++c) qop[c] = as_bf16x8(*(const uint4*)(qrow + (c * 2 + h2) * 8));
     }
     float m = PS_NEG_INF, l = 0.f;
+    float m_use = 0.f;  // what the exponentials subtract: m, or 0 while m = -inf; renewed where m is
     f32x16 acc[4];
 #pragma unroll
     for (int n = 0; n < 4; ++n)
@@ -216,8 +217,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
             for (int n = 0; n < 4; ++n) acc[n] *= alpha;
           }
           track = __builtin_amdgcn_ballot_w64(m == PS_NEG_INF) != 0;  // rows that have seen nothing yet have no reference
+          m_use = m == PS_NEG_INF ? 0.f : m;  // all scores of such a row are -inf: exp2 gives 0
         }
-        const float m_use = m == PS_NEG_INF ? 0.f : m;  // all scores of such a row are -inf: exp2 gives 0
         float psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
