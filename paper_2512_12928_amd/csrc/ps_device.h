@@ -24,7 +24,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 //    far behind (a row sum beyond PS_ROWSUM_LIMIT, or not a number: the tile is then done once more with its maximum
 //    taken, before anything of it has been accumulated).  In between the probabilities are bounded by that limit, and
 //    a tile costs 8 three-way maxima and a cross-lane exchange less.  (In the prefill role of attention_kernel the same
-//    check, once per half tile, cost what the maxima had: it takes the maximum of every tile.)
+//    check cost what the maxima had when made once per half tile, and more when made once per tile with all
+//    exponentials ahead of the output MFMAs: that role takes the maximum of every tile.)
 #define PS_RESCALE_SLACK 8.f
 #define PS_ROWSUM_LIMIT 0x1p40f
 
