@@ -112,8 +112,8 @@ typedef struct {
                               waves that fetch the walk's tiles and two that walk decode slots; needs
                               decode_chunk and decode_waves 0, else as 1).  0 (default): the library picks:
                               2 when neither kind of work dwarfs the other (the prefill work priced at 0.65
-                              to 4.5 times the decode work) and there are at least two prefill workgroups
-                              per compute unit (measured 3 to 15 % faster on such launches, the same or
+                              to 8 times the decode work) and there are at least two prefill workgroups
+                              per compute unit (measured 2 to 14 % faster on such launches, the same or
                               slower outside that range), else 1.                                     */
 } ps_layer_cfg;
 

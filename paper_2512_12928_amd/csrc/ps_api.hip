@@ -866,10 +866,10 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
     int waves = c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus;
     // Every workgroup carries both kinds of work (two decode slots per prefill work item and z-split).  Forced by
     // cfg.mixed_launch = 2; picked by the library when neither kind of work dwarfs the other (the prefill work priced
-    // at 0.65 to 4.5 times the decode work) and there are at least two prefill workgroups per compute unit.  Measured on
-    // an MI355X against disjoint units, by that ratio: 10, 4 % slower; 5.6, 1 % slower; 3.2, -2.6 %; 1.8, -10 %;
-    // 1.2, -15 %; 0.9, -10 %; 0.58 and 0.44, 1 to 2 % slower; 0.29, 7 % slower; with fewer prefill workgroups 0.92,
-    // -10 %; 0.43, 6 % slower.
+    // at 0.65 to 8 times the decode work) and there are at least two prefill workgroups per compute unit.  Measured on
+    // an MI355X against disjoint units, by that ratio: 10, the same; 7.2, -2 %; 5.8, -3 %; 4.2, -5 %; 3.3, -6 %; 1.8, -11 %;
+    // 1.2, -14 %; 0.9, -10 %; 0.7, -4 %; 0.59 and 0.43, 2 % slower; 0.28, 8 % slower; with fewer prefill workgroups
+    // 0.91, -9 %; 0.43, 6 % slower; 0.13, 9 % slower.
     const bool fusable = c->cfg.decode_waves == 0 && c->cfg.decode_chunk == 0 && c->profiling != 2 && !decode_reqs.empty() &&
                          !tiles.empty() && ps::fused_supports(c->G) &&
                          (int64_t)ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads <= INT32_MAX;
@@ -879,7 +879,7 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
       const double t_d = (double)decode_kv * (double)(c->block_bytes / ps::kBlockTokens) / (tune.stream_TBps * 1e6);  // us
       const double t_p = prefill_steps * tune.tile_step_us;
       const int64_t wgs = (int64_t)tiles.size() * c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
-      c->plan_fused = t_p >= 0.65 * t_d && t_p <= 4.5 * t_d && wgs >= 2 * (int64_t)c->n_cus;
+      c->plan_fused = t_p >= 0.65 * t_d && t_p <= 8.0 * t_d && wgs >= 2 * (int64_t)c->n_cus;
     }
     if (c->plan_fused) {
       waves = ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads;

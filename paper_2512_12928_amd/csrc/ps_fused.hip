@@ -26,8 +26,8 @@
 // Nobody waits at a barrier after the start: MFMA waves wait only for `ready`, feeders only for memory
 // and for `consumed`, decode waves only for memory; pair p's `ready` needs `consumed` of pair p - 4 only,
 // which needs `ready` of p - 4: every wait is for something earlier in that order, so the walk drains.
-// What it buys (MI355X), against the two kinds of work on disjoint compute units: 3 to 15 % off a launch in
-// which neither kind dwarfs the other (the prefill work 0.65 to 4.5 times the decode work); outside that
+// What it buys (MI355X), against the two kinds of work on disjoint compute units: 2 to 14 % off a launch in
+// which neither kind dwarfs the other (the prefill work 0.65 to 8 times the decode work); outside that
 // range the two layouts take the same time or this one more.  It stops there because every load on a
 // unit, hit or miss, returns at the pace of the misses in front of it, and because a load issued next to
 // MFMA waves costs its wave some 90 cycles (160 with a 64-bit address per lane).
