@@ -11,7 +11,7 @@ from paper_2512_12928_amd import binding as B
 from paper_2512_12928_amd import workloads as W
 from gpu_harness import DEV, Layer, check_close, dev_to_u16, oracle_cache, run_prefilled, u16_to_dev
 from paper_2512_12928_amd.kvlayout import from_device_layout, to_device_layout
-from test_gpu_step import custom_batch, oracle_out
+from test_gpu_step import custom_batch, drifting_batch, oracle_out
 
 pytestmark = pytest.mark.gpu
 KW = dict(mixed_launch=2)
@@ -41,6 +41,17 @@ def test_prefill_kv_partitions(split):
     items = [(1, 40), (64, 64), (200, 200), (70, 70 + 333), (129, 129 + 1000), (5, 700), (33, 33 + 64), (1, 900)]
     check(*custom_batch(8, 2, items, seed=21), prefill_split_tiles=split)
     check(*custom_batch(16, 2, items[:5], seed=22), prefill_split_tiles=split)
+
+
+@pytest.mark.parametrize("split", [1, 3, -1])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (16, 1), (64, 8)])
+def test_leaping_row_maxima_with_partitions(Hq, Hkv, split):
+    """Scores that leap by 65 to 163 powers of two along the walk (more than fp32 holds against a reference that lags),
+    with the prefill rows' KV ranges cut into partitions or not, for several group sizes: the MFMA waves take a tile's
+    maximum only when their row sums tell them to, and the partials they hand to the merge carry whatever reference
+    they ended with."""
+    b, t = drifting_batch("leaps", Hq, Hkv, seed=90 + Hq)
+    check(b, t, prefill_split_tiles=split)
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(1, 1), (2, 1), (4, 1), (8, 1), (16, 1), (6, 2), (12, 4), (64, 8)])

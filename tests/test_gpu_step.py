@@ -216,9 +216,16 @@ def test_row_maxima_that_drift_along_the_context(shape, mixed_launch):
     by several per tile on the short ones; "leaps" jumps between gains 0, 4 and 10, 65 to 163 powers of two at
     once, more than fp32 holds.  The online softmax has to follow that whatever its policy for renewing the
     reference maximum (a kernel may let the reference lag behind, and has to notice when it lags too far)."""
+    b, t = drifting_batch(shape)
+    got, cache = run_prefilled(b, t, mixed_launch=mixed_launch)
+    check_close(got, oracle_out(b, t, cache), False)
+
+
+def drifting_batch(shape, Hq=8, Hkv=2, seed=77):
+    """The batch of the test above: N(0,1) tensors with a shared +-1 direction in queries and keys (draws only)."""
     items = [(1, 90), (1, 700), (1, 4000), (40, 140), (200, 900), (64, 64 + 3000), (33, 33)]
-    b, t = custom_batch(8, 2, items, seed=77)
-    rng = np.random.default_rng(78)
+    b, t = custom_batch(Hq, Hkv, items, seed=seed)
+    rng = np.random.default_rng(seed + 1)
     s = b.shape
     q = W.bf16_bits_to_f32(t.q)
     for r in range(b.n_req):
@@ -232,8 +239,7 @@ def test_row_maxima_that_drift_along_the_context(shape, mixed_launch):
         a, e = int(b.q_start[r]), int(b.q_start[r + 1])
         q[a:e] += np.repeat(u, s.group, axis=0)[None]
     t.q = W.f32_to_bf16_bits(q)
-    got, cache = run_prefilled(b, t, mixed_launch=mixed_launch)
-    check_close(got, oracle_out(b, t, cache), False)
+    return b, t
 
 
 def test_block_relabelling_is_bit_identical():
