@@ -190,6 +190,11 @@ double mixed_makespan(const std::vector<TileKey>& tiles, int per_tile, int n_cus
   return end;
 }
 
+// Partial slots a batch of n_tokens may spend on prefill rows whose KV range is split: two per batch token, and 8192 on
+// top for small batches (a lone chunk over a long prefix is a handful of workgroups that walk the whole prefix each
+// unless every one of its query tiles can be cut), never more than the 8 partitions per row the split makes.
+static int64_t prefill_partial_budget(int64_t n_tokens) { return std::min<int64_t>(8 * n_tokens, 2 * n_tokens + 8192); }
+
 double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, int TT, size_t workspace_bytes, int& n_parts) {
   double prefill_steps = 0;
   const PlanTuning tune = tuning_of(c->cfg);
@@ -248,9 +253,10 @@ double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, i
       priced = true;
     }
   }
-  // partial slots: budget of two per batch token, and whatever the caller's workspace holds
+  // partial slots: the budget above, and whatever the caller's workspace holds; the longest walks are served first
   const size_t slot_bytes = (size_t)c->cfg.n_q_heads * ps::kPartStride * sizeof(float);
-  int64_t budget = std::min<int64_t>(2 * (int64_t)b->n_tokens, (int64_t)(workspace_bytes / slot_bytes) - n_parts);
+  int64_t budget = std::min<int64_t>(prefill_partial_budget(b->n_tokens), (int64_t)(workspace_bytes / slot_bytes) - n_parts);
+  if (split > 0) std::stable_sort(tiles.begin(), tiles.end(), [](const TileKey& x, const TileKey& y) { return x.reach > y.reach; });
   std::vector<TileKey> cut;
   for (auto& t : tiles) {
     const int qs = b->q_start[t.t.req], lq = b->q_start[t.t.req + 1] - qs;
@@ -686,8 +692,8 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
   const size_t max_parts = (size_t)max_req + (c->cfg.decode_chunk > 0
                                                  ? (size_t)(max_table_entries * ps::kBlockTokens / c->cfg.decode_chunk)
                                                  : std::min(slots_by_tiles, slots_by_waves));
-  // + up to two partial slots per batch token for prefill rows whose KV range is split
-  *out_bytes = align_up((max_parts + 2 * (size_t)max_tokens) * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256) + 256;
+  // + the partial slots of prefill rows whose KV range is split
+  *out_bytes = align_up((max_parts + (size_t)prefill_partial_budget(max_tokens)) * c->cfg.n_q_heads * ps::kPartStride * sizeof(float), 256) + 256;
   return PS_OK;
 }
 

@@ -150,6 +150,8 @@ def measure(batches: Sequence[W.MixedBatch], shape: W.LayerShape, n_blocks: int,
 
 
 def main(argv=None) -> int:
+    """python -m paper_2512_12928_amd.estimator [n_batches [file]]: the fit; with a file name the batches and their
+    measured times are also written there (JSON) for fitting other forms without a GPU."""
     n = int(argv[0]) if argv else 240
     shape = W.LayerShape(32, 8)
     n_blocks = 60_000
@@ -157,6 +159,10 @@ def main(argv=None) -> int:
     y = measure(batches, shape, n_blocks)
     X = np.stack([features(b.q_start, b.kv_len) for b in batches])
     walk = np.array([longest_walk(b.q_start, b.kv_len) for b in batches])
+    if argv and len(argv) > 1:
+        with open(argv[1], "w") as f:
+            json.dump([dict(l_q=np.diff(b.q_start).tolist(), kv_len=np.asarray(b.kv_len).tolist(), us=float(t))
+                       for b, t in zip(batches, y)], f)
     half = n // 2
     coef = fit(X[:half], y[:half])
     coef_m, w = fit_with_critical_path(X[:half], walk[:half], y[:half])
