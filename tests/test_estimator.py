@@ -58,3 +58,22 @@ def test_critical_path_form_recovers_a_planted_max():
     assert E.longest_walk(b.q_start, b.kv_len) == 17                    # ceil(1064 / 64)
     b = W.build_batch(W.LayerShape(32, 8), [(1, 100)], [1], np.random.default_rng(0), seed=0)
     assert E.longest_walk(b.q_start, b.kv_len) == 0
+
+
+def test_overlap_form_recovers_planted_parameters():
+    """T = t_c + max(P, D) + kappa * min(P, D) with P = max(prefill terms, w * longest walk): planted coefficients,
+    kappa and w come back from the fit (to the grid's step), kappa = 1 and w = 0 reproduce Eq. 7, and the additive form
+    alone cannot explain data that overlaps."""
+    batches = E.profiling_batches(160, 13, W.LayerShape(32, 8), 60_000)
+    X = np.stack([E.features(b.q_start, b.kv_len) for b in batches])
+    walk = np.array([E.longest_walk(b.q_start, b.kv_len) for b in batches])
+    planted = np.array([3e-6, 2e-5, 1.2e-2, 5.5e-4, 0.02, 24.0])
+    assert np.allclose(E.predict_overlap(planted, 1.0, 0.0, X, walk), X @ planted, rtol=1e-12)
+    y = E.predict_overlap(planted, 0.6, 0.5, X, walk)
+    both = (X[:, 2] > 0) & (X[:, 4] > 0)
+    assert both.sum() > 40 and (0.5 * walk > X[:, :3] @ planted[:3]).sum() > 5   # overlap and critical path both bind
+    coef, kappa, w = E.fit_with_overlap(X, walk, y)
+    err = np.abs(E.predict_overlap(coef, kappa, w, X, walk) - y) / y
+    assert abs(kappa - 0.6) <= 0.05 and abs(w - 0.5) <= 0.1 and err.mean() < 0.01
+    assert np.allclose(coef[3:], planted[3:], rtol=0.05)
+    assert E.mape(E.fit(X, y), X, y) > 3 * err.mean()
