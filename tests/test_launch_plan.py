@@ -52,10 +52,10 @@ def test_shares_of_the_benchmark_workloads():
 
 def test_which_mixed_batches_get_workgroups_that_carry_both_kinds_of_work():
     """Left to the library (mixed_launch = 0), a launch in which neither kind of work dwarfs the other and which has at
-    least two prefill workgroups per compute unit is laid out that way (workloads 4 and 5: the prefill work priced at 2.6
-    and 1.9 times the decode work; not workload 2, a quarter of a prefill workgroup per unit and mostly decode work, nor
-    workload 5 with an eighth of its decode requests); forced (2), any mixed batch is, and every prefill workgroup then
-    walks at most two decode slots of its kv-head."""
+    least one prefill workgroup per compute unit is laid out that way (workloads 4 and 5: the prefill work priced at 2.6
+    and 1.9 times the decode work; not workload 2, mostly decode work, nor workload 5 with an eighth of its decode
+    requests); with short KV walks the prefill work has to be the larger of the two; forced (2), any mixed batch is,
+    and every prefill workgroup then walks at most two decode slots of its kv-head."""
     p2, p4, p5 = (plan(W.make_workload(i)) for i in (2, 4, 5))
     assert p2["decode_workgroups"] > 0 and p2 == plan(W.make_workload(2), mixed_launch=1)
     assert p4["decode_workgroups"] == 0 and p4["prefill_workgroups"] == 512 and p4 == plan(W.make_workload(4), mixed_launch=2)
@@ -64,6 +64,15 @@ def test_which_mixed_batches_get_workgroups_that_carry_both_kinds_of_work():
     few = [(1, int(b5.kv_len[r])) for r in b5.decode_reqs[:64]] + [(b5.l_q(int(r)), int(b5.kv_len[r])) for r in b5.prefill_reqs]
     bf = W.build_batch(b5.shape, few, [1] * len(few), np.random.default_rng(3), seed=3)
     assert plan(bf)["decode_workgroups"] > 0 and plan(bf, mixed_launch=2)["decode_workgroups"] == 0
+    # one chunk next to 192 decode requests of 857 tokens, 256 prefill workgroups: long walks and twice the decode work
+    # -> both in every workgroup; short walks and half the decode work -> disjoint units; a ratio of 0.8: by walk length
+    def small(pre, n_dec):
+        items = [(1, 857)] * n_dec + pre
+        return plan(W.build_batch(W.LayerShape(32, 8), items, [1] * len(items), np.random.default_rng(5), n_device_blocks=60_000, seed=5))
+    assert small([(2048, 2048 + 4096)], 192)["decode_workgroups"] == 0 and small([(2048, 2048 + 4096)], 192)["prefill_workgroups"] == 256
+    assert small([(1024, 1024 + 2048)], 192)["decode_workgroups"] > 0
+    assert small([(2048, 2048 + 4096)], 384)["decode_workgroups"] == 0        # a ratio of 0.9, walks of 96 tiles on average
+    assert small([(4096, 4096)], 384)["decode_workgroups"] > 0                # 0.7, walks of 32 tiles on average
     for i in (2, 4, 5):
         b = W.make_workload(i)
         p = plan(b, mixed_launch=2)
