@@ -190,10 +190,14 @@ double mixed_makespan(const std::vector<TileKey>& tiles, int per_tile, int n_cus
   return end;
 }
 
+// A prefill row's KV range is cut into at most this many partitions.
+constexpr int kMaxPrefillParts = 32;
 // Partial slots a batch of n_tokens may spend on prefill rows whose KV range is split: two per batch token, and 8192 on
 // top for small batches (a lone chunk over a long prefix is a handful of workgroups that walk the whole prefix each
-// unless every one of its query tiles can be cut), never more than the 8 partitions per row the split makes.
-static int64_t prefill_partial_budget(int64_t n_tokens) { return std::min<int64_t>(8 * n_tokens, 2 * n_tokens + 8192); }
+// unless every one of its query tiles can be cut), never more than the split can use.
+static int64_t prefill_partial_budget(int64_t n_tokens) {
+  return std::min<int64_t>((int64_t)kMaxPrefillParts * n_tokens, 2 * n_tokens + 8192);
+}
 
 double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, int TT, size_t workspace_bytes, int& n_parts) {
   double prefill_steps = 0;
@@ -211,20 +215,20 @@ double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, i
   if (c->cfg.prefill_split_tiles > 0) {
     split = c->cfg.prefill_split_tiles;
   } else if (c->cfg.prefill_split_tiles == 0 && !tiles.empty()) {
-    // Candidates: the longest walk cut into k = 1..8 equal parts.  Each is priced in units of one
+    // Candidates: the longest walk cut into k = 1..8, 12, 16, 24 or 32 equal parts.  Each is priced in units of one
     // KV tile step of a workgroup (measured on workload-sized launches): the time the launch
     // ends when workgroups are handed, longest first, to whichever CU is free next, plus the merge
     // (a kernel launch worth 4 steps, and 0.0047 steps per partial row of 32 heads).  Launches of
     // more than 1024 workgroups balance well enough without a cut and are not priced.
     std::vector<int64_t> sizes, bins;
     double best = 0;
-    for (int k = 1; k <= 8; ++k) {
+    for (int k : {1, 2, 3, 4, 5, 6, 7, 8, 12, 16, 24, 32}) {
       const int64_t cand = (longest + k - 1) / k;
       if (k > 1 && cand < 8) break;
       sizes.clear();
       int64_t rows = 0;
       for (auto& t : tiles) {
-        int np = k == 1 ? 1 : (int)std::min<int64_t>((t.reach + cand - 1) / cand, 8);
+        int np = k == 1 ? 1 : (int)std::min<int64_t>((t.reach + cand - 1) / cand, kMaxPrefillParts);
         const int64_t len = (t.reach + np - 1) / np;
         np = (int)((t.reach + len - 1) / len);
         for (int q = 0; q < np; ++q) sizes.push_back(std::min<int64_t>((int64_t)(q + 1) * len, t.reach) - q * len);
@@ -261,7 +265,7 @@ double plan_prefill(ps_ctx* c, const ps_batch* b, std::vector<TileKey>& tiles, i
   for (auto& t : tiles) {
     const int qs = b->q_start[t.t.req], lq = b->q_start[t.t.req + 1] - qs;
     const int rows = std::min(TT, lq - t.t.q0);
-    int np = split > 0 ? (int)std::min<int64_t>((t.reach + split - 1) / split, 8) : 1;
+    int np = split > 0 ? (int)std::min<int64_t>((t.reach + split - 1) / split, kMaxPrefillParts) : 1;
     if (np > 1 && (int64_t)rows * np > budget) np = 1;
     if (np == 1) {
       t.t.tile_end = (int32_t)t.reach;
@@ -686,9 +690,9 @@ int ps_workspace_bytes(const ps_ctx* c, int32_t max_req, int32_t max_tokens, int
   const size_t slots_by_tiles = (size_t)((max_table_entries + max_req) / (2 * kMinSlotTiles)) + 1;
   size_t slots_by_waves =
       (size_t)((c->cfg.decode_waves > 0 ? c->cfg.decode_waves : ps::decode_waves_per_wg() * c->n_cus) / c->cfg.n_kv_heads) + 1;
-  if (c->cfg.mixed_launch != 1)  // the layout with two decode slots per prefill work item (a query tile, or one of its at most 8 partitions) may be picked
-    slots_by_waves = std::max(slots_by_waves,
-                              (size_t)ps::fused_decode_slots(1, c->G) * 8 * ((size_t)max_tokens / ps::prefill_tile_tokens(c->G) + (size_t)max_req) + 1);
+  if (c->cfg.mixed_launch != 1)  // the layout with two decode slots per prefill work item (a query tile, or one of its partitions) may be picked
+    slots_by_waves = std::max(slots_by_waves, (size_t)ps::fused_decode_slots(1, c->G) * kMaxPrefillParts *
+                                                  ((size_t)max_tokens / ps::prefill_tile_tokens(c->G) + (size_t)max_req) + 1);
   const size_t max_parts = (size_t)max_req + (c->cfg.decode_chunk > 0
                                                  ? (size_t)(max_table_entries * ps::kBlockTokens / c->cfg.decode_chunk)
                                                  : std::min(slots_by_tiles, slots_by_waves));

@@ -242,6 +242,18 @@ def drifting_batch(shape, Hq=8, Hkv=2, seed=77):
     return b, t
 
 
+@pytest.mark.parametrize("mixed_launch", [1, 2])
+def test_lone_chunk_over_a_long_prefix_is_cut_into_many_partitions(mixed_launch):
+    """A 40-token chunk over 20 000 cached tokens (a walk of 314 KV tiles) with a few decode requests: left alone the
+    planner cuts every query tile's walk into more than eight partitions (the merge then folds a row's partials eight
+    at a time), in either layout of the mixed launch."""
+    b, t = custom_batch(8, 2, [(1, 300), (40, 40 + 20_000), (1, 5000), (1, 17)], seed=55)
+    p = B.ps_plan_launch(8, 2, b.n_device_blocks, b, mixed_launch=mixed_launch)
+    assert 0 < p["prefill_split_tiles"] < 314 // 8          # more than eight partitions of the 314-tile walk
+    got, cache = run_prefilled(b, t, mixed_launch=mixed_launch)
+    check_close(got, oracle_out(b, t, cache), False)
+
+
 def test_block_relabelling_is_bit_identical():
     b = W.make_workload(1)
     t = W.make_tensors(b)
