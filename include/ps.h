@@ -112,8 +112,8 @@ typedef struct {
                               waves that fetch the walk's tiles and two that walk decode slots; needs
                               decode_chunk and decode_waves 0, else as 1).  0 (default): the library picks:
                               2 when neither kind of work dwarfs the other (the prefill work priced at 0.65
-                              to 8 times the decode work; at 1 to 8 times it when the prefill workgroups'
-                              KV walks are short) and there is at least one prefill workgroup per compute
+                              to 8 times the decode work; at 1 or 1.6 to 8 times it when the prefill
+                              workgroups' KV walks are short) and there is at least one prefill workgroup per compute
                               unit (measured 2 to 20 % faster on such launches, the same or slower
                               outside that range), else 1.                                            */
 } ps_layer_cfg;

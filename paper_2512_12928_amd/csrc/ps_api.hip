@@ -877,12 +877,14 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
     // Every workgroup carries both kinds of work (two decode slots per prefill work item and z-split).  Forced by
     // cfg.mixed_launch = 2; picked by the library when neither kind of work dwarfs the other and there is at least one
     // prefill workgroup per compute unit: the prefill work priced at no more than 8 times the decode work, and at no less
-    // than 0.65 times it when the walks are long (64 KV tiles or more per workgroup on average), no less than it otherwise.
+    // than 0.65 times it when the walks are long (64 KV tiles or more per workgroup on average), no less than it when they
+    // are of 32 tiles or more, no less than 1.6 times it when they are shorter.
     // Measured on an MI355X against disjoint units, by that ratio.  Launches of 2048 workgroups with walks of 72 tiles
     // on average: 10, the same; 7.2, -2 %; 5.8, -3 %; 4.2, -5 %; 3.3, -6 %; 1.8, -11 %; 1.2, -14 %; 0.9, -10 %; 0.7, -4 %;
     // 0.59 and 0.43, 2 % slower; 0.28, 8 % slower.  Launches of 256 to 512 workgroups: long walks 2.9, -5 %; 1.7, -16 %;
     // 1.3, -18 %; 0.93, -9 %; 0.73, -10 %; walks of 24 to 34 tiles 1.4, -4 to -21 %; 1.1, 2 % slower; 0.85, 6 % slower;
-    // 0.79, -9 %; 0.71, 3 % slower; 0.64, 14 % slower; 0.43, 3 to 21 % slower.
+    // 0.79, -9 %; 0.71, 3 % slower; 0.64, 14 % slower; 0.43, 3 to 21 % slower; walks of 12 to 20 tiles 1.9, -10 %;
+    // 1.8, -12 %; 1.3, 19 % slower; 1.15, 16 to 26 % slower.
     const bool fusable = c->cfg.decode_waves == 0 && c->cfg.decode_chunk == 0 && c->profiling != 2 && !decode_reqs.empty() &&
                          !tiles.empty() && ps::fused_supports(c->G) &&
                          (int64_t)ps::fused_decode_slots((int)tiles.size(), c->G) * c->cfg.n_kv_heads <= INT32_MAX;
@@ -894,7 +896,7 @@ static int plan_batch(ps_ctx* c, const ps_batch* b, bool has_new_kv, size_t work
       const int64_t wgs = (int64_t)tiles.size() * c->cfg.n_kv_heads * (c->G / ps::prefill_heads_per_wg(c->G));
       int64_t walk_sum = 0;
       for (auto& t : tiles) walk_sum += t.reach;
-      const double lo = walk_sum >= 64 * (int64_t)tiles.size() ? 0.65 : 1.0;
+      const double lo = walk_sum >= 64 * (int64_t)tiles.size() ? 0.65 : walk_sum >= 32 * (int64_t)tiles.size() ? 1.0 : 1.6;
       c->plan_fused = t_p >= lo * t_d && t_p <= 8.0 * t_d && wgs >= (int64_t)c->n_cus;
     }
     if (c->plan_fused) {
