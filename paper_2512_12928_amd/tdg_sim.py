@@ -25,7 +25,7 @@ def default_cfg(n_layers: int = 36, **kw) -> Dict:
     values are the fit of profiles/estimator_fit_mi355x.md rounded to integer picoseconds."""
     L = n_layers
     d = dict(n_classes=3, block_tokens=16, class_weight=[4, 2, 1], w_first=4, w_decode=1, ttft_slo_ps=2000 * MS,
-             tpot_slo_ps=100 * MS, a_p=2 * L, b_p=16 * L, c_p=10793 * L, a_d=557 * L, b_d=15951 * L, t_c=25740 * NS * L,
+             tpot_slo_ps=100 * MS, a_p=2 * L, b_p=15 * L, c_p=10279 * L, a_d=558 * L, b_d=10200 * L, t_c=26670 * NS * L,
              eta_ps=10 * MS, tau_ps=30_000 * MS, gamma_num=9, gamma_den=10, beta_num=2, beta_den=1, rho_num=9,
              rho_den=10, t_block_ps=1200 * NS * L, n_off_base=8)
     d.update(kw)
