@@ -77,6 +77,20 @@ __device__ __forceinline__ bf16x8 zero_from8(bf16x8 v, int first, int limit) {
   return __builtin_bit_cast(bf16x8, w);
 }
 
+// Sum of the 16 bf16 values in eight registers (each a pair), as fp32: four independent chains of v_dot2c_f32_bf16
+// against a pair of ones, then three additions.  The block ends with the wait states the ISA asks for before another
+// kind of vector instruction reads a dot product's result.
+__device__ __forceinline__ float sum_bf16x16(const uint4& a, const uint4& b) {
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  const uint32_t ones = 0x3F803F80u;
+  asm("v_dot2c_f32_bf16 %0, %4, %12\n\tv_dot2c_f32_bf16 %1, %5, %12\n\tv_dot2c_f32_bf16 %2, %6, %12\n\tv_dot2c_f32_bf16 %3, %7, %12\n\t"
+      "v_dot2c_f32_bf16 %0, %8, %12\n\tv_dot2c_f32_bf16 %1, %9, %12\n\tv_dot2c_f32_bf16 %2, %10, %12\n\tv_dot2c_f32_bf16 %3, %11, %12\n\t"
+      "s_nop 2"
+      : "+v"(s0), "+v"(s1), "+v"(s2), "+v"(s3)
+      : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "v"(b.x), "v"(b.y), "v"(b.z), "v"(b.w), "v"(ones));
+  return (s0 + s1) + (s2 + s3);
+}
+
 // max of two that are never NaN (fmaxf wraps NaN-quieting moves around its operands)
 __device__ __forceinline__ float max2(float a, float b) {
   float r;

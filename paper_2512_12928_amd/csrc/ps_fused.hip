@@ -219,12 +219,14 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
           track = __builtin_amdgcn_ballot_w64(m == PS_NEG_INF) != 0;  // rows that have seen nothing yet have no reference
           m_use = m == PS_NEG_INF ? 0.f : m;  // all scores of such a row are -inf: exp2 gives 0
         }
-        float psum = 0.f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], P.scale_log2, -m_use));
-          psum += s[e];
-        }
+        for (int e = 0; e < 16; ++e) s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], P.scale_log2, -m_use));
+        uint4 pv[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          pv[u] = make_uint4(pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
+                             pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7]));
+        const float psum = sum_bf16x16(pv[0], pv[1]);  // of the rounded probabilities: what the output MFMAs multiply by
         // Without the maximum nothing bounds the probabilities but the row sum itself: one beyond 2^40 (or infinite)
         // says that a row's scores have left the range its reference covers, and the tile is done once more, this time
         // with its maximum taken.  Nothing of the tile has gone into l or the accumulators yet, and the pair's count
@@ -237,11 +239,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         l += psum;
         bf16x8 pop[2];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          uint4 pv = {pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
-                      pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7])};
-          pop[u] = as_bf16x8(pv);
-        }
+        for (int u = 0; u < 2; ++u) pop[u] = as_bf16x8(pv[u]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int f = 4; f < 8; ++f) vf[f] = as_bf16x8(*(const uint4*)((const char*)&S + v_lane + f * 1024));

@@ -593,18 +593,19 @@ __device__ __forceinline__ void prefill_role(const StepParams& P, int bid, int H
       const float m_use = m == PS_NEG_INF ? 0.f : m;  // all scores of such a row are -inf: exp2 gives 0
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
-        float psum = 0.f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          s[hf][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[hf][e], P.scale_log2, -m_use));
-          psum += s[hf][e];
-        }
-        l += psum;
+        for (int e = 0; e < 16; ++e) s[hf][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[hf][e], P.scale_log2, -m_use));
+        uint4 pv[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          pv[u] = make_uint4(pack_bf16x2(s[hf][8 * u + 0], s[hf][8 * u + 1]), pack_bf16x2(s[hf][8 * u + 2], s[hf][8 * u + 3]),
+                             pack_bf16x2(s[hf][8 * u + 4], s[hf][8 * u + 5]), pack_bf16x2(s[hf][8 * u + 6], s[hf][8 * u + 7]));
+        // the row sum is that of the rounded probabilities, the ones the output MFMAs multiply by: numerator and
+        // denominator then carry the same rounding, and a row that one key dominates comes out as that key's value
+        l += sum_bf16x16(pv[0], pv[1]);
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-          uint4 pv = {pack_bf16x2(s[hf][8 * u + 0], s[hf][8 * u + 1]), pack_bf16x2(s[hf][8 * u + 2], s[hf][8 * u + 3]),
-                      pack_bf16x2(s[hf][8 * u + 4], s[hf][8 * u + 5]), pack_bf16x2(s[hf][8 * u + 6], s[hf][8 * u + 7])};
-          const bf16x8 pop = as_bf16x8(pv);
+          const bf16x8 pop = as_bf16x8(pv[u]);
 #pragma unroll
           for (int n = 0; n < 4; ++n)
             acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[hf][u * 4 + n], pop, acc[n], 0, 0, 0);

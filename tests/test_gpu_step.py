@@ -254,6 +254,42 @@ def test_lone_chunk_over_a_long_prefix_is_cut_into_many_partitions(mixed_launch)
     check_close(got, oracle_out(b, t, cache), False)
 
 
+@pytest.mark.parametrize("mixed_launch", [1, 2])
+def test_rows_that_one_key_dominates(mixed_launch):
+    """Two planted keys per request in the prefix (queries and planted keys share a +-1 direction): the first stands
+    20 powers of two above the other keys, the second, later in the context, 7 more, so every row is the second key's
+    value row but for 0.6 % of the first's.  The kernels round the probabilities to bf16 for the output product, and a
+    kernel whose reference for the exponentials is not the row's true maximum (it may lag by a few powers of two)
+    gives the dominant key a probability with an arbitrary 8-bit significand instead of 1: unless the row sum carries
+    the same rounding, the output is off by up to 2^-8 of a value of 3.5, more than the 1e-2 bound allows.  Asserted to
+    5e-3 (score noise leaves some rows a mixture of the two planted values, where the roundings of two probabilities
+    show)."""
+    items = [(1, 700), (1, 4000), (1, 300), (40, 40 + 1000), (200, 200 + 700), (64, 64 + 3000)]
+    b, t = custom_batch(8, 2, items, seed=91)
+    rng = np.random.default_rng(92)
+    s = b.shape
+    q = W.bf16_bits_to_f32(t.q)
+    pm = np.array([-1.0, 1.0], dtype=np.float32)
+    for r in range(b.n_req):
+        u = rng.choice(pm, size=(s.n_kv_heads, s.head_dim))
+        prefix = int(b.kv_len[r]) - b.l_q(r)
+        first = int(rng.integers(40, prefix // 2))
+        second = int(rng.integers(first + 70, prefix))       # a few tiles on, inside the prefix: every row sees both
+        k = W.bf16_bits_to_f32(t.k[r])
+        k[first] += 1.2 * u
+        k[second] += 1.65 * u
+        t.k[r] = W.f32_to_bf16_bits(k)
+        for pos in (first, second):
+            t.v[r][pos] = W.f32_to_bf16_bits(np.float32(3.5) * rng.choice(pm, size=(s.n_kv_heads, s.head_dim)))
+        a, e = int(b.q_start[r]), int(b.q_start[r + 1])
+        q[a:e] += np.repeat(u, s.group, axis=0)[None]
+    t.q = W.f32_to_bf16_bits(q)
+    got, cache = run_prefilled(b, t, mixed_launch=mixed_launch)
+    want = oracle_out(b, t, cache)
+    assert np.median(np.abs(want)) > 3.3                     # the rows are what was planted
+    check_close(got, want, False, tol=5e-3)
+
+
 def test_block_relabelling_is_bit_identical():
     b = W.make_workload(1)
     t = W.make_tensors(b)
