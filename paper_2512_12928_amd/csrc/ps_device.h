@@ -91,6 +91,17 @@ __device__ __forceinline__ float sum_bf16x16(const uint4& a, const uint4& b) {
   return (s0 + s1) + (s2 + s3);
 }
 
+// The same for the 8 bf16 values in four registers.
+__device__ __forceinline__ float sum_bf16x8(const uint4& a) {
+  float s0 = 0.f, s1 = 0.f;
+  const uint32_t ones = 0x3F803F80u;
+  asm("v_dot2c_f32_bf16 %0, %2, %6\n\tv_dot2c_f32_bf16 %1, %3, %6\n\tv_dot2c_f32_bf16 %0, %4, %6\n\tv_dot2c_f32_bf16 %1, %5, %6\n\t"
+      "s_nop 2"
+      : "+v"(s0), "+v"(s1)
+      : "v"(a.x), "v"(a.y), "v"(a.z), "v"(a.w), "v"(ones));
+  return s0 + s1;
+}
+
 // max of two that are never NaN (fmaxf wraps NaN-quieting moves around its operands)
 __device__ __forceinline__ float max2(float a, float b) {
   float r;

@@ -486,18 +486,16 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(3
         tmax = xor32_max(xor16_max(tmax));
         const float m_new = fmaxf(m, tmax);  // finite: every tile holds at least one valid token
         const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        float psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           s0[e] = __builtin_amdgcn_exp2f(s0[e] - m_new);
           s1[e] = __builtin_amdgcn_exp2f(s1[e] - m_new);
-          psum += s0[e] + s1[e];
         }
-        l = l * alpha + psum;
+        const uint4 pv = {pack_bf16x2(s0[0], s0[1]), pack_bf16x2(s0[2], s0[3]), pack_bf16x2(s1[0], s1[1]), pack_bf16x2(s1[2], s1[3])};
+        l = l * alpha + sum_bf16x8(pv);  // of the rounded probabilities, the ones the output MFMAs multiply by
         m = m_new;
 #pragma unroll
         for (int n = 0; n < 8; ++n) acc[n] *= alpha;
-        const uint4 pv = {pack_bf16x2(s0[0], s0[1]), pack_bf16x2(s0[2], s0[3]), pack_bf16x2(s1[0], s1[1]), pack_bf16x2(s1[2], s1[3])};
         const bf16x8 pop = as_bf16x8(pv);
 #pragma unroll
         for (int n = 0; n < 8; ++n) acc[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[n], pop, acc[n], 0, 0, 0);

@@ -229,21 +229,20 @@ __device__ __forceinline__ void decode_role(const StepParams& P, const DecodeIte
       tmax = xor32_max(tmax);
       const float m_new = fmaxf(m, tmax);  // finite: every tile holds at least one valid token
       const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-      float psum = 0.f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        s[e] = __builtin_amdgcn_exp2f(s[e] - m_new);
-        psum += s[e];
-      }
-      l = l * alpha + psum;
+      for (int e = 0; e < 16; ++e) s[e] = __builtin_amdgcn_exp2f(s[e] - m_new);
+      uint4 pv[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        pv[u] = make_uint4(pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
+                           pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7]));
+      l = l * alpha + sum_bf16x16(pv[0], pv[1]);  // of the rounded probabilities, the ones the output MFMAs multiply by
       m = m_new;
 #pragma unroll
       for (int n = 0; n < 4; ++n) acc[n] *= alpha;
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        uint4 pv = {pack_bf16x2(s[8 * u + 0], s[8 * u + 1]), pack_bf16x2(s[8 * u + 2], s[8 * u + 3]),
-                    pack_bf16x2(s[8 * u + 4], s[8 * u + 5]), pack_bf16x2(s[8 * u + 6], s[8 * u + 7])};
-        const bf16x8 pop = as_bf16x8(pv);
+        const bf16x8 pop = as_bf16x8(pv[u]);
 #pragma unroll
         for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u][n], pop, acc[n], 0, 0, 0);
       }
